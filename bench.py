@@ -1,0 +1,316 @@
+#!/usr/bin/env python3
+"""Benchmark of the MACKO sparse matrix-vector product on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--sweep] [--stack]
+
+Workload (default): the Llama2-7B-shaped linear layers at 50 % per-row
+unstructured sparsity (4 x 4096x4096, 2 x 11008x4096, 1 x 4096x11008), fp16
+N(0, 0.02) weights, fp16 N(0,1) activations, batch 1.  One "step" is one pass
+over one decoder layer's seven sparse products, back to back on one stream.
+Steps rotate over several copies of the layer at distinct addresses so that no
+step finds its matrices in the 256 MB last-level cache (the paper invalidates
+the cache before every run, Section 5.1).
+
+Prints ONE JSON line.  `value` is algorithmic bytes (format arrays + x + y, the
+compute-intensity accounting of Section 3.1) moved per second over the timed
+region; the same loop over the dense fp16 GEMV gives the speedup.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E bandwidth
+CACHE_BYTES = 256 << 20      # last-level (Infinity Cache) capacity to defeat
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def spmv_bytes(rep) -> int:
+    """values + deltas + row pointers + x once + y once."""
+    return rep.total_bytes + 2 * rep.cols + 2 * rep.rows
+
+
+def dense_bytes(rows, cols) -> int:
+    return 2 * rows * cols + 2 * cols + 2 * rows
+
+
+class SparseOp:
+    """One matrix bound to the device `copies` times at distinct addresses."""
+
+    def __init__(self, M, torch, case, copies):
+        self.name, self.rows, self.cols = case.name, case.rows, case.cols
+        first = M.encode(case.W).to_device()
+        self.report = first.report
+        self.handles = [first]
+        for _ in range(copies - 1):
+            bufs = [b.clone() for b in first.device_buffers()]
+            self.handles.append(M.wrap_device(case.rows, case.cols, self.report.pad_nnz, *bufs))
+        self.x = torch.from_numpy(case.x.view(np.float16)).cuda()
+        self.y = torch.empty(case.rows, dtype=torch.float16, device="cuda")
+        self.bytes = spmv_bytes(self.report)
+
+    def launch(self, copy, stream_ptr):
+        return self.handles[copy].spmv_raw(self.x.data_ptr(), self.y.data_ptr(), stream_ptr)
+
+
+class DenseOp:
+    def __init__(self, M, torch, case, copies):
+        self.name, self.rows, self.cols = case.name, case.rows, case.cols
+        W = torch.from_numpy(case.W.view(np.float16)).cuda()
+        self.W = [W] + [W.clone() for _ in range(copies - 1)]
+        self.x = torch.from_numpy(case.x.view(np.float16)).cuda()
+        self.y = torch.empty(case.rows, dtype=torch.float16, device="cuda")
+        self.bytes = dense_bytes(case.rows, case.cols)
+        self._fn = M.load_library().macko_dense_gemv
+
+    def launch(self, copy, stream_ptr):
+        W = self.W[copy]
+        return self._fn(W.data_ptr(), self.rows, self.cols, W.stride(0), self.x.data_ptr(),
+                        self.y.data_ptr(), stream_ptr)
+
+
+def time_region(torch, fn, n_warm, n_timed):
+    """fn(i) enqueues iteration i on torch's current stream.  Returns seconds for
+    the n_timed iterations, measured with HIP events on that stream."""
+    for i in range(n_warm):
+        fn(i)
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(n_timed):
+        fn(n_warm + i)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1e-3
+
+
+def time_single_op(torch, op, stream_ptr, n_warm, n_timed):
+    copies = len(op.handles) if hasattr(op, "handles") else len(op.W)
+
+    def fn(i):
+        st = op.launch(i % copies, stream_ptr)
+        if st != 0:
+            raise RuntimeError(f"launch failed with status {st}")
+    return time_region(torch, fn, n_warm, n_timed) / n_timed
+
+
+def copies_for(nbytes, total=2 << 30):
+    """Enough copies that consecutive uses of one copy are separated by more than
+    the last-level cache, within a bounded footprint."""
+    return max(2, min(64, -(-total // max(nbytes, 1))))
+
+
+def cpu_baseline(oracle, cases, min_cpu_seconds=10.0):
+    """The oracle's SpMV (fp64, from the format buffers) timed on the host."""
+    encs = [(oracle.encode(c.W), c.x) for c in cases]
+    threads = oracle.max_threads()
+    nbytes = sum(e.total_bytes + 2 * e.cols + 2 * e.rows for e, _ in encs)
+    for e, x in encs:          # warm-up
+        oracle.spmv(e, x)
+    passes, t0 = 0, time.perf_counter()
+    best = float("inf")
+    while True:
+        t1 = time.perf_counter()
+        for e, x in encs:
+            oracle.spmv(e, x)
+        best = min(best, time.perf_counter() - t1)
+        passes += 1
+        if (time.perf_counter() - t0) * threads >= min_cpu_seconds or passes >= 50:
+            break
+    return {
+        "value": nbytes / best / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": f"one pass over the {len(encs)} distinct layer matrices "
+                  f"({nbytes / 1e6:.1f} MB of format+x+y), best of {passes} passes, OpenMP over rows",
+        "us_per_pass": best * 1e6,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--sweep", action="store_true", help="also time the 36864x12288 sparsity sweep")
+    ap.add_argument("--stack", action="store_true", help="also time the Llama2-13B-shaped 32-layer stack")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
+
+    import torch
+    import oracle
+    import workloads as wl
+    import paper_2511_13061_amd as M
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    M.load_library()
+    torch.cuda.set_device(0)
+    stream_ptr = int(torch.cuda.current_stream().cuda_stream)
+    props = torch.cuda.get_device_properties(0)
+    log(f"device: {props.name}, {props.multi_processor_count} CUs, {props.total_memory / 2**30:.0f} GiB")
+
+    # ---- workload: one Llama2-7B-shaped layer at 50 % ------------------------
+    t0 = time.perf_counter()
+    cases = list(wl.config2())
+    layer_plan = [("qkvo", 4), ("gate_up", 2), ("down", 1)]
+    layer_macko_bytes = 0
+    n_layers = 8
+    sparse_ops, dense_ops = {}, {}
+    for case, (tag, mult) in zip(cases, layer_plan):
+        sparse_ops[tag] = SparseOp(M, torch, case, copies=mult * n_layers)
+        dense_ops[tag] = DenseOp(M, torch, case, copies=mult * n_layers)
+        layer_macko_bytes += mult * sparse_ops[tag].bytes
+    layer_dense_bytes = sum(mult * dense_ops[tag].bytes for tag, mult in layer_plan)
+    launches_per_step = sum(m for _, m in layer_plan)
+    log(f"setup {time.perf_counter() - t0:.1f}s: layer = {layer_macko_bytes / 1e6:.1f} MB MACKO, "
+        f"{layer_dense_bytes / 1e6:.1f} MB dense, {n_layers} copies")
+
+    def make_step(ops):
+        def step(i):
+            layer = i % n_layers
+            for tag, mult in layer_plan:
+                op = ops[tag]
+                for k in range(mult):
+                    st = op.launch(layer * mult + k, stream_ptr)
+                    if st != 0:
+                        raise RuntimeError(f"launch failed with status {st}")
+        return step
+
+    torch.cuda.synchronize()
+    t_sparse = time_region(torch, make_step(sparse_ops), args.warmup, args.steps)
+    t_dense = time_region(torch, make_step(dense_ops), args.warmup, args.steps)
+    ms_per_step = t_sparse / args.steps * 1e3
+    gbps = layer_macko_bytes / (t_sparse / args.steps) / 1e9
+    dense_gbps = layer_dense_bytes / (t_dense / args.steps) / 1e9
+    log(f"layer: MACKO {ms_per_step * 1e3:.1f} us/step ({gbps:.0f} GB/s), dense "
+        f"{t_dense / args.steps * 1e6:.1f} us/step ({dense_gbps:.0f} GB/s), speedup {t_dense / t_sparse:.3f}")
+
+    # ---- per-shape numbers (cold rotation over the same copies) ---------------
+    per_shape = {}
+    n_single = max(50, args.steps // 2)
+    for tag, _ in layer_plan:
+        so, do = sparse_ops[tag], dense_ops[tag]
+        ts = time_single_op(torch, so, stream_ptr, max(10, args.warmup // 2), n_single)
+        td = time_single_op(torch, do, stream_ptr, max(10, args.warmup // 2), n_single)
+        per_shape[f"{so.rows}x{so.cols}"] = {
+            "macko_us": round(ts * 1e6, 2), "dense_us": round(td * 1e6, 2),
+            "macko_GBps": round(so.bytes / ts / 1e9, 1), "dense_GBps": round(do.bytes / td / 1e9, 1),
+            "speedup_vs_dense": round(td / ts, 3),
+            "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
+            "effd": round(so.report.effd, 4), "padding_entries": so.report.padding_entries,
+        }
+        log(f"  {tag}: {per_shape[f'{so.rows}x{so.cols}']}")
+
+    # dominant kernel of the step: the wave-per-row SpMV kernel (all seven launches)
+    avg_launch_s = t_sparse / (args.steps * launches_per_step)
+    avg_launch_bytes = layer_macko_bytes / launches_per_step
+    roofline = {
+        "bound": "hbm", "kernel": "spmv_wave_row_kernel",
+        "achieved": round(avg_launch_bytes / avg_launch_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(avg_launch_bytes / avg_launch_s / 1e9 / HBM_PEAK_GBPS, 4),
+        "avg_launch_us": round(avg_launch_s * 1e6, 3), "bytes_per_launch": int(avg_launch_bytes),
+        "traffic": None,
+    }
+
+    extra = {}
+    del dense_ops
+    torch.cuda.empty_cache()
+
+    # ---- optional: sparsity sweep on 36864 x 12288 ---------------------------
+    if args.sweep:
+        sweep = {}
+        dense_t = None
+        for s in wl.SWEEP_SPARSITIES:
+            case = wl.config3(s)
+            so = SparseOp(M, torch, case, copies=2)
+            ts = time_single_op(torch, so, stream_ptr, 5, 40)
+            row = {"macko_us": round(ts * 1e6, 1), "macko_GBps": round(so.bytes / ts / 1e9, 1),
+                   "frac_of_peak": round(so.bytes / ts / 1e9 / HBM_PEAK_GBPS, 4),
+                   "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
+                   "effd": round(so.report.effd, 4), "padding_entries": so.report.padding_entries}
+            if s == 0:
+                do = DenseOp(M, torch, case, copies=2)
+                dense_t = time_single_op(torch, do, stream_ptr, 5, 40)
+                row["dense_us"] = round(dense_t * 1e6, 1)
+                row["dense_GBps"] = round(do.bytes / dense_t / 1e9, 1)
+                del do
+            row["speedup_vs_dense"] = round(dense_t / ts, 3)
+            sweep[str(s)] = row
+            log(f"  sweep {s}%: {row}")
+            del so, case
+            torch.cuda.empty_cache()
+        extra["sweep_36864x12288"] = sweep
+
+    # ---- optional: Llama2-13B-shaped 32-layer stack ---------------------------
+    if args.stack:
+        plan13 = [("qkvo", 4), ("gate_up", 2), ("down", 1)]
+        ops13 = {}
+        dops13 = {}
+        for case, (tag, mult) in zip(wl.config5_layer(), plan13):
+            ops13[tag] = SparseOp(M, torch, case, copies=mult * 32)
+            dops13[tag] = DenseOp(M, torch, case, copies=mult * 32)
+        def stack_pass(ops):
+            def run(_i):
+                for layer in range(32):
+                    for tag, mult in plan13:
+                        for k in range(mult):
+                            ops[tag].launch(layer * mult + k, stream_ptr)
+            return run
+        ts = time_region(torch, stack_pass(ops13), 2, 10) / 10
+        td = time_region(torch, stack_pass(dops13), 2, 10) / 10
+        sb = 32 * sum(m * ops13[t].bytes for t, m in plan13)
+        db = 32 * sum(m * dops13[t].bytes for t, m in plan13)
+        extra["stack_llama2_13b_32layers"] = {
+            "launches": 224, "macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
+            "macko_GB": round(sb / 1e9, 3), "dense_GB": round(db / 1e9, 3),
+            "macko_GBps": round(sb / ts / 1e9, 1), "dense_GBps": round(db / td / 1e9, 1),
+            "speedup_vs_dense": round(td / ts, 3),
+            "note": "one layer's three distinct matrices, device buffers replicated to 32 layers at distinct addresses",
+        }
+        log(f"  stack: {extra['stack_llama2_13b_32layers']}")
+        del ops13, dops13
+        torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(oracle, cases)
+        log(f"cpu oracle: {cpu}")
+
+    out = {
+        "metric": "achieved HBM GB/s of the MACKO SpMV (format + x + y bytes) at 50% sparsity, Llama2-7B-shaped layers",
+        "value": round(gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 in, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama2-7B-shaped layer set, 50% per-row unstructured sparsity, "
+                               "one step = 4x(4096x4096) + 2x(11008x4096) + 1x(4096x11008) SpMVs, batch 1",
+                   "layer_copies_rotated": n_layers, "launches_per_step": launches_per_step,
+                   "macko_bytes_per_step": layer_macko_bytes, "dense_bytes_per_step": layer_dense_bytes},
+        "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+        "us_per_spmv": round(ms_per_step * 1e3 / launches_per_step, 3),
+        "dense_gemv": {"ms_per_step": round(t_dense / args.steps * 1e3, 5), "GBps": round(dense_gbps, 1)},
+        "speedup_vs_dense_gemv": round(t_dense / t_sparse, 3),
+        "memory_reduction_vs_dense": round(layer_dense_bytes / layer_macko_bytes, 3),
+        "per_shape": per_shape,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    out.update(extra)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

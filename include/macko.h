@@ -1,0 +1,168 @@
+/*
+ * libmacko -- MACKO sparse matrix-vector product for AMD Instinct MI355X (gfx950).
+ *
+ * C ABI.  Implements the storage format of Section 4.1 of "MACKO: Sparse
+ * Matrix-Vector Multiplication for Low Sparsity" (arXiv 2511.13061) for
+ * b_val = 16 (fp16 values) and b_delta = 4 (4-bit delta-coded column
+ * coordinates), and the product Y = M V of its Appendix A / Section 4.4, plus
+ * the dense fp16 GEMV of Section 4.3 that the paper measures speedups against.
+ *
+ * Conventions
+ *   - Every function returns MACKO_OK (0) or a negative macko_status code; no
+ *     C++ exception crosses this boundary.  On failure output handles are set
+ *     to NULL and nothing is leaked.
+ *   - "host" pointers are ordinary CPU memory, "dev" pointers are HIP device
+ *     memory on the current device; `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).
+ *   - fp16 data is passed as raw IEEE binary16 bit patterns (uint16_t).
+ *   - Matrices are row-major; `ld` is the distance between rows in elements.
+ *   - The kernels only enqueue work on `stream` and never synchronise, unless
+ *     a function's comment says otherwise.
+ *
+ * Format layout (identical on host and device)
+ *   values   uint16_t[alloc_nnz]   fp16 bits; +0 at padding entries and in the tail
+ *   deltas   uint8_t [alloc_nnz/2] entry k is the 4-bit code (delta-1) in byte k>>1,
+ *                                  bits 4*(k&1) .. 4*(k&1)+3
+ *   row_ptr  uint32_t[rows+1]      index of each row's first entry
+ *   The delta of a row's first entry is its column + 1; a gap larger than 16 is
+ *   bridged by zero-valued entries with delta 16 placed greedily.  An element
+ *   is a zero iff its bits are +0 or -0.  alloc_nnz = pad_nnz rounded up to 32
+ *   (both arrays are multiples of 16 bytes, Section 4.5).
+ */
+#ifndef MACKO_H_
+#define MACKO_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MACKO_API __attribute__((visibility("default")))
+
+typedef enum macko_status {
+  MACKO_OK = 0,
+  MACKO_E_INVALID_ARG = -1,   /* NULL pointer, negative size, ld < cols, misaligned buffer */
+  MACKO_E_OVERFLOW = -2,      /* alloc_nnz >= 2^32: does not fit the 32-bit row pointers    */
+  MACKO_E_UNSUPPORTED = -3,   /* shape or option this build has no kernel for               */
+  MACKO_E_OUT_OF_MEMORY = -4, /* host or device allocation failed                           */
+  MACKO_E_NOT_BOUND = -5,     /* device operation on a handle that has no device buffers    */
+  MACKO_E_HIP = -6            /* a HIP call failed; see macko_last_hip_error()              */
+} macko_status;
+
+/* Opaque encoded matrix.  Created by the encode / wrap calls, released by
+ * macko_destroy.  Immutable once bound, so concurrent macko_spmv calls on
+ * different streams are allowed. */
+typedef struct macko_matrix* macko_handle_t;
+
+/* Storage / padding report (Section 3.1 eq. 2, Section 4.2 eqs. 8-10). */
+typedef struct macko_report {
+  int64_t rows, cols;
+  int64_t nnz;              /* non-zero elements of the dense input                    */
+  int64_t pad_nnz;          /* stored entries = nnz + padding_entries                  */
+  int64_t alloc_nnz;        /* pad_nnz rounded up to 32 (array tail padding)           */
+  int64_t padding_entries;  /* zero entries inserted to keep every delta <= 16         */
+  int64_t empty_rows;
+  int64_t max_row_entries;  /* longest row, in stored entries                          */
+  int64_t values_bytes, deltas_bytes, rowptr_bytes, total_bytes, dense_bytes;
+  double density;           /* d = nnz / (rows*cols)                                   */
+  double effd;              /* total_bytes / dense_bytes (eq. 2, row pointers included) */
+  double effd_best;         /* eq. 8  at this d                                        */
+  double effd_expected;     /* eq. 10 at this d                                        */
+  double effd_worst;        /* eq. 9  at this d                                        */
+  int32_t b_val, b_delta;   /* 16, 4                                                   */
+} macko_report_t;
+
+/* ---- encoding (Section 4.1) ---------------------------------------------- */
+
+/* Encode a dense fp16 matrix held in host memory.  The new handle owns host
+ * copies of the three arrays; it has no device buffers until macko_bind_device.
+ * `report` may be NULL.  rows == 0 or cols == 0 is valid. */
+MACKO_API int macko_encode(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
+                           macko_handle_t* out, macko_report_t* report);
+
+/* Encode a dense fp16 matrix held in device memory, on the GPU.  The library
+ * allocates the device buffers (hipMalloc) and the handle owns them; the handle
+ * is bound on return and keeps no host copy.  Synchronises `stream` (the sizes
+ * of the outputs are only known after a counting pass).  The result is
+ * bit-identical to macko_encode on the same input. */
+MACKO_API int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld,
+                                  void* stream, macko_handle_t* out, macko_report_t* report);
+
+/* Adopt device buffers that already hold an encoding (a copy made by the
+ * caller, a loaded checkpoint).  The caller keeps ownership of the buffers and
+ * must keep them alive while the handle is used.  values_dev and deltas_dev
+ * must be 16-byte aligned, rowptr_dev 4-byte aligned; pad_nnz must equal
+ * row_ptr[rows].  The contents are trusted, not validated. */
+MACKO_API int macko_wrap_device(int64_t rows, int64_t cols, int64_t pad_nnz, const void* values_dev,
+                                const void* deltas_dev, const void* rowptr_dev, macko_handle_t* out);
+
+/* Copy of the report computed at encode time (for wrapped handles only the
+ * size fields are known; nnz-derived fields are -1 / NaN). */
+MACKO_API int macko_get_report(macko_handle_t h, macko_report_t* report);
+
+/* Bytes the caller must provide to macko_bind_device for each array. */
+MACKO_API int macko_device_bytes(macko_handle_t h, int64_t* values_bytes, int64_t* deltas_bytes,
+                                 int64_t* rowptr_bytes);
+
+/* Attach caller-owned device buffers (each at least as large as reported by
+ * macko_device_bytes; values_dev and deltas_dev 16-byte aligned) and enqueue
+ * the host-to-device copies of the encoding on `stream`.  The host arrays of
+ * the handle must stay alive until those copies complete (they do: the handle
+ * owns them).  The buffers must outlive the handle's use. */
+MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas_dev,
+                                void* rowptr_dev, void* stream);
+
+/* Borrowed pointers to the host arrays (valid until macko_destroy); any output
+ * pointer may be NULL.  MACKO_E_UNSUPPORTED for handles without host copies. */
+MACKO_API int macko_host_buffers(macko_handle_t h, const uint16_t** values, const uint8_t** deltas,
+                                 const uint32_t** row_ptr);
+
+/* Copy the bound device arrays back into caller-provided host memory of the
+ * sizes reported by macko_device_bytes.  Synchronous. */
+MACKO_API int macko_fetch_device(macko_handle_t h, uint16_t* values_host, uint8_t* deltas_host,
+                                 uint32_t* rowptr_host);
+
+/* Decode the host copy back to a dense rows x cols fp16 matrix (the format is
+ * lossless; -0 inputs come back as +0). */
+MACKO_API int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld);
+
+/* ---- the product (Section 4.4; Y = M V of Appendix A) --------------------- */
+
+/* y[r] = sum_k values[k] * x[column(k)] over row r's entries, fp32
+ * accumulation, result rounded to fp16 (round to nearest even).
+ * x_dev: fp16[cols], y_dev: fp16[rows], both on the device, 2-byte aligned
+ * (16-byte aligned x takes the fast staging path); they must not alias each
+ * other or the format arrays.  y is overwritten.  Enqueues one kernel. */
+MACKO_API int macko_spmv(macko_handle_t h, const void* x_dev, void* y_dev, void* stream);
+
+/* Dense fp16 GEMV y = W x with fp32 accumulation (SplitK over lanes of a
+ * wavefront, Section 4.3): the baseline the sparse product is compared with.
+ * W_dev: fp16, rows x cols, row-major with leading dimension ld. */
+MACKO_API int macko_dense_gemv(const void* W_dev, int64_t rows, int64_t cols, int64_t ld,
+                               const void* x_dev, void* y_dev, void* stream);
+
+/* ---- housekeeping ---------------------------------------------------------- */
+
+MACKO_API void macko_destroy(macko_handle_t h);
+
+MACKO_API const char* macko_status_string(int status);
+
+/* hipError_t of the most recent failing HIP call on this thread (0 if none). */
+MACKO_API int macko_last_hip_error(void);
+
+/* Launch-shape knobs for experiments; every value has a safe default and out
+ * of range values are rejected with MACKO_E_INVALID_ARG.
+ *   "spmv_kernel"       0 auto, 1 generic sub-wave kernel, 2 wave-per-row kernel
+ *   "spmv_lanes"        0 auto, else lanes per row for the generic kernel (16/32/64)
+ *   "spmv_block"        threads per workgroup for spmv (multiple of 64, <= 1024), 0 auto
+ *   "spmv_rows_per_wg"  rows handled by one workgroup, 0 auto
+ *   "gemv_block", "gemv_rows_per_wg"  the same for the dense GEMV
+ * Settings are process wide and not thread safe. */
+MACKO_API int macko_set_tuning(const char* name, int64_t value);
+MACKO_API int macko_get_tuning(const char* name, int64_t* value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MACKO_H_ */

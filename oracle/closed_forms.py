@@ -36,7 +36,7 @@ def effd_macko_worst(d: float, b_val: int = 16, b_delta: int = 4) -> float:
 def padding_per_nonzero_expected(d: float, b_delta: int = 4) -> float:
     """z / (1 - z) with z = (1-d)^(2^b_delta): expected padding entries per
     non-zero under an iid Bernoulli(d) mask (text before eq. 10)."""
-    if d >= 1.0:
+    if d >= 1.0 or d <= 0.0:      # no zeros to bridge / no non-zeros to bridge to
         return 0.0
     z = (1.0 - d) ** (2 ** b_delta)
     return z / (1.0 - z)

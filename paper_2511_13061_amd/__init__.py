@@ -1,0 +1,20 @@
+"""MACKO sparse matrix-vector product for AMD Instinct MI355X (gfx950).
+
+Thin ctypes binding over ``libmacko.so`` (see ``include/macko.h``).  Every
+arithmetic step runs inside the library's HIP kernels; this package only
+marshals arguments.  PyTorch supplies device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    MackoError,
+    MackoMatrix,
+    Report,
+    dense_gemv,
+    encode,
+    encode_device,
+    get_tuning,
+    library_path,
+    load_library,
+    set_tuning,
+    status_string,
+    wrap_device,
+)

@@ -1,0 +1,303 @@
+"""ctypes binding for libmacko.so: same names as the C ABI, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmacko.so")
+_lib = None
+
+EXPORTED_SYMBOLS = [
+    "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_get_report",
+    "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
+    "macko_decode", "macko_spmv", "macko_dense_gemv", "macko_destroy", "macko_status_string",
+    "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
+]
+
+
+class MackoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = status_string(status)
+        if status == -6:
+            msg += f" (hipError {load_library().macko_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+class _CReport(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in (
+        "rows", "cols", "nnz", "pad_nnz", "alloc_nnz", "padding_entries", "empty_rows",
+        "max_row_entries", "values_bytes", "deltas_bytes", "rowptr_bytes", "total_bytes",
+        "dense_bytes")] + [(n, ctypes.c_double) for n in (
+            "density", "effd", "effd_best", "effd_expected", "effd_worst")] + [
+        ("b_val", ctypes.c_int32), ("b_delta", ctypes.c_int32)]
+
+
+@dataclass
+class Report:
+    rows: int
+    cols: int
+    nnz: int
+    pad_nnz: int
+    alloc_nnz: int
+    padding_entries: int
+    empty_rows: int
+    max_row_entries: int
+    values_bytes: int
+    deltas_bytes: int
+    rowptr_bytes: int
+    total_bytes: int
+    dense_bytes: int
+    density: float
+    effd: float
+    effd_best: float
+    effd_expected: float
+    effd_worst: float
+    b_val: int
+    b_delta: int
+
+    @classmethod
+    def _from_c(cls, c: _CReport) -> "Report":
+        return cls(**{name: getattr(c, name) for name, _ in _CReport._fields_})
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libmacko.so.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2511_13061_amd.build` "
+            "(or __graft_entry__.build()); there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    i64p = ctypes.POINTER(i64)
+    rp = ctypes.POINTER(_CReport)
+    hp = ctypes.POINTER(vp)
+    lib.macko_encode.argtypes = [vp, i64, i64, i64, hp, rp]
+    lib.macko_encode_device.argtypes = [vp, i64, i64, i64, vp, hp, rp]
+    lib.macko_wrap_device.argtypes = [i64, i64, i64, vp, vp, vp, hp]
+    lib.macko_get_report.argtypes = [vp, rp]
+    lib.macko_device_bytes.argtypes = [vp, i64p, i64p, i64p]
+    lib.macko_bind_device.argtypes = [vp, vp, vp, vp, vp]
+    lib.macko_host_buffers.argtypes = [vp, hp, hp, hp]
+    lib.macko_fetch_device.argtypes = [vp, vp, vp, vp]
+    lib.macko_decode.argtypes = [vp, vp, i64]
+    lib.macko_spmv.argtypes = [vp, vp, vp, vp]
+    lib.macko_dense_gemv.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    lib.macko_destroy.argtypes = [vp]
+    lib.macko_destroy.restype = None
+    lib.macko_status_string.argtypes = [ci]
+    lib.macko_status_string.restype = ctypes.c_char_p
+    lib.macko_last_hip_error.argtypes = []
+    lib.macko_set_tuning.argtypes = [ctypes.c_char_p, i64]
+    lib.macko_get_tuning.argtypes = [ctypes.c_char_p, i64p]
+    for name in EXPORTED_SYMBOLS:
+        fn = getattr(lib, name)
+        if name not in ("macko_destroy", "macko_status_string"):
+            fn.restype = ci
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().macko_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise MackoError(status, where)
+
+
+def set_tuning(name: str, value: int) -> None:
+    _check(load_library().macko_set_tuning(name.encode(), int(value)), f"macko_set_tuning({name})")
+
+
+def get_tuning(name: str) -> int:
+    v = ctypes.c_int64(0)
+    _check(load_library().macko_get_tuning(name.encode(), ctypes.byref(v)), f"macko_get_tuning({name})")
+    return int(v.value)
+
+
+def _host_u16_matrix(dense) -> np.ndarray:
+    a = np.asarray(dense)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16 or a.ndim != 2:
+        raise TypeError("dense must be a 2-D float16 / uint16 array")
+    if a.size and (a.strides[1] != 2 or a.strides[0] % 2 != 0 or a.strides[0] < 2 * a.shape[1]):
+        a = np.ascontiguousarray(a)
+    return a
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return stream
+    return int(stream.cuda_stream)
+
+
+def _dev_ptr(t) -> int:
+    return int(t.data_ptr())
+
+
+class MackoMatrix:
+    """Owner of a macko_handle_t (and of the torch tensors bound to it)."""
+
+    def __init__(self, handle: int, report: Optional[Report]):
+        self._h = ctypes.c_void_p(handle)
+        self.report = report
+        self._keep = []          # torch tensors that back the device arrays
+
+    # -- lifetime ---------------------------------------------------------
+    def destroy(self) -> None:
+        if self._h:
+            load_library().macko_destroy(self._h)
+            self._h = ctypes.c_void_p(None)
+            self._keep = []
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    @property
+    def rows(self) -> int:
+        return self.get_report().rows
+
+    @property
+    def cols(self) -> int:
+        return self.get_report().cols
+
+    # -- C ABI calls ------------------------------------------------------
+    def get_report(self) -> Report:
+        c = _CReport()
+        _check(load_library().macko_get_report(self._h, ctypes.byref(c)), "macko_get_report")
+        return Report._from_c(c)
+
+    def device_bytes(self):
+        a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        _check(load_library().macko_device_bytes(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
+               "macko_device_bytes")
+        return int(a.value), int(b.value), int(c.value)
+
+    def bind_device(self, values_dev, deltas_dev, rowptr_dev, stream=None) -> None:
+        """values_dev / deltas_dev / rowptr_dev: torch uint8 CUDA tensors of at
+        least device_bytes() bytes."""
+        _check(load_library().macko_bind_device(self._h, _dev_ptr(values_dev), _dev_ptr(deltas_dev),
+                                                _dev_ptr(rowptr_dev), _stream_ptr(stream)),
+               "macko_bind_device")
+        self._keep = [values_dev, deltas_dev, rowptr_dev]
+
+    def to_device(self, device="cuda", stream=None) -> "MackoMatrix":
+        """Allocate torch device memory for the three arrays and bind it."""
+        import torch
+        vb, db, rb = self.device_bytes()
+        bufs = [torch.empty(max(n, 16), dtype=torch.uint8, device=device) for n in (vb, db, rb)]
+        self.bind_device(*bufs, stream=stream)
+        return self
+
+    def device_buffers(self):
+        return list(self._keep)
+
+    def host_buffers(self):
+        """Copies of the host arrays as numpy (values u16, deltas u8, row_ptr u32)."""
+        v, d, r = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        _check(load_library().macko_host_buffers(self._h, ctypes.byref(v), ctypes.byref(d), ctypes.byref(r)),
+               "macko_host_buffers")
+        rep = self.get_report()
+        def grab(ptr, nbytes, dtype):
+            if nbytes == 0:
+                return np.zeros(0, dtype=dtype)
+            raw = (ctypes.c_uint8 * nbytes).from_address(ptr.value)
+            return np.frombuffer(raw, dtype=dtype).copy()
+        return (grab(v, rep.values_bytes, np.uint16), grab(d, rep.deltas_bytes, np.uint8),
+                grab(r, rep.rowptr_bytes, np.uint32))
+
+    def fetch_device(self):
+        """Device arrays copied back to numpy (values u16, deltas u8, row_ptr u32)."""
+        vb, db, rb = self.device_bytes()
+        v = np.zeros(vb // 2, dtype=np.uint16)
+        d = np.zeros(db, dtype=np.uint8)
+        r = np.zeros(rb // 4, dtype=np.uint32)
+        _check(load_library().macko_fetch_device(self._h, v.ctypes.data, d.ctypes.data, r.ctypes.data),
+               "macko_fetch_device")
+        return v, d, r
+
+    def decode(self) -> np.ndarray:
+        rep = self.get_report()
+        out = np.empty((rep.rows, rep.cols), dtype=np.uint16)
+        _check(load_library().macko_decode(self._h, out.ctypes.data, rep.cols), "macko_decode")
+        return out
+
+    def spmv(self, x_dev, y_dev=None, stream=None):
+        """y = W x.  x_dev: torch float16 CUDA tensor [cols]; returns y_dev [rows]."""
+        import torch
+        if y_dev is None:
+            y_dev = torch.empty(self.rows, dtype=torch.float16, device=x_dev.device)
+        _check(load_library().macko_spmv(self._h, _dev_ptr(x_dev), _dev_ptr(y_dev), _stream_ptr(stream)),
+               "macko_spmv")
+        return y_dev
+
+    def spmv_raw(self, x_ptr: int, y_ptr: int, stream_ptr: int) -> int:
+        """Unchecked call for timing loops; returns the status."""
+        return load_library().macko_spmv(self._h, x_ptr, y_ptr, stream_ptr)
+
+
+def encode(dense) -> MackoMatrix:
+    """macko_encode on a host fp16 matrix (numpy float16 or uint16 bits)."""
+    a = _host_u16_matrix(dense)
+    h = ctypes.c_void_p()
+    rep = _CReport()
+    ld = a.strides[0] // 2 if a.size else a.shape[1]      # numpy reports zero strides for empty arrays
+    _check(load_library().macko_encode(a.ctypes.data, a.shape[0], a.shape[1], ld,
+                                       ctypes.byref(h), ctypes.byref(rep)), "macko_encode")
+    return MackoMatrix(h.value, Report._from_c(rep))
+
+
+def encode_device(dense_dev, stream=None) -> MackoMatrix:
+    """macko_encode_device on a torch float16 CUDA matrix (row-major)."""
+    if dense_dev.dim() != 2 or dense_dev.stride(1) != 1:
+        raise ValueError("dense_dev must be a row-major 2-D tensor")
+    h = ctypes.c_void_p()
+    rep = _CReport()
+    _check(load_library().macko_encode_device(_dev_ptr(dense_dev), dense_dev.shape[0], dense_dev.shape[1],
+                                              dense_dev.stride(0), _stream_ptr(stream), ctypes.byref(h),
+                                              ctypes.byref(rep)), "macko_encode_device")
+    return MackoMatrix(h.value, Report._from_c(rep))
+
+
+def wrap_device(rows: int, cols: int, pad_nnz: int, values_dev, deltas_dev, rowptr_dev) -> MackoMatrix:
+    """macko_wrap_device: adopt device arrays that already hold an encoding."""
+    h = ctypes.c_void_p()
+    _check(load_library().macko_wrap_device(rows, cols, pad_nnz, _dev_ptr(values_dev), _dev_ptr(deltas_dev),
+                                            _dev_ptr(rowptr_dev), ctypes.byref(h)), "macko_wrap_device")
+    m = MackoMatrix(h.value, None)
+    m._keep = [values_dev, deltas_dev, rowptr_dev]
+    return m
+
+
+def dense_gemv(W_dev, x_dev, y_dev=None, stream=None):
+    """macko_dense_gemv: y = W x for a row-major fp16 CUDA matrix."""
+    import torch
+    if W_dev.dim() != 2 or W_dev.stride(1) != 1:
+        raise ValueError("W_dev must be a row-major 2-D tensor")
+    if y_dev is None:
+        y_dev = torch.empty(W_dev.shape[0], dtype=torch.float16, device=W_dev.device)
+    _check(load_library().macko_dense_gemv(_dev_ptr(W_dev), W_dev.shape[0], W_dev.shape[1], W_dev.stride(0),
+                                           _dev_ptr(x_dev), _dev_ptr(y_dev), _stream_ptr(stream)),
+           "macko_dense_gemv")
+    return y_dev

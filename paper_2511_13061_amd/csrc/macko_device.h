@@ -1,0 +1,104 @@
+// Device-side helpers shared by the gfx950 kernels: wave64 cross-lane
+// primitives on DPP, and staging of the activation vector into LDS.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace macko {
+
+constexpr int kWave = 64;
+
+// The activation vector x sits in LDS between two zero-filled guard regions:
+//   [0, kFrontPad) zeros | x[0 .. C) | zeros up to the end of the allocation.
+// Entries that a lane loads but that belong to a neighbouring row decode to
+// positions just before column 0 or after the row's last column; the guards
+// make those reads return +0 so that they contribute nothing.
+constexpr int kFrontPad = 2048;  // bytes
+constexpr int kBackPad = 2048;   // bytes
+
+__host__ __device__ inline int64_t lds_bytes_for(int64_t cols) {
+  return kFrontPad + 16 * ((cols + 7) / 8) + kBackPad;
+}
+
+// ---- DPP cross-lane primitives (wave64, GCN DPP controls) --------------------
+// row_shr:n shifts within a row of 16 lanes; row_bcast:15 / row_bcast:31 carry a
+// row's (half-wave's) last lane into the following rows.  Lanes without a source
+// keep `old` (= the additive identity).
+
+// One DPP step "v += lanes shifted by ctrl", emitted as a single VALU
+// instruction.  The leading s_nop covers the two wait states a DPP read needs
+// after a VALU write of the same register.  bound_ctrl:0 makes lanes without a
+// source read 0; rows excluded by row_mask keep their value (dst is tied to v).
+#define MACKO_DPP_ADD(op, v, ctrl, rmask)                                                     \
+  asm volatile("s_nop 1\n\t" op " %0, %0, %0 " ctrl " row_mask:" rmask " bank_mask:0xf bound_ctrl:0" \
+               : "+v"(v))
+
+// Inclusive prefix sum over the 64 lanes (Alg. 1 of the paper computes the same
+// quantity with five shuffle levels on 32 lanes; a wavefront needs six).
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+  MACKO_DPP_ADD("v_add_u32_dpp", v, "row_shr:1", "0xf");
+  MACKO_DPP_ADD("v_add_u32_dpp", v, "row_shr:2", "0xf");
+  MACKO_DPP_ADD("v_add_u32_dpp", v, "row_shr:4", "0xf");
+  MACKO_DPP_ADD("v_add_u32_dpp", v, "row_shr:8", "0xf");
+  MACKO_DPP_ADD("v_add_u32_dpp", v, "row_bcast:15", "0xa");
+  MACKO_DPP_ADD("v_add_u32_dpp", v, "row_bcast:31", "0xc");
+  return v;
+}
+
+// Sum over the 64 lanes; the total ends up in lane 63 (other lanes hold prefixes).
+__device__ __forceinline__ float wave_sum_to_last_lane(float v) {
+  MACKO_DPP_ADD("v_add_f32_dpp", v, "row_shr:1", "0xf");
+  MACKO_DPP_ADD("v_add_f32_dpp", v, "row_shr:2", "0xf");
+  MACKO_DPP_ADD("v_add_f32_dpp", v, "row_shr:4", "0xf");
+  MACKO_DPP_ADD("v_add_f32_dpp", v, "row_shr:8", "0xf");
+  MACKO_DPP_ADD("v_add_f32_dpp", v, "row_bcast:15", "0xa");
+  MACKO_DPP_ADD("v_add_f32_dpp", v, "row_bcast:31", "0xc");
+  return v;
+}
+
+// (a << sh) + b in one full-rate VALU instruction.  Written as asm so that the
+// compiler does not fuse chains of these into a quarter-rate 32-bit multiply.
+template <int SH>
+__device__ __forceinline__ uint32_t lshl_add(uint32_t a, uint32_t b) {
+  uint32_t r;
+  asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "n"(SH), "v"(b));
+  return r;
+}
+
+// fp32 -> fp16 bits, round to nearest even (v_cvt_f16_f32 under the default mode)
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
+  _Float16 h = (_Float16)f;
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
+  return (float)__builtin_bit_cast(_Float16, b);
+}
+
+// Copy x (fp16[cols], global) into the LDS layout described above.  Must be
+// called by every thread of the workgroup; ends with a barrier.
+__device__ __forceinline__ void stage_x_to_lds(unsigned char* lds, const uint16_t* __restrict__ x,
+                                               int cols, int lds_bytes) {
+  const int tid = threadIdx.x;
+  const int nt = blockDim.x;
+  const uint4 zero = make_uint4(0, 0, 0, 0);
+  uint4* lds16 = reinterpret_cast<uint4*>(lds);
+  for (int i = tid; i < kFrontPad / 16; i += nt) lds16[i] = zero;
+  const int chunks = cols >> 3;                       // whole 16-byte chunks of x
+  const int tail_chunks = (cols + 7) >> 3;            // chunks touched by x
+  for (int i = kFrontPad / 16 + tail_chunks + tid; i < lds_bytes / 16; i += nt) lds16[i] = zero;
+  uint16_t* xs = reinterpret_cast<uint16_t*>(lds + kFrontPad);
+  if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
+    const uint4* xg = reinterpret_cast<const uint4*>(x);
+    uint4* xd = reinterpret_cast<uint4*>(xs);
+    for (int i = tid; i < chunks; i += nt) xd[i] = xg[i];
+    for (int i = chunks * 8 + tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
+  } else {
+    for (int i = tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
+  }
+  __syncthreads();
+}
+
+}  // namespace macko

@@ -1,0 +1,164 @@
+// Dense fp16 GEMV y = W x for gfx950: the SplitK scheme of Section 4.3 of the
+// paper (lanes of one wavefront split a row's dot product, a cross-lane sum
+// finishes it), with 64-lane wavefronts, 16-byte loads per lane, x staged in
+// LDS and fp32 accumulation.  This is the baseline the sparse product is
+// compared with.
+#include "macko_device.h"
+#include "macko_internal.h"
+
+namespace macko {
+namespace {
+
+// Fast path: cols and ld multiples of 8, W 16-byte aligned.  One wavefront per
+// row; per step a lane multiplies 8 consecutive weights with 8 consecutive x.
+// A wavefront owns a contiguous share of the workgroup's rows and treats them as
+// one stream of (row, step) items: loads run RING items ahead of the arithmetic
+// and cross row boundaries, every item issues exactly one load, and the results
+// of up to 64 rows are collected in a register and stored with one coalesced
+// store.
+template <int RING>
+__global__ void __launch_bounds__(1024)
+gemv_wave_row_kernel(const uint4* __restrict__ W, const uint16_t* __restrict__ x,
+                     uint16_t* __restrict__ y, int rows, int cols, int64_t ld8, int rows_per_wg,
+                     int lds_bytes) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int row_begin = blockIdx.x * rows_per_wg;
+  const int row_end = min(rows, row_begin + rows_per_wg);
+  const int nwaves = blockDim.x >> 6;
+  stage_x_to_lds(lds, x, cols, lds_bytes);
+  const uint4* xs = reinterpret_cast<const uint4*>(lds + kFrontPad);
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c8 = cols >> 3;                            // 16-byte chunks per row
+  const int nsteps = (c8 + 63) >> 6;
+  const bool ragged = (c8 & 63) != 0;                  // last step only partly inside the row
+  const int per_wave = (row_end - row_begin + nwaves - 1) / nwaves;
+  const int wrow_begin = min(row_end, row_begin + wave * per_wave);
+  const int wrow_end = min(row_end, wrow_begin + per_wave);
+
+  for (int blk = wrow_begin; blk < wrow_end; blk += 64) {
+    const int nb = min(64, wrow_end - blk);
+    float yv = 0.0f;                                   // lane i: result of row blk + i
+    int ld_i = 0, ld_step = 0;                         // load side
+    int cp_i = 0, cp_step = 0;                         // compute side
+    const uint4* src = W + (int64_t)blk * ld8;         // row the next load reads from
+    const uint4* src_next = src;
+    int chunk = min(lane, c8 - 1);
+    uint4 q[RING];
+    auto issue = [&](int j) {
+      src = src_next;
+      if (ld_i < nb) {
+        chunk = min(ld_step * 64 + lane, c8 - 1);
+        if (++ld_step == nsteps) {
+          ld_step = 0;
+          if (++ld_i < nb) src_next = src + ld8;
+        }
+      }
+      q[j] = src[chunk];                               // padding items re-read the previous address
+    };
+#pragma unroll
+    for (int j = 0; j < RING; ++j) issue(j);
+
+    float acc = 0.0f;
+    while (cp_i < nb) {
+#pragma unroll
+      for (int j = 0; j < RING; ++j) {
+        uint4 w = q[j];
+        const bool live = cp_i < nb;
+        const int idx = cp_step * 64 + lane;
+        if (!live || (ragged && cp_step == nsteps - 1)) {
+          const bool in = live && idx < c8;
+          w.x = in ? w.x : 0u;
+          w.y = in ? w.y : 0u;
+          w.z = in ? w.z : 0u;
+          w.w = in ? w.w : 0u;
+        }
+        const uint4 xv = xs[idx];                      // chunks past the row end read the zero guard
+#define MACKO_LO(u) f16_bits_to_f32((uint16_t)((u) & 0xFFFFu))
+#define MACKO_HI(u) f16_bits_to_f32((uint16_t)((u) >> 16))
+        acc = fmaf(MACKO_LO(w.x), MACKO_LO(xv.x), acc);
+        acc = fmaf(MACKO_HI(w.x), MACKO_HI(xv.x), acc);
+        acc = fmaf(MACKO_LO(w.y), MACKO_LO(xv.y), acc);
+        acc = fmaf(MACKO_HI(w.y), MACKO_HI(xv.y), acc);
+        acc = fmaf(MACKO_LO(w.z), MACKO_LO(xv.z), acc);
+        acc = fmaf(MACKO_HI(w.z), MACKO_HI(xv.z), acc);
+        acc = fmaf(MACKO_LO(w.w), MACKO_LO(xv.w), acc);
+        acc = fmaf(MACKO_HI(w.w), MACKO_HI(xv.w), acc);
+#undef MACKO_LO
+#undef MACKO_HI
+        issue(j);
+        if (live) {
+          if (++cp_step == nsteps) {
+            const float total = wave_sum_to_last_lane(acc);
+            const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), 63);
+            yv = lane == cp_i ? __builtin_bit_cast(float, tbits) : yv;
+            acc = 0.0f;
+            cp_step = 0;
+            ++cp_i;
+          }
+        } else {
+          cp_step = 0;
+        }
+      }
+    }
+    if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
+  }
+}
+
+// Any shape / alignment: one wavefront per row, 2-byte loads, x from global.
+__global__ void __launch_bounds__(256)
+gemv_generic_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__ x,
+                    uint16_t* __restrict__ y, int rows, int cols, int64_t ld) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int nwaves = blockDim.x >> 6;
+  for (int row = blockIdx.x * nwaves + wave; row < rows; row += gridDim.x * nwaves) {
+    const uint16_t* wr = W + (int64_t)row * ld;
+    float acc = 0.0f;
+    for (int c = lane; c < cols; c += 64) acc = fmaf(f16_bits_to_f32(wr[c]), f16_bits_to_f32(x[c]), acc);
+    acc = wave_sum_to_last_lane(acc);
+    if (lane == 63) y[row] = f32_to_f16_bits(acc);
+  }
+}
+
+}  // namespace
+
+int launch_dense_gemv(const void* W, int64_t rows, int64_t cols, int64_t ld, const void* x, void* y,
+                      hipStream_t stream) {
+  const Tuning& t = tuning();
+  const int cus = device_cu_count();
+  const int64_t lds_bytes = lds_bytes_for(cols);
+  const bool fast = cols > 0 && (cols % 8 == 0) && (ld % 8 == 0) &&
+                    (reinterpret_cast<uintptr_t>(W) & 15) == 0 && lds_bytes <= 160 * 1024 - 64;
+  const uint16_t* xp = static_cast<const uint16_t*>(x);
+  uint16_t* yp = static_cast<uint16_t*>(y);
+  if (fast) {
+    const int block = t.gemv_block ? (int)t.gemv_block : 512;
+    const int nwaves = block / 64;
+    int64_t rpw = t.gemv_rows_per_wg;
+    if (rpw == 0) {
+      const int64_t target_wgs = (int64_t)cus * 4;
+      rpw = std::max<int64_t>((rows + target_wgs - 1) / target_wgs, nwaves);
+    }
+    const int64_t grid = (rows + rpw - 1) / rpw;
+    auto kfn = gemv_wave_row_kernel<4>;
+    if (lds_bytes > 64 * 1024) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return hip_fail(e);
+    }
+    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds_bytes, stream,
+                       static_cast<const uint4*>(W), xp, yp, (int)rows, (int)cols, ld / 8, (int)rpw,
+                       (int)lds_bytes);
+  } else {
+    const int64_t grid = std::min<int64_t>((rows + 3) / 4, (int64_t)cus * 8);
+    hipLaunchKernelGGL(gemv_generic_kernel, dim3((unsigned)std::max<int64_t>(grid, 1)), dim3(256), 0,
+                       stream, static_cast<const uint16_t*>(W), xp, yp, (int)rows, (int)cols, ld);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  return MACKO_OK;
+}
+
+}  // namespace macko

@@ -1,0 +1,428 @@
+// Host side of libmacko: the C ABI, the handle, the host encoder / decoder and
+// the storage report.  The format is that of Section 4.1 with b_val = 16 and
+// b_delta = 4; see include/macko.h for the byte layout.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <string>
+#include <thread>
+
+#include "macko_internal.h"
+
+namespace macko {
+
+static thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  (void)hipGetLastError();  // clear the sticky error so later calls report their own
+  return MACKO_E_HIP;
+}
+
+Tuning& tuning() {
+  static Tuning t;
+  return t;
+}
+
+int device_cu_count() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
+// Storage report: eq. 2 for the measured effective density, eqs. 8-10 for the
+// best / worst / expected cases at the measured density.
+void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, int64_t pad_nnz,
+                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries) {
+  std::memset(rep, 0, sizeof(*rep));
+  rep->rows = rows;
+  rep->cols = cols;
+  rep->nnz = nnz;
+  rep->pad_nnz = pad_nnz;
+  rep->alloc_nnz = alloc_nnz;
+  rep->padding_entries = nnz >= 0 ? pad_nnz - nnz : -1;
+  rep->empty_rows = empty_rows;
+  rep->max_row_entries = max_row_entries;
+  rep->values_bytes = alloc_nnz * 2;
+  rep->deltas_bytes = alloc_nnz / 2;
+  rep->rowptr_bytes = 4 * (rows + 1);
+  rep->total_bytes = rep->values_bytes + rep->deltas_bytes + rep->rowptr_bytes;
+  rep->dense_bytes = 2 * rows * cols;
+  rep->b_val = 16;
+  rep->b_delta = kDeltaBits;
+  const double cells = static_cast<double>(rows) * static_cast<double>(cols);
+  const double nan = std::numeric_limits<double>::quiet_NaN();
+  rep->effd = cells > 0 ? static_cast<double>(rep->total_bytes) / (2.0 * cells) : 0.0;
+  if (nnz < 0 || cells <= 0) {
+    rep->density = rep->effd_best = rep->effd_expected = rep->effd_worst = cells > 0 ? nan : 0.0;
+    return;
+  }
+  const double d = static_cast<double>(nnz) / cells;
+  const double per_entry = (16.0 + kDeltaBits) / 16.0;
+  rep->density = d;
+  rep->effd_best = d * per_entry;
+  rep->effd_worst = (d + (1.0 - d) / kMaxDelta) * per_entry;
+  const double z = std::pow(1.0 - d, static_cast<double>(kMaxDelta));
+  rep->effd_expected = (d > 0.0 && d < 1.0) ? d * (1.0 + z / (1.0 - z)) * per_entry : d * per_entry;
+}
+
+namespace {
+
+inline bool is_nonzero(uint16_t bits) { return (bits & 0x7FFFu) != 0; }
+
+template <class F>
+void parallel_blocks(int64_t n, F&& body) {
+  unsigned hw = std::thread::hardware_concurrency();
+  int64_t nthreads = std::max<int64_t>(1, std::min<int64_t>(hw ? hw : 1, 32));
+  nthreads = std::min<int64_t>(nthreads, std::max<int64_t>(1, n / 64));
+  if (nthreads <= 1) {
+    body(0, n);
+    return;
+  }
+  std::vector<std::thread> pool;
+  int64_t chunk = (n + nthreads - 1) / nthreads;
+  for (int64_t t = 0; t < nthreads; ++t) {
+    int64_t lo = t * chunk, hi = std::min(n, lo + chunk);
+    if (lo >= hi) break;
+    pool.emplace_back([=, &body] { body(lo, hi); });
+  }
+  for (auto& th : pool) th.join();
+}
+
+// Stored entries of one row: a non-zero whose distance to the previously
+// stored column is g costs (g-1)/16 padding entries plus itself.
+inline void count_row(const uint16_t* row, int64_t cols, int64_t* entries, int64_t* nnz) {
+  int64_t prev = -1, e = 0, n = 0;
+  for (int64_t c = 0; c < cols; ++c) {
+    if (!is_nonzero(row[c])) continue;
+    e += 1 + ((c - prev - 1) >> kDeltaBits);
+    ++n;
+    prev = c;
+  }
+  *entries = e;
+  *nnz = n;
+}
+
+// Write one row's entries; codes go to a byte-per-entry scratch array that is
+// packed afterwards (two rows may share a byte of the packed array).
+inline void fill_row(const uint16_t* row, int64_t cols, uint16_t* values, uint8_t* codes) {
+  int64_t prev = -1, k = 0;
+  for (int64_t c = 0; c < cols; ++c) {
+    const uint16_t w = row[c];
+    if (!is_nonzero(w)) continue;
+    const int64_t g1 = c - prev - 1;          // gap - 1
+    for (int64_t p = g1 >> kDeltaBits; p > 0; --p) {
+      values[k] = 0;
+      codes[k] = kMaxDelta - 1;
+      ++k;
+    }
+    values[k] = w;
+    codes[k] = static_cast<uint8_t>(g1 & (kMaxDelta - 1));
+    ++k;
+    prev = c;
+  }
+}
+
+int encode_host(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, macko_matrix* m) {
+  std::vector<int64_t> entries(rows), nnzs(rows);
+  parallel_blocks(rows, [&](int64_t lo, int64_t hi) {
+    for (int64_t r = lo; r < hi; ++r) count_row(dense + r * ld, cols, &entries[r], &nnzs[r]);
+  });
+  int64_t pad_nnz = 0, nnz = 0, empty = 0, longest = 0;
+  m->h_row_ptr.assign(rows + 1, 0);
+  for (int64_t r = 0; r < rows; ++r) {
+    pad_nnz += entries[r];
+    nnz += nnzs[r];
+    empty += entries[r] == 0;
+    longest = std::max(longest, entries[r]);
+    if (pad_nnz >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
+    m->h_row_ptr[r + 1] = static_cast<uint32_t>(pad_nnz);
+  }
+  const int64_t alloc = (pad_nnz + kAllocGranule - 1) / kAllocGranule * kAllocGranule;
+  if (alloc >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
+  m->h_values.assign(alloc, 0);
+  m->h_deltas.assign(alloc / 2, 0);
+  std::vector<uint8_t> codes(alloc, 0);
+  parallel_blocks(rows, [&](int64_t lo, int64_t hi) {
+    for (int64_t r = lo; r < hi; ++r) {
+      const int64_t at = m->h_row_ptr[r];
+      fill_row(dense + r * ld, cols, m->h_values.data() + at, codes.data() + at);
+    }
+  });
+  parallel_blocks(alloc / 2, [&](int64_t lo, int64_t hi) {
+    for (int64_t b = lo; b < hi; ++b)
+      m->h_deltas[b] = static_cast<uint8_t>(codes[2 * b] | (codes[2 * b + 1] << 4));
+  });
+  m->rows = rows;
+  m->cols = cols;
+  m->pad_nnz = pad_nnz;
+  m->alloc_nnz = alloc;
+  m->has_host = true;
+  fill_report(&m->report, rows, cols, nnz, pad_nnz, alloc, empty, longest);
+  return MACKO_OK;
+}
+
+}  // namespace
+}  // namespace macko
+
+using macko::tuning;
+
+extern "C" {
+
+int macko_encode(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
+                 macko_handle_t* out, macko_report_t* report) {
+  if (out) *out = nullptr;
+  if (!out || rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
+  if (!dense_host && rows > 0 && cols > 0) return MACKO_E_INVALID_ARG;
+  if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  macko_matrix* m = nullptr;
+  try {
+    m = new macko_matrix();
+    int st = macko::encode_host(dense_host, rows, cols, ld, m);
+    if (st != MACKO_OK) {
+      delete m;
+      return st;
+    }
+  } catch (const std::bad_alloc&) {
+    delete m;
+    return MACKO_E_OUT_OF_MEMORY;
+  } catch (...) {
+    delete m;
+    return MACKO_E_INVALID_ARG;
+  }
+  if (report) *report = m->report;
+  *out = m;
+  return MACKO_OK;
+}
+
+int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, void* stream,
+                        macko_handle_t* out, macko_report_t* report) {
+  if (out) *out = nullptr;
+  if (!out || rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
+  if (!dense_dev && rows > 0 && cols > 0) return MACKO_E_INVALID_ARG;
+  if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  macko_matrix* m = new (std::nothrow) macko_matrix();
+  if (!m) return MACKO_E_OUT_OF_MEMORY;
+  uint16_t* v = nullptr;
+  uint8_t* d = nullptr;
+  uint32_t* rp = nullptr;
+  int64_t nnz = 0, pad = 0, alloc = 0, empty = 0, longest = 0;
+  int st = macko::encode_on_device(static_cast<const uint16_t*>(dense_dev), rows, cols, ld,
+                                   static_cast<hipStream_t>(stream), &v, &d, &rp, &nnz, &pad, &alloc,
+                                   &empty, &longest);
+  if (st != MACKO_OK) {
+    delete m;
+    return st;
+  }
+  m->rows = rows;
+  m->cols = cols;
+  m->pad_nnz = pad;
+  m->alloc_nnz = alloc;
+  m->d_values = v;
+  m->d_deltas = d;
+  m->d_row_ptr = rp;
+  m->bound = true;
+  m->owns_device = true;
+  macko::fill_report(&m->report, rows, cols, nnz, pad, alloc, empty, longest);
+  if (report) *report = m->report;
+  *out = m;
+  return MACKO_OK;
+}
+
+int macko_wrap_device(int64_t rows, int64_t cols, int64_t pad_nnz, const void* values_dev,
+                      const void* deltas_dev, const void* rowptr_dev, macko_handle_t* out) {
+  if (out) *out = nullptr;
+  if (!out || rows < 0 || cols < 0 || pad_nnz < 0 || !rowptr_dev) return MACKO_E_INVALID_ARG;
+  if (pad_nnz > 0 && (!values_dev || !deltas_dev)) return MACKO_E_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(values_dev) & 15) || (reinterpret_cast<uintptr_t>(deltas_dev) & 15) ||
+      (reinterpret_cast<uintptr_t>(rowptr_dev) & 3))
+    return MACKO_E_INVALID_ARG;
+  const int64_t alloc = (pad_nnz + macko::kAllocGranule - 1) / macko::kAllocGranule * macko::kAllocGranule;
+  if (alloc >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
+  if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  macko_matrix* m = new (std::nothrow) macko_matrix();
+  if (!m) return MACKO_E_OUT_OF_MEMORY;
+  m->rows = rows;
+  m->cols = cols;
+  m->pad_nnz = pad_nnz;
+  m->alloc_nnz = alloc;
+  m->d_values = static_cast<const uint16_t*>(values_dev);
+  m->d_deltas = static_cast<const uint8_t*>(deltas_dev);
+  m->d_row_ptr = static_cast<const uint32_t*>(rowptr_dev);
+  m->bound = true;
+  macko::fill_report(&m->report, rows, cols, -1, pad_nnz, alloc, -1, -1);
+  *out = m;
+  return MACKO_OK;
+}
+
+int macko_get_report(macko_handle_t h, macko_report_t* report) {
+  if (!h || !report) return MACKO_E_INVALID_ARG;
+  *report = h->report;
+  return MACKO_OK;
+}
+
+int macko_device_bytes(macko_handle_t h, int64_t* values_bytes, int64_t* deltas_bytes,
+                       int64_t* rowptr_bytes) {
+  if (!h) return MACKO_E_INVALID_ARG;
+  if (values_bytes) *values_bytes = h->alloc_nnz * 2;
+  if (deltas_bytes) *deltas_bytes = h->alloc_nnz / 2;
+  if (rowptr_bytes) *rowptr_bytes = 4 * (h->rows + 1);
+  return MACKO_OK;
+}
+
+int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas_dev, void* rowptr_dev,
+                      void* stream) {
+  if (!h || !rowptr_dev) return MACKO_E_INVALID_ARG;
+  if (!h->has_host) return MACKO_E_UNSUPPORTED;
+  if (h->alloc_nnz > 0 && (!values_dev || !deltas_dev)) return MACKO_E_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(values_dev) & 15) || (reinterpret_cast<uintptr_t>(deltas_dev) & 15) ||
+      (reinterpret_cast<uintptr_t>(rowptr_dev) & 3))
+    return MACKO_E_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (h->alloc_nnz > 0) {
+    MACKO_HIP_TRY(hipMemcpyAsync(values_dev, h->h_values.data(), h->alloc_nnz * 2, hipMemcpyHostToDevice, s));
+    MACKO_HIP_TRY(hipMemcpyAsync(deltas_dev, h->h_deltas.data(), h->alloc_nnz / 2, hipMemcpyHostToDevice, s));
+  }
+  MACKO_HIP_TRY(hipMemcpyAsync(rowptr_dev, h->h_row_ptr.data(), 4 * (h->rows + 1), hipMemcpyHostToDevice, s));
+  // the host vectors are pageable: make sure the copies have left them before returning
+  MACKO_HIP_TRY(hipStreamSynchronize(s));
+  h->d_values = static_cast<const uint16_t*>(values_dev);
+  h->d_deltas = static_cast<const uint8_t*>(deltas_dev);
+  h->d_row_ptr = static_cast<const uint32_t*>(rowptr_dev);
+  h->bound = true;
+  h->owns_device = false;
+  return MACKO_OK;
+}
+
+int macko_host_buffers(macko_handle_t h, const uint16_t** values, const uint8_t** deltas,
+                       const uint32_t** row_ptr) {
+  if (!h) return MACKO_E_INVALID_ARG;
+  if (!h->has_host) return MACKO_E_UNSUPPORTED;
+  if (values) *values = h->h_values.data();
+  if (deltas) *deltas = h->h_deltas.data();
+  if (row_ptr) *row_ptr = h->h_row_ptr.data();
+  return MACKO_OK;
+}
+
+int macko_fetch_device(macko_handle_t h, uint16_t* values_host, uint8_t* deltas_host,
+                       uint32_t* rowptr_host) {
+  if (!h || !rowptr_host) return MACKO_E_INVALID_ARG;
+  if (!h->bound) return MACKO_E_NOT_BOUND;
+  if (h->alloc_nnz > 0) {
+    if (!values_host || !deltas_host) return MACKO_E_INVALID_ARG;
+    MACKO_HIP_TRY(hipMemcpy(values_host, h->d_values, h->alloc_nnz * 2, hipMemcpyDeviceToHost));
+    MACKO_HIP_TRY(hipMemcpy(deltas_host, h->d_deltas, h->alloc_nnz / 2, hipMemcpyDeviceToHost));
+  }
+  MACKO_HIP_TRY(hipMemcpy(rowptr_host, h->d_row_ptr, 4 * (h->rows + 1), hipMemcpyDeviceToHost));
+  return MACKO_OK;
+}
+
+int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld) {
+  if (!h || ld < h->cols) return MACKO_E_INVALID_ARG;
+  if (!h->has_host) return MACKO_E_UNSUPPORTED;
+  if (!dense_host_out && h->rows > 0 && h->cols > 0) return MACKO_E_INVALID_ARG;
+  for (int64_t r = 0; r < h->rows; ++r) {
+    uint16_t* row = dense_host_out + r * ld;
+    std::fill(row, row + h->cols, uint16_t{0});
+    int64_t pos = 0;  // column + 1 of the last decoded entry
+    for (int64_t k = h->h_row_ptr[r]; k < h->h_row_ptr[r + 1]; ++k) {
+      pos += ((h->h_deltas[k >> 1] >> (4 * (k & 1))) & 15) + 1;
+      if (pos > h->cols) return MACKO_E_INVALID_ARG;
+      row[pos - 1] = h->h_values[k];
+    }
+  }
+  return MACKO_OK;
+}
+
+int macko_spmv(macko_handle_t h, const void* x_dev, void* y_dev, void* stream) {
+  if (!h) return MACKO_E_INVALID_ARG;
+  if (!h->bound) return MACKO_E_NOT_BOUND;
+  if (h->rows == 0) return MACKO_OK;
+  if (!y_dev || (!x_dev && h->cols > 0)) return MACKO_E_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(x_dev) & 1) || (reinterpret_cast<uintptr_t>(y_dev) & 1))
+    return MACKO_E_INVALID_ARG;
+  return macko::launch_spmv(h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
+                            h->report.max_row_entries, x_dev, y_dev, static_cast<hipStream_t>(stream));
+}
+
+int macko_dense_gemv(const void* W_dev, int64_t rows, int64_t cols, int64_t ld, const void* x_dev,
+                     void* y_dev, void* stream) {
+  if (rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
+  if (rows == 0) return MACKO_OK;
+  if (!y_dev || (cols > 0 && (!W_dev || !x_dev))) return MACKO_E_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(x_dev) & 1) || (reinterpret_cast<uintptr_t>(y_dev) & 1) ||
+      (reinterpret_cast<uintptr_t>(W_dev) & 1))
+    return MACKO_E_INVALID_ARG;
+  if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  return macko::launch_dense_gemv(W_dev, rows, cols, ld, x_dev, y_dev, static_cast<hipStream_t>(stream));
+}
+
+void macko_destroy(macko_handle_t h) {
+  if (!h) return;
+  if (h->owns_device) {
+    (void)hipFree(const_cast<uint16_t*>(h->d_values));
+    (void)hipFree(const_cast<uint8_t*>(h->d_deltas));
+    (void)hipFree(const_cast<uint32_t*>(h->d_row_ptr));
+  }
+  delete h;
+}
+
+const char* macko_status_string(int status) {
+  switch (status) {
+    case MACKO_OK: return "ok";
+    case MACKO_E_INVALID_ARG: return "invalid argument";
+    case MACKO_E_OVERFLOW: return "entry count does not fit 32-bit row pointers";
+    case MACKO_E_UNSUPPORTED: return "unsupported";
+    case MACKO_E_OUT_OF_MEMORY: return "out of memory";
+    case MACKO_E_NOT_BOUND: return "handle has no device buffers";
+    case MACKO_E_HIP: return "HIP error";
+    default: return "unknown status";
+  }
+}
+
+int macko_last_hip_error(void) { return macko::g_last_hip_error; }
+
+static int64_t* tuning_slot(const char* name) {
+  if (!name) return nullptr;
+  macko::Tuning& t = tuning();
+  const std::string n(name);
+  if (n == "spmv_kernel") return &t.spmv_kernel;
+  if (n == "spmv_lanes") return &t.spmv_lanes;
+  if (n == "spmv_block") return &t.spmv_block;
+  if (n == "spmv_rows_per_wg") return &t.spmv_rows_per_wg;
+  if (n == "gemv_block") return &t.gemv_block;
+  if (n == "gemv_rows_per_wg") return &t.gemv_rows_per_wg;
+  return nullptr;
+}
+
+int macko_set_tuning(const char* name, int64_t value) {
+  int64_t* slot = tuning_slot(name);
+  if (!slot || value < 0) return MACKO_E_INVALID_ARG;
+  const std::string n(name);
+  if (n == "spmv_kernel" && value > 2) return MACKO_E_INVALID_ARG;
+  if (n == "spmv_lanes" && value != 0 && value != 16 && value != 32 && value != 64) return MACKO_E_INVALID_ARG;
+  if ((n == "spmv_block" || n == "gemv_block") && value != 0 && (value % 64 != 0 || value > 1024))
+    return MACKO_E_INVALID_ARG;
+  if ((n == "spmv_rows_per_wg" || n == "gemv_rows_per_wg") && value > (int64_t{1} << 30))
+    return MACKO_E_INVALID_ARG;
+  *slot = value;
+  return MACKO_OK;
+}
+
+int macko_get_tuning(const char* name, int64_t* value) {
+  int64_t* slot = tuning_slot(name);
+  if (!slot || !value) return MACKO_E_INVALID_ARG;
+  *value = *slot;
+  return MACKO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of libmacko.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "macko.h"
+
+namespace macko {
+
+constexpr int kDeltaBits = 4;           // b_delta
+constexpr int kMaxDelta = 16;           // 2^b_delta
+constexpr int kAllocGranule = 32;       // entries per 16 bytes of packed deltas
+
+struct Tuning {
+  int64_t spmv_kernel = 0;
+  int64_t spmv_lanes = 0;
+  int64_t spmv_block = 0;
+  int64_t spmv_rows_per_wg = 0;
+  int64_t gemv_block = 0;
+  int64_t gemv_rows_per_wg = 0;
+};
+Tuning& tuning();
+
+// record a failing HIP call for macko_last_hip_error()
+int hip_fail(hipError_t e);
+#define MACKO_HIP_TRY(expr)                                   \
+  do {                                                        \
+    hipError_t e__ = (expr);                                  \
+    if (e__ != hipSuccess) return ::macko::hip_fail(e__);     \
+  } while (0)
+
+int device_cu_count();
+
+// launchers implemented in the .hip files; all return a macko_status
+int launch_spmv(const uint16_t* values, const uint8_t* deltas, const uint32_t* row_ptr, int64_t rows,
+                int64_t cols, int64_t pad_nnz, int64_t max_row_entries, const void* x, void* y,
+                hipStream_t stream);
+int launch_dense_gemv(const void* W, int64_t rows, int64_t cols, int64_t ld, const void* x, void* y,
+                      hipStream_t stream);
+// GPU encoder: counting pass + fill pass.  Allocates *values, *deltas, *row_ptr with hipMalloc.
+int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, hipStream_t stream,
+                     uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
+                     int64_t* pad_nnz, int64_t* alloc_nnz, int64_t* empty_rows,
+                     int64_t* max_row_entries);
+
+void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, int64_t pad_nnz,
+                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries);
+
+}  // namespace macko
+
+struct macko_matrix {
+  int64_t rows = 0, cols = 0;
+  int64_t pad_nnz = 0, alloc_nnz = 0;
+  macko_report_t report{};
+  // host copy (empty for device-encoded and wrapped handles)
+  bool has_host = false;
+  std::vector<uint16_t> h_values;
+  std::vector<uint8_t> h_deltas;
+  std::vector<uint32_t> h_row_ptr;
+  // device binding
+  const uint16_t* d_values = nullptr;
+  const uint8_t* d_deltas = nullptr;
+  const uint32_t* d_row_ptr = nullptr;
+  bool bound = false;
+  bool owns_device = false;
+};

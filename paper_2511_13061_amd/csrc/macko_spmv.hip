@@ -1,0 +1,355 @@
+// MACKO sparse matrix-vector product for gfx950 (Section 4.4 of the paper,
+// re-designed for 64-lane wavefronts).
+//
+// Per step a lane owns 8 consecutive stored entries: one 32-bit word of packed
+// 4-bit codes and one 128-bit vector of fp16 values, so a wavefront streams
+// 256 B of deltas and 1024 B of values per step, fully coalesced.  Column
+// positions are rebuilt in registers (per-lane SWAR prefix over the 8 codes,
+// then a DPP prefix sum over the lanes), the activation vector is gathered from
+// LDS, products are accumulated in fp32 and reduced over the wavefront with DPP.
+#include "macko_device.h"
+#include "macko_internal.h"
+
+namespace macko {
+namespace {
+
+// ---------------------------------------------------------------------------
+// Generic kernel: LANES (16, 32 or 64) lanes cooperate on a row, so a wavefront
+// works on 64/LANES rows at once.  Every entry is individually masked against
+// the row bounds.  Used for short rows and as the fallback when x does not fit
+// in LDS (XLDS = false gathers x from global memory).
+// ---------------------------------------------------------------------------
+template <int LANES, bool XLDS>
+__global__ void __launch_bounds__(1024)
+spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
+                    const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
+                    uint16_t* __restrict__ y, int rows, int cols, int rows_per_wg, int lds_bytes) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  if (XLDS) stage_x_to_lds(lds, x, cols, lds_bytes);
+  const uint16_t* xs = XLDS ? reinterpret_cast<const uint16_t*>(lds + kFrontPad) : x;
+
+  const int groups = blockDim.x / LANES;
+  const int group = threadIdx.x / LANES;
+  const int gl = threadIdx.x % LANES;                 // lane within the row's group
+  const int row_begin = blockIdx.x * rows_per_wg;
+  const int row_end = min(rows, row_begin + rows_per_wg);
+
+  for (int rb = row_begin; rb < row_end; rb += groups) {
+    const int row = rb + group;
+    const bool active = row < row_end;
+    const uint32_t start = active ? row_ptr[row] : 0u;
+    const uint32_t end = active ? row_ptr[row + 1] : 0u;
+    uint32_t cur = start & ~7u;        // reverse-offset alignment: back up to an 8-entry boundary
+    int pos = 0;                       // sum of deltas consumed so far = last column + 1
+    float acc = 0.0f;
+    while (__any(cur < end)) {
+      const uint32_t e0 = cur + 8u * gl;
+      uint32_t w = 0;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (e0 < end) {                  // the 8-entry chunk intersects [start, end)
+        w = deltas[e0 >> 3];
+        v = values[e0 >> 3];
+      }
+      const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+      int d[8];
+      int local = 0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const bool valid = (e0 + k >= start) && (e0 + k < end);
+        d[k] = valid ? (int)((w >> (4 * k)) & 15u) + 1 : 0;
+        local += d[k];
+      }
+      int incl = local;                // inclusive prefix over the group (Alg. 1)
+#pragma unroll
+      for (int off = 1; off < LANES; off <<= 1) {
+        const int t = __shfl_up(incl, off, LANES);
+        if (gl >= off) incl += t;
+      }
+      int p = pos + incl - local;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        p += d[k];
+        if (d[k] != 0) {
+          const uint16_t hv = (uint16_t)(vv[k >> 1] >> (16 * (k & 1)));
+          acc = fmaf(f16_bits_to_f32(hv), f16_bits_to_f32(xs[p - 1]), acc);
+        }
+      }
+      pos += __shfl(incl, LANES - 1, LANES);
+      cur += 8u * LANES;
+    }
+#pragma unroll
+    for (int off = LANES / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, LANES);
+    if (active && gl == 0) y[row] = f32_to_f16_bits(acc);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Wave-per-row kernel: the fast path for rows of at least a few hundred
+// entries.  Row bounds, step counts and the running column base are wavefront
+// uniform and live in scalar registers.
+//
+// Position arithmetic is done in units of bytes of the LDS copy of x, i.e.
+// doubled: an entry with code c advances the position by 2c + 2.  Within a lane
+// the 8 doubled code prefixes (at most 2*15*8 = 240) fit the bytes of two 32-bit
+// words; the constant part 2(k+1) of entry k goes into the immediate offset of
+// the LDS read.
+//
+// A workgroup owns rows [row_begin, row_end); each of its wavefronts owns a
+// contiguous share of them and works through it in blocks of up to 64 rows.
+// For a block, lane i fetches row i's pointers once (one coalesced load); the
+// scalar row bounds are then picked out of that register with v_readlane, and
+// the 64 results are collected in a register (v_writelane) and stored with one
+// coalesced store.  The steady-state loop therefore contains no memory
+// instruction other than the two streaming loads per item.
+//
+// The block's rows form one stream of (row, step) items.  Loads run RING items
+// ahead of the arithmetic and cross row boundaries, so the memory pipeline does
+// not drain between rows.  Every item issues exactly one deltas load and one
+// values load, unconditionally (lanes past the row end re-read the row's last
+// chunk, items past the block's last row re-read the previous address), which
+// lets the compiler count outstanding loads exactly.
+//
+// Entries of neighbouring rows that share a lane's 8-entry chunk:
+//  - before the row start: the base is set so that the row's first entry lands
+//    on its own column; earlier entries then decode to positions <= 0, which
+//    read the zero guard in front of x and contribute nothing;
+//  - after the row end (last step only): their codes and values are cleared.
+// No load ever leaves [0, alloc_nnz).
+// ---------------------------------------------------------------------------
+struct RowCursor {
+  int i;               // row index within the block (== nb when exhausted)
+  uint32_t start, end; // its entry range
+  uint32_t a0;         // start rounded down to 8 entries (reverse-offset alignment)
+  int nsteps, step;
+};
+
+// Move the cursor to the first non-empty row at or after cur.i.
+__device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t rp_lo, uint32_t rp_hi) {
+  cur.start = cur.end = 0;
+  while (cur.i < nb) {
+    cur.start = (uint32_t)__builtin_amdgcn_readlane((int)rp_lo, cur.i);
+    cur.end = (uint32_t)__builtin_amdgcn_readlane((int)rp_hi, cur.i);
+    if (cur.end > cur.start) break;
+    ++cur.i;
+  }
+  cur.a0 = cur.start & ~7u;
+  cur.nsteps = (int)((cur.end - cur.a0 + 511u) >> 9);
+  cur.step = 0;
+}
+
+template <int RING>
+__global__ void __launch_bounds__(1024)
+spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
+                     const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
+                     uint16_t* __restrict__ y, int rows, int cols, int rows_per_wg, int lds_bytes) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int row_begin = blockIdx.x * rows_per_wg;
+  const int row_end = min(rows, row_begin + rows_per_wg);
+  const int nwaves = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+  if (row_ptr[row_end] == row_ptr[row_begin]) {        // nothing stored in this block of rows
+    for (int r = row_begin + (int)threadIdx.x; r < row_end; r += blockDim.x) y[r] = 0;
+    return;
+  }
+  stage_x_to_lds(lds, x, cols, lds_bytes);             // ends with a barrier
+
+  // byte address of "position 0" minus the 2 that turns a position into a column
+  const unsigned char* xbase = lds + kFrontPad - 2;
+  const uint32_t lane8 = 8u * lane;
+  const int per_wave = (row_end - row_begin + nwaves - 1) / nwaves;
+  const int wrow_begin = min(row_end, row_begin + wave * per_wave);
+  const int wrow_end = min(row_end, wrow_begin + per_wave);
+
+  uint32_t chunk = 0;                                  // 8-entry chunk index this lane loads next
+
+  for (int blk = wrow_begin; blk < wrow_end; blk += 64) {
+    const int nb = min(64, wrow_end - blk);
+    uint32_t rp_lo = 0, rp_hi = 0;
+    if (lane < nb) {
+      rp_lo = row_ptr[blk + lane];
+      rp_hi = row_ptr[blk + lane + 1];
+    }
+    float yv = 0.0f;                                   // lane i: result of row blk + i
+
+    RowCursor ld, cp;                                  // load side, compute side
+    ld.i = 0;
+    seek_nonempty(ld, nb, rp_lo, rp_hi);
+    cp = ld;
+
+    uint32_t wq[RING];
+    uint4 vq[RING];
+    auto issue = [&](int j) {
+      if (ld.i < nb) {
+        const uint32_t e0 = ld.a0 + 512u * ld.step + lane8;
+        chunk = min(e0, ld.end - 1u) >> 3;
+        if (++ld.step == ld.nsteps) {
+          ++ld.i;
+          seek_nonempty(ld, nb, rp_lo, rp_hi);
+        }
+      }
+      wq[j] = deltas[chunk];
+      vq[j] = values[chunk];
+    };
+#pragma unroll
+    for (int j = 0; j < RING; ++j) issue(j);
+
+    float acc = 0.0f;
+    int base2 = 0;                                     // doubled position before this step (uniform)
+    while (cp.i < nb) {
+#pragma unroll
+      for (int j = 0; j < RING; ++j) {
+        uint32_t w = wq[j];
+        uint4 v = vq[j];
+
+        const bool live = cp.i < nb;                   // false for the padding items after the last row
+        if (!live) base2 = 0;                          // keep the (unused) gathers of padding items in range
+        const uint32_t end_eff = live ? cp.end : 0u;
+        const uint32_t e0 = cp.a0 + 512u * cp.step + lane8;
+        if (!live || cp.step == cp.nsteps - 1) {       // clear what lies past the row end
+          const uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;   // valid entries in this lane's chunk
+          w = nv != 0 ? w : 0u;
+          v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
+          v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
+          v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
+          v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
+        }
+        // doubled codes of even / odd entries, one per byte
+        const uint32_t lo2 = (w << 1) & 0x1E1E1E1Eu;
+        const uint32_t hi2 = (w >> 3) & 0x1E1E1E1Eu;
+        uint32_t P = lo2 + hi2;                        // pair sums
+        P = lshl_add<8>(P, P);
+        P = lshl_add<16>(P, P);                        // byte m: doubled code prefix through entry 2m+1
+        const uint32_t E = lshl_add<8>(P, lo2);        // byte m: doubled code prefix through entry 2m
+        const uint32_t tot = (P >> 24) + 16u;          // doubled sum of this lane's 8 deltas
+        const uint32_t incl = wave_incl_scan_u32(tot);
+        if (live && cp.step == 0) {
+          base2 = 0;
+          const int before = (int)(cp.start - cp.a0);  // entries of the previous row in lane 0's chunk
+          if (before > 0) {
+            const int k = before - 1;
+            const uint32_t src = __builtin_amdgcn_readfirstlane((k & 1) ? P : E);
+            base2 = -(int)(((src >> (8 * (k >> 1))) & 0xFFu) + 2u * (uint32_t)(k + 1));
+          }
+        }
+        const uint32_t lanebase = (uint32_t)base2 + incl - tot;
+        const unsigned char* xl = xbase + lanebase;
+#define MACKO_X(k, word, m) \
+  f16_bits_to_f32(*reinterpret_cast<const uint16_t*>(xl + (((word) >> (8 * (m))) & 0xFFu) + 2 * ((k) + 1)))
+#define MACKO_LO(u) f16_bits_to_f32((uint16_t)((u) & 0xFFFFu))
+#define MACKO_HI(u) f16_bits_to_f32((uint16_t)((u) >> 16))
+        acc = fmaf(MACKO_LO(v.x), MACKO_X(0, E, 0), acc);
+        acc = fmaf(MACKO_HI(v.x), MACKO_X(1, P, 0), acc);
+        acc = fmaf(MACKO_LO(v.y), MACKO_X(2, E, 1), acc);
+        acc = fmaf(MACKO_HI(v.y), MACKO_X(3, P, 1), acc);
+        acc = fmaf(MACKO_LO(v.z), MACKO_X(4, E, 2), acc);
+        acc = fmaf(MACKO_HI(v.z), MACKO_X(5, P, 2), acc);
+        acc = fmaf(MACKO_LO(v.w), MACKO_X(6, E, 3), acc);
+        acc = fmaf(MACKO_HI(v.w), MACKO_X(7, P, 3), acc);
+#undef MACKO_X
+#undef MACKO_LO
+#undef MACKO_HI
+        issue(j);                                      // refill the slot just consumed, RING items ahead
+        base2 += (int)__builtin_amdgcn_readlane((int)incl, 63);
+        if (live && ++cp.step == cp.nsteps) {          // row finished: reduce, keep the result, next row
+          const float total = wave_sum_to_last_lane(acc);
+          const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), 63);
+          yv = lane == cp.i ? __builtin_bit_cast(float, tbits) : yv;
+          acc = 0.0f;
+          ++cp.i;
+          seek_nonempty(cp, nb, rp_lo, rp_hi);
+        }
+      }
+    }
+    if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
+  }
+}
+
+template <class K>
+int set_lds_limit(K kernel, int64_t bytes) {
+  if (bytes > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return MACKO_OK;
+}
+
+constexpr int64_t kMaxLdsBytes = 160 * 1024 - 64;   // 160 KB per CU minus the static row counter
+
+}  // namespace
+
+int launch_spmv(const uint16_t* values, const uint8_t* deltas, const uint32_t* row_ptr, int64_t rows,
+                int64_t cols, int64_t pad_nnz, int64_t max_row_entries, const void* x, void* y,
+                hipStream_t stream) {
+  (void)max_row_entries;
+  const Tuning& t = tuning();
+  const int cus = device_cu_count();
+  const int64_t lds_bytes = lds_bytes_for(cols);
+  const bool lds_ok = lds_bytes <= kMaxLdsBytes;
+  const int64_t avg = rows > 0 ? pad_nnz / rows : 0;
+
+  int kernel = (int)t.spmv_kernel;
+  if (kernel == 0) kernel = (avg >= 384 && lds_ok) ? 2 : 1;
+  if (kernel == 2 && !lds_ok) return MACKO_E_UNSUPPORTED;
+
+  const uint4* v4 = reinterpret_cast<const uint4*>(values);
+  const uint32_t* d4 = reinterpret_cast<const uint32_t*>(deltas);
+  const uint16_t* xp = static_cast<const uint16_t*>(x);
+  uint16_t* yp = static_cast<uint16_t*>(y);
+
+  if (kernel == 2) {
+    const int block = t.spmv_block ? (int)t.spmv_block : 512;
+    const int nwaves = block / 64;
+    int64_t rpw = t.spmv_rows_per_wg;
+    if (rpw == 0) {
+      // enough workgroups to keep every CU busy with a few of them, but each
+      // long enough to amortise staging x
+      const int64_t target_wgs = (int64_t)cus * 4;
+      rpw = (rows + target_wgs - 1) / target_wgs;
+      rpw = std::max<int64_t>(rpw, nwaves);
+    }
+    const int64_t grid = (rows + rpw - 1) / rpw;
+    auto kfn = spmv_wave_row_kernel<4>;
+    int st = set_lds_limit(kfn, lds_bytes);
+    if (st != MACKO_OK) return st;
+    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds_bytes, stream, v4, d4,
+                       row_ptr, xp, yp, (int)rows, (int)cols, (int)rpw, (int)lds_bytes);
+  } else {
+    int lanes = (int)t.spmv_lanes;
+    if (lanes == 0) lanes = avg >= 384 ? 64 : (avg >= 192 ? 32 : 16);
+    const int block = t.spmv_block ? (int)t.spmv_block : 256;
+    const int groups = block / lanes;
+    int64_t rpw = t.spmv_rows_per_wg;
+    if (rpw == 0) {
+      const int64_t target_wgs = (int64_t)cus * 4;
+      rpw = (rows + target_wgs - 1) / target_wgs;
+      rpw = (std::max<int64_t>(rpw, groups) + groups - 1) / groups * groups;
+    }
+    const int64_t grid = (rows + rpw - 1) / rpw;
+    const size_t shm = lds_ok ? (size_t)lds_bytes : 0;
+#define MACKO_LAUNCH_SUB(L)                                                                          \
+  do {                                                                                               \
+    if (lds_ok) {                                                                                    \
+      auto kfn = spmv_subwave_kernel<L, true>;                                                       \
+      int st = set_lds_limit(kfn, lds_bytes);                                                        \
+      if (st != MACKO_OK) return st;                                                                 \
+      hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), shm, stream, v4, d4, row_ptr, xp,   \
+                         yp, (int)rows, (int)cols, (int)rpw, (int)lds_bytes);                        \
+    } else {                                                                                         \
+      hipLaunchKernelGGL((spmv_subwave_kernel<L, false>), dim3((unsigned)grid), dim3(block), 0,      \
+                         stream, v4, d4, row_ptr, xp, yp, (int)rows, (int)cols, (int)rpw, 0);        \
+    }                                                                                                \
+  } while (0)
+    if (lanes == 64) MACKO_LAUNCH_SUB(64);
+    else if (lanes == 32) MACKO_LAUNCH_SUB(32);
+    else MACKO_LAUNCH_SUB(16);
+#undef MACKO_LAUNCH_SUB
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(e);
+  return MACKO_OK;
+}
+
+}  // namespace macko

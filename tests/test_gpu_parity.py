@@ -1,0 +1,324 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Encodings must match the oracle byte for byte.  Every y_i must satisfy
+|y_gpu - y_fp64| <= 1e-2 * sum_j |w_ij x_j| + 1e-3, with y_fp64 the dense
+product by definition (Appendix A of the paper) computed by the oracle.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+M = pytest.importorskip("paper_2511_13061_amd")
+
+REL_TOL = 1e-2
+ABS_TOL = 1e-3
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu_and_library():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    M.load_library()          # raises if libmacko.so is missing: no fallback
+    yield
+    for knob in ("spmv_kernel", "spmv_lanes", "spmv_block", "spmv_rows_per_wg", "gemv_block",
+                 "gemv_rows_per_wg"):
+        M.set_tuning(knob, 0)
+
+
+def to_dev(a_u16):
+    return torch.from_numpy(np.ascontiguousarray(a_u16).view(np.float16)).cuda()
+
+
+def check_y(y_dev, W, x, what=""):
+    y64, s64 = oracle.dense_matvec(W, x)
+    y = y_dev.float().cpu().numpy().astype(np.float64)
+    assert y.shape == y64.shape
+    assert np.isfinite(y).all(), what
+    err = np.abs(y - y64)
+    bound = REL_TOL * s64 + ABS_TOL
+    worst = int(np.argmax(err - bound))
+    assert (err <= bound).all(), (
+        f"{what}: row {worst}: |{y[worst]} - {y64[worst]}| = {err[worst]} > {bound[worst]}")
+    # the tolerance is loose; fp32 accumulation should in fact sit well inside it
+    return float(np.max(err / bound))
+
+
+def spmv_case(W, x, **knobs):
+    for k, v in knobs.items():
+        M.set_tuning(k, v)
+    try:
+        m = M.encode(W).to_device()
+        y = m.spmv(to_dev(x))
+        torch.cuda.synchronize()
+    finally:
+        for k in knobs:
+            M.set_tuning(k, 0)
+    return y
+
+
+def assert_same_encoding(arrays, enc):
+    v, d, r = arrays
+    assert np.array_equal(r, enc.row_ptr)
+    assert np.array_equal(v, enc.values)
+    assert np.array_equal(d, enc.deltas)
+
+
+# ------------------------------------------------------------------ small and ragged
+
+SMALL = {
+    "c1_512": lambda: (wl.config1().W, wl.config1().x),
+    "ragged_777": lambda: (wl.bernoulli(301, 777, 0.5, 0.02, 9, 1), wl.x_vector(777, 9, 1)),
+    "long_rows_5000": lambda: (wl.bernoulli(70, 5000, 0.6, 0.02, 9, 2), wl.x_vector(5000, 9, 2)),
+    "very_sparse": lambda: (wl.bernoulli(200, 3000, 0.02, 1.0, 9, 3), wl.x_vector(3000, 9, 3)),
+    "dense": lambda: (wl.bernoulli(100, 1031, 1.0, 0.02, 9, 4), wl.x_vector(1031, 9, 4)),
+    "c4_small": lambda: (wl.config4(rows=256, cols=2048).W, wl.config4(rows=256, cols=2048).x),
+    "c4b_small": lambda: (wl.config4b(rows=128, cols=2048).W, wl.config4b(rows=128, cols=2048).x),
+    "one_row": lambda: (wl.bernoulli(1, 9000, 0.5, 0.02, 9, 5), wl.x_vector(9000, 9, 5)),
+    "one_col": lambda: (wl.bernoulli(300, 1, 0.5, 1.0, 9, 6), wl.x_vector(1, 9, 6)),
+}
+
+VARIANTS = {
+    "auto": {},
+    "sub16": {"spmv_kernel": 1, "spmv_lanes": 16},
+    "sub32": {"spmv_kernel": 1, "spmv_lanes": 32},
+    "sub64": {"spmv_kernel": 1, "spmv_lanes": 64},
+    "wave_row": {"spmv_kernel": 2},
+    "wave_row_b256_r5": {"spmv_kernel": 2, "spmv_block": 256, "spmv_rows_per_wg": 5},
+    "wave_row_b1024_r700": {"spmv_kernel": 2, "spmv_block": 1024, "spmv_rows_per_wg": 700},
+    "wave_row_b64_r200": {"spmv_kernel": 2, "spmv_block": 64, "spmv_rows_per_wg": 200},
+}
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("case", list(SMALL))
+def test_spmv_small_cases_all_kernels(case, variant):
+    W, x = SMALL[case]()
+    y = spmv_case(W, x, **VARIANTS[variant])
+    check_y(y, W, x, f"{case}/{variant}")
+
+
+def test_spmv_empty_rows_mixed_with_full_rows_and_row_boundaries_inside_chunks():
+    rng = np.random.default_rng(5)
+    C = 4096
+    W = wl.bernoulli(400, C, 0.5, 0.02, 11, 1)
+    W[rng.choice(400, 120, replace=False)] = 0           # empty rows, some adjacent
+    W[10:30] = 0
+    W[395:] = 0                                          # trailing empty rows
+    # rows with 1..9 entries so that several rows share one 8-entry chunk
+    for r in range(40, 60):
+        W[r] = 0
+        cols = rng.choice(C, size=(r - 39) % 10 + 1, replace=False)
+        W[r, cols] = wl.normal_f16(cols.size, 1.0, 11, r, nonzero=True)
+    x = wl.x_vector(C, 11, 1)
+    for variant in ("auto", "wave_row", "sub16", "wave_row_b64_r200"):
+        y = spmv_case(W, x, **VARIANTS[variant])
+        check_y(y, W, x, variant)
+        assert (y[10:30] == 0).all() and (y[395:] == 0).all()
+
+
+def test_spmv_all_zero_matrix_and_zero_sized():
+    x = wl.x_vector(640, 3, 3)
+    y = spmv_case(np.zeros((77, 640), dtype=np.uint16), x, spmv_kernel=2)
+    assert (y == 0).all()
+    y = spmv_case(np.zeros((77, 640), dtype=np.uint16), x)
+    assert (y == 0).all()
+    m = M.encode(np.zeros((0, 640), dtype=np.uint16)).to_device()
+    m.spmv(to_dev(x), torch.empty(0, dtype=torch.float16, device="cuda"))
+    torch.cuda.synchronize()
+
+
+def test_subnormal_weights_are_not_flushed():
+    # every weight is an fp16 subnormal; x = 2048 makes the exact row sums O(1)
+    rng = np.random.default_rng(1)
+    R, C = 64, 2048
+    W = np.zeros((R, C), dtype=np.uint16)
+    mask = rng.random((R, C)) < 0.5
+    W[mask] = rng.integers(1, 0x400, size=int(mask.sum()), dtype=np.uint16)   # positive subnormals
+    x = np.full(C, np.float16(2048.0)).view(np.uint16)
+    for variant in ("wave_row", "sub64"):
+        y = spmv_case(W, x, **VARIANTS[variant])
+        check_y(y, W, x, variant)
+        y64, _ = oracle.dense_matvec(W, x)
+        assert y64.min() > 10.0                                   # flushing would give exactly 0
+        assert np.allclose(y.float().cpu().numpy(), y64, rtol=2e-3)
+
+
+def test_unaligned_x_and_y_pointers():
+    W = wl.bernoulli(150, 1000, 0.5, 0.02, 4, 4)
+    x = wl.x_vector(1000, 4, 4)
+    xbuf = torch.zeros(1001, dtype=torch.float16, device="cuda")
+    xbuf[1:] = to_dev(x)
+    ybuf = torch.zeros(151, dtype=torch.float16, device="cuda")
+    m = M.encode(W).to_device()
+    for kernel in (1, 2):
+        M.set_tuning("spmv_kernel", kernel)
+        m.spmv(xbuf[1:], ybuf[1:])
+        torch.cuda.synchronize()
+        check_y(ybuf[1:], W, x, f"kernel {kernel}")
+    M.set_tuning("spmv_kernel", 0)
+
+
+def test_x_larger_than_64k_lds_and_x_larger_than_lds():
+    # 40000 columns need ~82 KB of LDS (above the 64 KB default limit)
+    W = wl.bernoulli(40, 40000, 0.3, 0.02, 6, 1)
+    x = wl.x_vector(40000, 6, 1)
+    check_y(spmv_case(W, x, spmv_kernel=2), W, x, "80KB LDS wave_row")
+    check_y(spmv_case(W, x, spmv_kernel=1, spmv_lanes=64), W, x, "80KB LDS sub64")
+    # 100000 columns do not fit in LDS at all: x is gathered from global memory
+    W = wl.bernoulli(24, 100000, 0.2, 0.02, 6, 2)
+    x = wl.x_vector(100000, 6, 2)
+    check_y(spmv_case(W, x), W, x, "global x")
+
+
+def test_wrap_device_reuses_an_existing_encoding():
+    W = wl.bernoulli(300, 2048, 0.5, 0.02, 8, 8)
+    x = wl.x_vector(2048, 8, 8)
+    m = M.encode(W).to_device()
+    v, d, r = [b.clone() for b in m.device_buffers()]
+    w = M.wrap_device(300, 2048, m.report.pad_nnz, v, d, r)
+    y = w.spmv(to_dev(x))
+    torch.cuda.synchronize()
+    check_y(y, W, x, "wrapped")
+    assert torch.equal(y, m.spmv(to_dev(x)))
+
+
+# ------------------------------------------------------------------ GPU encoder
+
+ENC_CASES = {
+    "c1": lambda: wl.config1().W,
+    "ragged": lambda: wl.bernoulli(301, 777, 0.5, 0.02, 9, 1),
+    "very_sparse": lambda: wl.bernoulli(200, 3000, 0.02, 1.0, 9, 3),
+    "dense": lambda: wl.bernoulli(100, 1031, 1.0, 0.02, 9, 4),
+    "c4": lambda: wl.config4(rows=256, cols=2048).W,
+    "c4b": lambda: wl.config4b(rows=128, cols=2048).W,
+    "one_col": lambda: wl.bernoulli(300, 1, 0.5, 1.0, 9, 6),
+    "empty": lambda: np.zeros((50, 600), dtype=np.uint16),
+    "llama_slice": lambda: wl.half_row_matrix(512, 4096, 42),
+}
+
+
+@pytest.mark.parametrize("case", list(ENC_CASES))
+def test_gpu_encoder_is_bit_exact(case):
+    W = ENC_CASES[case]()
+    enc = oracle.encode(W)
+    g = M.encode_device(to_dev(W))
+    assert_same_encoding(g.fetch_device(), enc)
+    rep = g.report
+    assert (rep.nnz, rep.pad_nnz, rep.alloc_nnz) == (enc.nnz, enc.pad_nnz, enc.alloc_nnz)
+    ent = np.diff(enc.row_ptr.astype(np.int64))
+    assert rep.empty_rows == int((ent == 0).sum()) and rep.max_row_entries == int(ent.max(initial=0))
+    assert rep.total_bytes == enc.total_bytes
+    # and the device-encoded handle multiplies correctly
+    x = wl.x_vector(W.shape[1], 1, 1)
+    y = g.spmv(to_dev(x))
+    torch.cuda.synchronize()
+    check_y(y, W, x, case)
+
+
+def test_gpu_encoder_special_values_and_strided_unaligned_input():
+    W = wl.bernoulli(64, 1001, 0.3, 0.02, 2, 2)
+    W[0, 3] = 0x8000
+    W[0, 5] = 0x0001
+    W[1, 0] = 0x7C00
+    W[2, 50] = 0xFE00
+    W[5, 17] = 0x8001
+    enc = oracle.encode(W)
+    big = torch.zeros((64, 1003), dtype=torch.float16, device="cuda")     # ld = 1003: no 16-byte rows
+    big[:, 1:1002] = to_dev(W)
+    g = M.encode_device(big[:, 1:1002])
+    assert_same_encoding(g.fetch_device(), enc)
+    # the host encoder bound to the device gives the same bytes
+    h = M.encode(W).to_device()
+    assert_same_encoding(h.fetch_device(), enc)
+
+
+# ------------------------------------------------------------------ dense GEMV baseline
+
+@pytest.mark.parametrize("shape", [(512, 512), (300, 1000), (77, 4096), (64, 8200), (10, 40000), (33, 777), (5, 3)])
+def test_dense_gemv(shape):
+    R, C = shape
+    W = wl.bernoulli(R, C, 1.0, 0.02, 12, R)
+    x = wl.x_vector(C, 12, R)
+    y = M.dense_gemv(to_dev(W), to_dev(x))
+    torch.cuda.synchronize()
+    check_y(y, W, x, f"gemv {shape}")
+    for knobs in ({"gemv_block": 256, "gemv_rows_per_wg": 3}, {"gemv_block": 1024, "gemv_rows_per_wg": 1000}):
+        for k, v in knobs.items():
+            M.set_tuning(k, v)
+        y = M.dense_gemv(to_dev(W), to_dev(x))
+        torch.cuda.synchronize()
+        check_y(y, W, x, f"gemv {shape} {knobs}")
+        for k in knobs:
+            M.set_tuning(k, 0)
+
+
+def test_dense_gemv_with_leading_dimension_and_on_sparse_input():
+    W = wl.half_row_matrix(200, 1024, 5)
+    x = wl.x_vector(1024, 5, 5)
+    big = torch.zeros((200, 1040), dtype=torch.float16, device="cuda")
+    big[:, :1024] = to_dev(W)
+    y = M.dense_gemv(big[:, :1024], to_dev(x))
+    torch.cuda.synchronize()
+    check_y(y, W, x, "ld=1040")
+    # sparse and dense paths agree on the same matrix to within both tolerances
+    ys = spmv_case(W, x)
+    assert torch.allclose(ys.float(), y.float(), atol=2e-3, rtol=2e-2)
+
+
+# ------------------------------------------------------------------ full-size configurations
+
+def test_config2_llama2_7b_shapes_full_size():
+    for case in wl.config2():
+        enc = oracle.encode(case.W)
+        m = M.encode(case.W)
+        assert_same_encoding(m.host_buffers(), enc)
+        m.to_device()
+        y = m.spmv(to_dev(case.x))
+        torch.cuda.synchronize()
+        check_y(y, case.W, case.x, case.name)
+        yd = M.dense_gemv(to_dev(case.W), to_dev(case.x))
+        torch.cuda.synchronize()
+        check_y(yd, case.W, case.x, case.name + " dense")
+        g = M.encode_device(to_dev(case.W))
+        assert_same_encoding(g.fetch_device(), enc)
+
+
+@pytest.mark.parametrize("sparsity", [0, 50, 90])
+def test_config3_sweep_matrix_full_size(sparsity):
+    case = wl.config3(sparsity)
+    m = M.encode(case.W).to_device()
+    y = m.spmv(to_dev(case.x))
+    torch.cuda.synchronize()
+    check_y(y, case.W, case.x, case.name)
+    rep = m.report
+    assert rep.effd_best <= rep.effd + 1e-9
+    if sparsity == 50:
+        enc = oracle.encode(case.W)
+        assert_same_encoding(m.fetch_device(), enc)
+        g = M.encode_device(to_dev(case.W))
+        assert_same_encoding(g.fetch_device(), enc)
+
+
+def test_config4_adversarial_full_size():
+    for case in (wl.config4(), wl.config4b()):
+        enc = oracle.encode(case.W)
+        m = M.encode(case.W)
+        assert_same_encoding(m.host_buffers(), enc)
+        m.to_device()
+        y = m.spmv(to_dev(case.x))
+        torch.cuda.synchronize()
+        check_y(y, case.W, case.x, case.name)
+        g = M.encode_device(to_dev(case.W))
+        assert_same_encoding(g.fetch_device(), enc)
+
+
+def test_config5_llama2_13b_layer_shapes_full_size():
+    for case in wl.config5_layer():
+        m = M.encode(case.W).to_device()
+        y = m.spmv(to_dev(case.x))
+        torch.cuda.synchronize()
+        check_y(y, case.W, case.x, case.name)

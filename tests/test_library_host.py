@@ -1,0 +1,132 @@
+"""The library's host side against the oracle (CPU only, no GPU calls).
+
+The host encoder of libmacko is a separate implementation (two parallel passes
+and a closed-form padding count); it must agree with the oracle byte for byte.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+
+M = pytest.importorskip("paper_2511_13061_amd")
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def same_encoding(m, enc):
+    v, d, r = m.host_buffers()
+    assert v.dtype == np.uint16 and d.dtype == np.uint8 and r.dtype == np.uint32
+    assert np.array_equal(v, enc.values)
+    assert np.array_equal(d, enc.deltas)
+    assert np.array_equal(r, enc.row_ptr)
+
+
+def same_report(rep, enc, W):
+    assert (rep.rows, rep.cols) == W.shape
+    assert rep.nnz == enc.nnz and rep.pad_nnz == enc.pad_nnz and rep.alloc_nnz == enc.alloc_nnz
+    assert rep.padding_entries == enc.padding_entries
+    assert rep.values_bytes == enc.values_bytes and rep.deltas_bytes == enc.deltas_bytes
+    assert rep.rowptr_bytes == enc.rowptr_bytes and rep.total_bytes == enc.total_bytes
+    assert rep.dense_bytes == enc.dense_bytes
+    ent = np.diff(enc.row_ptr.astype(np.int64))
+    assert rep.empty_rows == int((ent == 0).sum())
+    assert rep.max_row_entries == (int(ent.max()) if ent.size else 0)
+    assert rep.b_val == 16 and rep.b_delta == 4
+    if W.size:
+        d = enc.nnz / W.size
+        cf = oracle.closed_forms
+        assert rep.density == pytest.approx(d, abs=1e-15)
+        assert rep.effd == pytest.approx(enc.effd, rel=1e-14)
+        assert rep.effd_best == pytest.approx(cf.effd_macko_best(d), rel=1e-13)
+        assert rep.effd_worst == pytest.approx(cf.effd_macko_worst(d), rel=1e-13)
+        assert rep.effd_expected == pytest.approx(cf.effd_macko_expected(d), rel=1e-12)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "macko.h")).read()
+    declared = set(re.findall(r"MACKO_API\s+[\w\s\*]+?\b(macko_\w+)\s*\(", header))
+    assert declared == set(M.binding.EXPORTED_SYMBOLS)
+    lib = ctypes.CDLL(M.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+CASES = [
+    ("c1", lambda: wl.config1().W),
+    ("bern_sparse", lambda: wl.bernoulli(97, 1531, 0.03, 1.0, 5, 1)),
+    ("bern_half", lambda: wl.bernoulli(130, 777, 0.5, 0.02, 5, 2)),
+    ("dense", lambda: wl.bernoulli(33, 257, 1.0, 0.02, 5, 3)),
+    ("c4", lambda: wl.config4(rows=96, cols=1200).W),
+    ("c4b", lambda: wl.config4b(rows=40, cols=992).W),
+    ("one_col", lambda: wl.bernoulli(50, 1, 0.5, 1.0, 5, 4)),
+    ("wide_empty", lambda: np.zeros((9, 4000), dtype=np.uint16)),
+]
+
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+def test_host_encoder_is_bit_exact_against_the_oracle(name, make):
+    W = make()
+    enc = oracle.encode(W)
+    rep_holder = M.encode(W)
+    same_encoding(rep_holder, enc)
+    same_report(rep_holder.report, enc, W)
+    assert np.array_equal(rep_holder.decode(), oracle.decode(enc))
+    rep_holder.destroy()
+
+
+def test_special_bit_patterns_and_strided_input():
+    W = np.zeros((6, 100), dtype=np.uint16)
+    W[0, 3] = 0x8000      # -0 dropped
+    W[0, 99] = 0x0001     # subnormal kept, long gap
+    W[1, 0] = 0x7C00
+    W[2, 50] = 0xFE00
+    W[5, 17] = 0x8001
+    big = np.zeros((6, 128), dtype=np.uint16)
+    big[:, :100] = W
+    m = M.encode(big[:, :100])          # ld = 128 > cols
+    same_encoding(m, oracle.encode(W))
+    canon = W.copy(); canon[0, 3] = 0
+    assert np.array_equal(m.decode(), canon)
+
+
+def test_empty_shapes_and_error_codes():
+    lib = M.load_library()
+    for shape in [(0, 5), (5, 0), (0, 0)]:
+        m = M.encode(np.zeros(shape, dtype=np.uint16))
+        assert m.report.pad_nnz == 0 and m.report.alloc_nnz == 0
+        v, d, r = m.host_buffers()
+        assert r.tolist() == [0] * (shape[0] + 1) and v.size == 0 and d.size == 0
+    h = ctypes.c_void_p(123)
+    W = np.ones((2, 2), dtype=np.uint16)
+    assert lib.macko_encode(W.ctypes.data, 2, 2, 1, ctypes.byref(h), None) == -1   # ld < cols
+    assert h.value is None
+    assert lib.macko_encode(None, 2, 2, 2, ctypes.byref(h), None) == -1
+    assert lib.macko_encode(W.ctypes.data, -1, 2, 2, ctypes.byref(h), None) == -1
+    assert lib.macko_encode(W.ctypes.data, 2, 2, 2, None, None) == -1
+    m = M.encode(W)
+    # not bound: device operations are refused without touching the GPU
+    assert lib.macko_spmv(m._h, 16, 16, None) == -5
+    assert lib.macko_fetch_device(m._h, 16, 16, 16) == -5
+    assert M.status_string(-5) == "handle has no device buffers"
+    assert M.status_string(0) == "ok"
+    with pytest.raises(M.MackoError):
+        M.set_tuning("no_such_knob", 1)
+    with pytest.raises(M.MackoError):
+        M.set_tuning("spmv_block", 100)
+    M.set_tuning("spmv_block", 256)
+    assert M.get_tuning("spmv_block") == 256
+    M.set_tuning("spmv_block", 0)
+    lib.macko_destroy(None)
+
+
+def test_padding_bound_reported_for_llama_like_rows():
+    W = wl.half_row_matrix(64, 4096, 77)
+    m = M.encode(W)
+    r = m.report
+    assert r.nnz == 64 * 2048 and r.density == 0.5
+    assert r.effd_best <= r.effd <= r.effd_worst
+    assert r.padding_entries <= 64 * 4096 * 0.5 / 16
