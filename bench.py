@@ -146,6 +146,11 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time the 36864x12288 sparsity sweep")
     ap.add_argument("--stack", action="store_true", help="also time the Llama2-13B-shaped 32-layer stack")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter probe for rocprofv3 --pmc: a 1 GiB device copy of known size, then a "
+                         "few cold launches of every kernel of the step; prints no JSON line")
+    ap.add_argument("--probe-sweep", type=int, default=None, metavar="S",
+                    help="counter probe: a few cold launches on the 36864x12288 matrix at S %% sparsity; no JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
@@ -162,6 +167,15 @@ def main():
     stream_ptr = int(torch.cuda.current_stream().cuda_stream)
     props = torch.cuda.get_device_properties(0)
     log(f"device: {props.name}, {props.multi_processor_count} CUs, {props.total_memory / 2**30:.0f} GiB")
+
+    if args.probe_sweep is not None:
+        case = wl.config3(args.probe_sweep)
+        so = SparseOp(M, torch, case, copies=2)
+        do = DenseOp(M, torch, case, copies=2)
+        ts = time_single_op(torch, so, stream_ptr, 2, 8)
+        td = time_single_op(torch, do, stream_ptr, 2, 8)
+        log(f"probe-sweep {args.probe_sweep}%: spmv {ts * 1e6:.1f} us, dense gemv {td * 1e6:.1f} us (10 launches each)")
+        return
 
     # ---- workload: one Llama2-7B-shaped layer at 50 % ------------------------
     t0 = time.perf_counter()
@@ -189,6 +203,20 @@ def main():
                     if st != 0:
                         raise RuntimeError(f"launch failed with status {st}")
         return step
+
+    if args.probe:
+        # known traffic for scaling the counters: 1 GiB read + 1 GiB written per copy
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        for i in range(2 * n_layers):
+            make_step(sparse_ops)(i)
+            make_step(dense_ops)(i)
+        torch.cuda.synchronize()
+        log("probe done: 3 copies of 1 GiB, then", 2 * n_layers, "sparse and dense steps")
+        return
 
     torch.cuda.synchronize()
     t_sparse = time_region(torch, make_step(sparse_ops), args.warmup, args.steps)
@@ -218,12 +246,18 @@ def main():
     # dominant kernel of the step: the wave-per-row SpMV kernel (all seven launches)
     avg_launch_s = t_sparse / (args.steps * launches_per_step)
     avg_launch_bytes = layer_macko_bytes / launches_per_step
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "spmv_wave_row_kernel_llama2_7b_layer_hbm_traffic.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(float(line.split(":")[1]))
     roofline = {
         "bound": "hbm", "kernel": "spmv_wave_row_kernel",
         "achieved": round(avg_launch_bytes / avg_launch_s / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(avg_launch_bytes / avg_launch_s / 1e9 / HBM_PEAK_GBPS, 4),
         "avg_launch_us": round(avg_launch_s * 1e6, 3), "bytes_per_launch": int(avg_launch_bytes),
-        "traffic": None,
+        "traffic": traffic,
     }
 
     extra = {}

@@ -77,28 +77,68 @@ __device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
   return (float)__builtin_bit_cast(_Float16, b);
 }
 
-// Copy x (fp16[cols], global) into the LDS layout described above.  Must be
-// called by every thread of the workgroup; ends with a barrier.
-__device__ __forceinline__ void stage_x_to_lds(unsigned char* lds, const uint16_t* __restrict__ x,
-                                               int cols, int lds_bytes) {
+// Staging of x (fp16[cols], global) into the LDS layout described above, split
+// in two so that a kernel can put its own first loads between the halves:
+// stage_x_begin only issues global loads into registers (up to XR 16-byte chunks
+// per thread, fast path for a 16-byte aligned x); stage_x_finish writes them to
+// LDS, copies whatever did not fit (or everything, for an unaligned x), zeroes
+// the guards and ends with a barrier.  Both must be called by every thread.
+constexpr int kXStageRegs = 4;
+
+struct XStage {
+  uint4 r[kXStageRegs];
+};
+
+// The loads go through a raw buffer descriptor that covers exactly the whole
+// chunks of x: threads whose chunk lies beyond it (and every thread, when x is
+// not 16-byte aligned and the descriptor is made empty) get zeros back without
+// touching memory.  The loads are therefore unconditional, which keeps the
+// compiler's count of outstanding loads exact.
+__device__ __forceinline__ void stage_x_begin(XStage& st, const uint16_t* __restrict__ x, int cols) {
+  const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+  const int bytes = aligned ? (cols >> 3) * 16 : 0;   // whole 16-byte chunks of x
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x), 0, bytes, 0x00020000);
+#pragma unroll
+  for (int k = 0; k < kXStageRegs; ++k) {
+    const int i = (int)threadIdx.x + k * (int)blockDim.x;
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, i * 16, 0, 0);
+    st.r[k] = make_uint4(v[0], v[1], v[2], v[3]);
+  }
+}
+
+__device__ __forceinline__ void stage_x_finish(unsigned char* lds, const XStage& st,
+                                               const uint16_t* __restrict__ x, int cols, int lds_bytes) {
   const int tid = threadIdx.x;
   const int nt = blockDim.x;
   const uint4 zero = make_uint4(0, 0, 0, 0);
   uint4* lds16 = reinterpret_cast<uint4*>(lds);
-  for (int i = tid; i < kFrontPad / 16; i += nt) lds16[i] = zero;
-  const int chunks = cols >> 3;                       // whole 16-byte chunks of x
+  const int chunks = cols >> 3;
   const int tail_chunks = (cols + 7) >> 3;            // chunks touched by x
+  for (int i = tid; i < kFrontPad / 16; i += nt) lds16[i] = zero;
   for (int i = kFrontPad / 16 + tail_chunks + tid; i < lds_bytes / 16; i += nt) lds16[i] = zero;
   uint16_t* xs = reinterpret_cast<uint16_t*>(lds + kFrontPad);
+  uint4* xd = reinterpret_cast<uint4*>(xs);
   if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
     const uint4* xg = reinterpret_cast<const uint4*>(x);
-    uint4* xd = reinterpret_cast<uint4*>(xs);
-    for (int i = tid; i < chunks; i += nt) xd[i] = xg[i];
+#pragma unroll
+    for (int k = 0; k < kXStageRegs; ++k) {
+      const int i = tid + k * nt;
+      if (i < chunks) xd[i] = st.r[k];
+    }
+    for (int i = tid + kXStageRegs * nt; i < chunks; i += nt) xd[i] = xg[i];
     for (int i = chunks * 8 + tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
   } else {
     for (int i = tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
   }
   __syncthreads();
+}
+
+__device__ __forceinline__ void stage_x_to_lds(unsigned char* lds, const uint16_t* __restrict__ x,
+                                               int cols, int lds_bytes) {
+  XStage st;
+  stage_x_begin(st, x, cols);
+  stage_x_finish(lds, st, x, cols, lds_bytes);
 }
 
 }  // namespace macko

@@ -25,7 +25,6 @@ gemv_wave_row_kernel(const uint4* __restrict__ W, const uint16_t* __restrict__ x
   const int row_begin = blockIdx.x * rows_per_wg;
   const int row_end = min(rows, row_begin + rows_per_wg);
   const int nwaves = blockDim.x >> 6;
-  stage_x_to_lds(lds, x, cols, lds_bytes);
   const uint4* xs = reinterpret_cast<const uint4*>(lds + kFrontPad);
 
   const int lane = threadIdx.x & 63;
@@ -37,35 +36,48 @@ gemv_wave_row_kernel(const uint4* __restrict__ W, const uint16_t* __restrict__ x
   const int wrow_begin = min(row_end, row_begin + wave * per_wave);
   const int wrow_end = min(row_end, wrow_begin + per_wave);
 
-  for (int blk = wrow_begin; blk < wrow_end; blk += 64) {
-    const int nb = min(64, wrow_end - blk);
-    float yv = 0.0f;                                   // lane i: result of row blk + i
-    int ld_i = 0, ld_step = 0;                         // load side
-    int cp_i = 0, cp_step = 0;                         // compute side
-    const uint4* src = W + (int64_t)blk * ld8;         // row the next load reads from
-    const uint4* src_next = src;
-    int chunk = min(lane, c8 - 1);
-    uint4 q[RING];
-    auto issue = [&](int j) {
-      src = src_next;
-      if (ld_i < nb) {
-        chunk = min(ld_step * 64 + lane, c8 - 1);
-        if (++ld_step == nsteps) {
-          ld_step = 0;
-          if (++ld_i < nb) src_next = src + ld8;
-        }
+  int blk = wrow_begin;
+  int nb = max(0, min(64, wrow_end - blk));
+  int ld_i = 0, ld_step = 0;                           // load side
+  int cp_i = 0, cp_step = 0;                           // compute side
+  const uint4* src = W;                                // row the next load reads from
+  const uint4* src_next = W;
+  int chunk = min(lane, c8 - 1);
+  uint4 q[RING];
+  auto issue = [&](int j) {
+    src = src_next;
+    if (ld_i < nb) {
+      chunk = min(ld_step * 64 + lane, c8 - 1);
+      if (++ld_step == nsteps) {
+        ld_step = 0;
+        if (++ld_i < nb) src_next = src + ld8;
       }
-      q[j] = src[chunk];                               // padding items re-read the previous address
-    };
+    }
+    q[j] = src[chunk];                                 // padding items re-read the previous address
+  };
+  auto open_block = [&]() {
+    ld_i = ld_step = cp_i = cp_step = 0;
+    if (nb > 0) src_next = W + (int64_t)blk * ld8;
 #pragma unroll
     for (int j = 0; j < RING; ++j) issue(j);
+  };
 
+  // x is requested first, then the first weight loads go out, and only then is
+  // x written to LDS: the stream is already in flight behind the barrier
+  XStage xst;
+  stage_x_begin(xst, x, cols);
+  open_block();
+  stage_x_finish(lds, xst, x, cols, lds_bytes);        // ends with a barrier
+
+  while (true) {
+    float yv = 0.0f;                                   // lane i: result of row blk + i
     float acc = 0.0f;
     while (cp_i < nb) {
 #pragma unroll
       for (int j = 0; j < RING; ++j) {
         uint4 w = q[j];
         const bool live = cp_i < nb;
+        if (!live) cp_step = 0;
         const int idx = cp_step * 64 + lane;
         if (!live || (ragged && cp_step == nsteps - 1)) {
           const bool in = live && idx < c8;
@@ -88,21 +100,21 @@ gemv_wave_row_kernel(const uint4* __restrict__ W, const uint16_t* __restrict__ x
 #undef MACKO_LO
 #undef MACKO_HI
         issue(j);
-        if (live) {
-          if (++cp_step == nsteps) {
-            const float total = wave_sum_to_last_lane(acc);
-            const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), 63);
-            yv = lane == cp_i ? __builtin_bit_cast(float, tbits) : yv;
-            acc = 0.0f;
-            cp_step = 0;
-            ++cp_i;
-          }
-        } else {
+        if (live && ++cp_step == nsteps) {
+          const float total = wave_sum_to_last_lane(acc);
+          const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), 63);
+          yv = lane == cp_i ? __builtin_bit_cast(float, tbits) : yv;
+          acc = 0.0f;
           cp_step = 0;
+          ++cp_i;
         }
       }
     }
     if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
+    blk += 64;
+    if (blk >= wrow_end) break;
+    nb = min(64, wrow_end - blk);
+    open_block();
   }
 }
 
@@ -138,7 +150,7 @@ int launch_dense_gemv(const void* W, int64_t rows, int64_t cols, int64_t ld, con
     const int nwaves = block / 64;
     int64_t rpw = t.gemv_rows_per_wg;
     if (rpw == 0) {
-      const int64_t target_wgs = (int64_t)cus * 4;
+      const int64_t target_wgs = (int64_t)cus * 16;
       rpw = std::max<int64_t>((rows + target_wgs - 1) / target_wgs, nwaves);
     }
     const int64_t grid = (rows + rpw - 1) / rpw;

@@ -116,6 +116,12 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
 //  - after the row end (last step only): their codes and values are cleared.
 // No load ever leaves [0, alloc_nnz).
 // ---------------------------------------------------------------------------
+// x element whose plain LDS offset relative to the start of x is q (q may be
+// slightly negative or past the end: both land in the zero guards).
+__device__ __forceinline__ float gather_x(const unsigned char* xbase, int q) {
+  return f16_bits_to_f32(*reinterpret_cast<const uint16_t*>(xbase + q));
+}
+
 struct RowCursor {
   int i;               // row index within the block (== nb when exhausted)
   uint32_t start, end; // its entry range
@@ -123,7 +129,8 @@ struct RowCursor {
   int nsteps, step;
 };
 
-// Move the cursor to the first non-empty row at or after cur.i.
+// Move the cursor to the first non-empty row at or after cur.i.  Only lanes
+// below nb hold pointers of the block's rows; others are never selected.
 __device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t rp_lo, uint32_t rp_hi) {
   cur.start = cur.end = 0;
   while (cur.i < nb) {
@@ -148,53 +155,56 @@ spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-
-  if (row_ptr[row_end] == row_ptr[row_begin]) {        // nothing stored in this block of rows
-    for (int r = row_begin + (int)threadIdx.x; r < row_end; r += blockDim.x) y[r] = 0;
-    return;
-  }
-  stage_x_to_lds(lds, x, cols, lds_bytes);             // ends with a barrier
-
-  // byte address of "position 0" minus the 2 that turns a position into a column
-  const unsigned char* xbase = lds + kFrontPad - 2;
+  const unsigned char* xbase = lds + kFrontPad;       // LDS address of x[0]
   const uint32_t lane8 = 8u * lane;
   const int per_wave = (row_end - row_begin + nwaves - 1) / nwaves;
   const int wrow_begin = min(row_end, row_begin + wave * per_wave);
   const int wrow_end = min(row_end, wrow_begin + per_wave);
 
-  uint32_t chunk = 0;                                  // 8-entry chunk index this lane loads next
+  uint32_t chunk = 0;      // 8-entry chunk index this lane loads next (chunk 0 exists: pad_nnz > 0)
+  int blk = wrow_begin;
+  int nb = max(0, min(64, wrow_end - blk));
+  uint32_t rp_lo = 0, rp_hi = 0;
+  RowCursor ld, cp;                                    // load side, compute side
+  uint32_t wq[RING];
+  uint4 vq[RING];
 
-  for (int blk = wrow_begin; blk < wrow_end; blk += 64) {
-    const int nb = min(64, wrow_end - blk);
-    uint32_t rp_lo = 0, rp_hi = 0;
-    if (lane < nb) {
-      rp_lo = row_ptr[blk + lane];
-      rp_hi = row_ptr[blk + lane + 1];
+  auto issue = [&](int j) {
+    if (ld.i < nb) {
+      const uint32_t e0 = ld.a0 + 512u * ld.step + lane8;
+      chunk = min(e0, ld.end - 1u) >> 3;
+      if (++ld.step == ld.nsteps) {
+        ++ld.i;
+        seek_nonempty(ld, nb, rp_lo, rp_hi);
+      }
     }
-    float yv = 0.0f;                                   // lane i: result of row blk + i
-
-    RowCursor ld, cp;                                  // load side, compute side
+    wq[j] = deltas[chunk];
+    vq[j] = values[chunk];
+  };
+  auto fetch_row_ptrs = [&]() {                        // unconditional loads, clamped to the last row
+    const int r = min(blk + lane, rows - 1);
+    rp_lo = row_ptr[r];
+    rp_hi = row_ptr[r + 1];
+  };
+  auto prime_ring = [&]() {
     ld.i = 0;
     seek_nonempty(ld, nb, rp_lo, rp_hi);
     cp = ld;
-
-    uint32_t wq[RING];
-    uint4 vq[RING];
-    auto issue = [&](int j) {
-      if (ld.i < nb) {
-        const uint32_t e0 = ld.a0 + 512u * ld.step + lane8;
-        chunk = min(e0, ld.end - 1u) >> 3;
-        if (++ld.step == ld.nsteps) {
-          ++ld.i;
-          seek_nonempty(ld, nb, rp_lo, rp_hi);
-        }
-      }
-      wq[j] = deltas[chunk];
-      vq[j] = values[chunk];
-    };
 #pragma unroll
     for (int j = 0; j < RING; ++j) issue(j);
+  };
 
+  // Start-up order: the row pointers and x are requested together; once they
+  // are in registers the first streaming loads go out, and only then is x
+  // written to LDS, so the stream is already in flight behind the barrier.
+  XStage xst;
+  fetch_row_ptrs();
+  stage_x_begin(xst, x, cols);
+  prime_ring();
+  stage_x_finish(lds, xst, x, cols, lds_bytes);        // ends with a barrier
+
+  while (true) {
+    float yv = 0.0f;                                   // lane i: result of row blk + i
     float acc = 0.0f;
     int base2 = 0;                                     // doubled position before this step (uniform)
     while (cp.i < nb) {
@@ -233,20 +243,22 @@ spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
             base2 = -(int)(((src >> (8 * (k >> 1))) & 0xFFu) + 2u * (uint32_t)(k + 1));
           }
         }
-        const uint32_t lanebase = (uint32_t)base2 + incl - tot;
-        const unsigned char* xl = xbase + lanebase;
-#define MACKO_X(k, word, m) \
-  f16_bits_to_f32(*reinterpret_cast<const uint16_t*>(xl + (((word) >> (8 * (m))) & 0xFFu) + 2 * ((k) + 1)))
+        // byte m of E2 / P2: doubled position of entry 2m / 2m+1 relative to the lane,
+        // minus 2 (so that the largest value, 240 + 14, still fits a byte)
+        const uint32_t E2 = E + 0x0C080400u;
+        const uint32_t P2 = P + 0x0E0A0602u;
+        const int lanebase = base2 + (int)(incl - tot);   // byte offset in x of the lane's chunk start
+#define MACKO_X(word, m) gather_x(xbase, lanebase + (int)(((word) >> (8 * (m))) & 0xFFu))
 #define MACKO_LO(u) f16_bits_to_f32((uint16_t)((u) & 0xFFFFu))
 #define MACKO_HI(u) f16_bits_to_f32((uint16_t)((u) >> 16))
-        acc = fmaf(MACKO_LO(v.x), MACKO_X(0, E, 0), acc);
-        acc = fmaf(MACKO_HI(v.x), MACKO_X(1, P, 0), acc);
-        acc = fmaf(MACKO_LO(v.y), MACKO_X(2, E, 1), acc);
-        acc = fmaf(MACKO_HI(v.y), MACKO_X(3, P, 1), acc);
-        acc = fmaf(MACKO_LO(v.z), MACKO_X(4, E, 2), acc);
-        acc = fmaf(MACKO_HI(v.z), MACKO_X(5, P, 2), acc);
-        acc = fmaf(MACKO_LO(v.w), MACKO_X(6, E, 3), acc);
-        acc = fmaf(MACKO_HI(v.w), MACKO_X(7, P, 3), acc);
+        acc = fmaf(MACKO_LO(v.x), MACKO_X(E2, 0), acc);
+        acc = fmaf(MACKO_HI(v.x), MACKO_X(P2, 0), acc);
+        acc = fmaf(MACKO_LO(v.y), MACKO_X(E2, 1), acc);
+        acc = fmaf(MACKO_HI(v.y), MACKO_X(P2, 1), acc);
+        acc = fmaf(MACKO_LO(v.z), MACKO_X(E2, 2), acc);
+        acc = fmaf(MACKO_HI(v.z), MACKO_X(P2, 2), acc);
+        acc = fmaf(MACKO_LO(v.w), MACKO_X(E2, 3), acc);
+        acc = fmaf(MACKO_HI(v.w), MACKO_X(P2, 3), acc);
 #undef MACKO_X
 #undef MACKO_LO
 #undef MACKO_HI
@@ -263,7 +275,18 @@ spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
       }
     }
     if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
+    blk += 64;
+    if (blk >= wrow_end) break;
+    nb = min(64, wrow_end - blk);
+    fetch_row_ptrs();
+    prime_ring();
   }
+}
+
+// y = 0 for a matrix without stored entries
+__global__ void __launch_bounds__(256) zero_y_kernel(uint16_t* __restrict__ y, int rows) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows) y[i] = 0;
 }
 
 template <class K>
@@ -290,6 +313,13 @@ int launch_spmv(const uint16_t* values, const uint8_t* deltas, const uint32_t* r
   const bool lds_ok = lds_bytes <= kMaxLdsBytes;
   const int64_t avg = rows > 0 ? pad_nnz / rows : 0;
 
+  if (pad_nnz == 0) {                                  // nothing stored: y = 0
+    hipLaunchKernelGGL(zero_y_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<uint16_t*>(y), (int)rows);
+    hipError_t e0 = hipGetLastError();
+    return e0 == hipSuccess ? MACKO_OK : hip_fail(e0);
+  }
+
   int kernel = (int)t.spmv_kernel;
   if (kernel == 0) kernel = (avg >= 384 && lds_ok) ? 2 : 1;
   if (kernel == 2 && !lds_ok) return MACKO_E_UNSUPPORTED;
@@ -304,11 +334,13 @@ int launch_spmv(const uint16_t* values, const uint8_t* deltas, const uint32_t* r
     const int nwaves = block / 64;
     int64_t rpw = t.spmv_rows_per_wg;
     if (rpw == 0) {
-      // enough workgroups to keep every CU busy with a few of them, but each
-      // long enough to amortise staging x
-      const int64_t target_wgs = (int64_t)cus * 4;
-      rpw = (rows + target_wgs - 1) / target_wgs;
-      rpw = std::max<int64_t>(rpw, nwaves);
+      // A wavefront should own about 16 steps of work so that its load pipeline
+      // runs in steady state (short rows: several rows per wavefront), but never
+      // so much that fewer than ~16 wavefronts per CU remain.
+      const int64_t steps_per_row = std::max<int64_t>(1, (avg + 511) / 512);
+      const int64_t want = (16 + steps_per_row - 1) / steps_per_row;
+      const int64_t cap = std::max<int64_t>(1, rows / ((int64_t)cus * 16));
+      rpw = std::min(want, cap) * nwaves;
     }
     const int64_t grid = (rows + rpw - 1) / rpw;
     auto kfn = spmv_wave_row_kernel<4>;
