@@ -227,6 +227,46 @@ def main():
     log(f"layer: MACKO {ms_per_step * 1e3:.1f} us/step ({gbps:.0f} GB/s), dense "
         f"{t_dense / args.steps * 1e6:.1f} us/step ({dense_gbps:.0f} GB/s), speedup {t_dense / t_sparse:.3f}")
 
+    # ---- the same layer with grouped launches in dependency order --------------
+    # {q,k,v} -> {o} -> {gate,up} -> {down}: products that do not depend on each other share a launch
+    def grouped_steps(kind):
+        steps = []
+        for layer in range(n_layers):
+            def pick(tag, ks):
+                op = (sparse_ops if kind == "sparse" else dense_ops)[tag]
+                mult = dict(layer_plan)[tag]
+                if kind == "sparse":
+                    return [op.handles[layer * mult + k] for k in ks], [op.x] * len(ks), \
+                           [torch.empty_like(op.y) for _ in ks]
+                return [op.W[layer * mult + k] for k in ks], [op.x] * len(ks), [torch.empty_like(op.y) for _ in ks]
+            Group = M.SpmvGroup if kind == "sparse" else M.GemvGroup
+            steps.append([Group(*pick("qkvo", [0, 1, 2])), Group(*pick("qkvo", [3])),
+                          Group(*pick("gate_up", [0, 1])), Group(*pick("down", [0]))])
+        return steps
+
+    def make_grouped_step(steps):
+        def step(i):
+            for g in steps[i % n_layers]:
+                st = g.launch_raw(stream_ptr)
+                if st != 0:
+                    raise RuntimeError(f"grouped launch failed with status {st}")
+        return step
+
+    gs, gd = grouped_steps("sparse"), grouped_steps("dense")
+    tg_sparse = time_region(torch, make_grouped_step(gs), args.warmup, args.steps)
+    tg_dense = time_region(torch, make_grouped_step(gd), args.warmup, args.steps)
+    grouped = {
+        "launches_per_step": 4, "order": "{q,k,v} -> {o} -> {gate,up} -> {down}",
+        "macko_ms_per_step": round(tg_sparse / args.steps * 1e3, 5),
+        "dense_ms_per_step": round(tg_dense / args.steps * 1e3, 5),
+        "macko_GBps": round(layer_macko_bytes / (tg_sparse / args.steps) / 1e9, 1),
+        "dense_GBps": round(layer_dense_bytes / (tg_dense / args.steps) / 1e9, 1),
+        "frac_of_hbm_peak": round(layer_macko_bytes / (tg_sparse / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
+        "speedup_vs_dense_gemv": round(tg_dense / tg_sparse, 3),
+    }
+    log(f"grouped (4 launches): {grouped}")
+    del gs, gd
+
     # ---- per-shape numbers (cold rotation over the same copies) ---------------
     per_shape = {}
     n_single = max(50, args.steps // 2)
@@ -339,6 +379,7 @@ def main():
         "speedup_vs_dense_gemv": round(t_dense / t_sparse, 3),
         "memory_reduction_vs_dense": round(layer_dense_bytes / layer_macko_bytes, 3),
         "per_shape": per_shape,
+        "grouped_launches": grouped,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -5,16 +5,20 @@ arithmetic step runs inside the library's HIP kernels; this package only
 marshals arguments.  PyTorch supplies device memory and streams.
 """
 from .binding import (  # noqa: F401
+    GemvGroup,
     MackoError,
     MackoMatrix,
     Report,
+    SpmvGroup,
     dense_gemv,
+    dense_gemv_group,
     encode,
     encode_device,
     get_tuning,
     library_path,
     load_library,
     set_tuning,
+    spmv_group,
     status_string,
     wrap_device,
 )

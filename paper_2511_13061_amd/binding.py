@@ -15,7 +15,7 @@ _lib = None
 EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_spmv", "macko_dense_gemv", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -95,6 +95,9 @@ def load_library():
     lib.macko_decode.argtypes = [vp, vp, i64]
     lib.macko_spmv.argtypes = [vp, vp, vp, vp]
     lib.macko_dense_gemv.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    vpp = ctypes.POINTER(vp)
+    lib.macko_spmv_group.argtypes = [ci, vpp, vpp, vpp, vp]
+    lib.macko_dense_gemv_group.argtypes = [ci, vpp, i64p, i64p, i64p, vpp, vpp, vp]
     lib.macko_destroy.argtypes = [vp]
     lib.macko_destroy.restype = None
     lib.macko_status_string.argtypes = [ci]
@@ -301,3 +304,64 @@ def dense_gemv(W_dev, x_dev, y_dev=None, stream=None):
                                            _dev_ptr(x_dev), _dev_ptr(y_dev), _stream_ptr(stream)),
            "macko_dense_gemv")
     return y_dev
+
+
+class SpmvGroup:
+    """Pre-marshalled arguments of macko_spmv_group for a fixed set of products."""
+
+    def __init__(self, matrices, xs, ys):
+        n = len(matrices)
+        self.n = n
+        self._keep = (list(matrices), list(xs), list(ys))
+        VP = ctypes.c_void_p * n
+        self._h = VP(*[m._h.value for m in matrices])
+        self._x = VP(*[_dev_ptr(x) for x in xs])
+        self._y = VP(*[_dev_ptr(y) for y in ys])
+
+    def launch_raw(self, stream_ptr: int) -> int:
+        return load_library().macko_spmv_group(self.n, self._h, self._x, self._y, stream_ptr)
+
+    def launch(self, stream=None) -> None:
+        _check(self.launch_raw(_stream_ptr(stream)), "macko_spmv_group")
+
+
+class GemvGroup:
+    """Pre-marshalled arguments of macko_dense_gemv_group."""
+
+    def __init__(self, Ws, xs, ys):
+        n = len(Ws)
+        self.n = n
+        self._keep = (list(Ws), list(xs), list(ys))
+        VP = ctypes.c_void_p * n
+        I64 = ctypes.c_int64 * n
+        self._W = VP(*[_dev_ptr(W) for W in Ws])
+        self._rows = I64(*[W.shape[0] for W in Ws])
+        self._cols = I64(*[W.shape[1] for W in Ws])
+        self._ld = I64(*[W.stride(0) for W in Ws])
+        self._x = VP(*[_dev_ptr(x) for x in xs])
+        self._y = VP(*[_dev_ptr(y) for y in ys])
+
+    def launch_raw(self, stream_ptr: int) -> int:
+        return load_library().macko_dense_gemv_group(self.n, self._W, self._rows, self._cols, self._ld,
+                                                     self._x, self._y, stream_ptr)
+
+    def launch(self, stream=None) -> None:
+        _check(self.launch_raw(_stream_ptr(stream)), "macko_dense_gemv_group")
+
+
+def spmv_group(matrices, xs, ys=None, stream=None):
+    """macko_spmv_group: independent products y_i = W_i x_i in one launch."""
+    import torch
+    if ys is None:
+        ys = [torch.empty(m.rows, dtype=torch.float16, device=x.device) for m, x in zip(matrices, xs)]
+    SpmvGroup(matrices, xs, ys).launch(stream)
+    return ys
+
+
+def dense_gemv_group(Ws, xs, ys=None, stream=None):
+    """macko_dense_gemv_group."""
+    import torch
+    if ys is None:
+        ys = [torch.empty(W.shape[0], dtype=torch.float16, device=W.device) for W in Ws]
+    GemvGroup(Ws, xs, ys).launch(stream)
+    return ys

@@ -16,13 +16,31 @@ namespace {
 // and cross row boundaries, every item issues exactly one load, and the results
 // of up to 64 rows are collected in a register and stored with one coalesced
 // store.
+// One matrix of a grouped launch: workgroups [wg_begin, next wg_begin) work on it.
+struct GemvMat {
+  const uint4* W;
+  const uint16_t* x;
+  uint16_t* y;
+  int64_t ld8;
+  int rows, cols, rows_per_wg, wg_begin;
+};
+struct GemvGroupArgs {
+  int n;
+  GemvMat m[kMaxGroup];
+};
+
 template <int RING>
-__global__ void __launch_bounds__(1024)
-gemv_wave_row_kernel(const uint4* __restrict__ W, const uint16_t* __restrict__ x,
-                     uint16_t* __restrict__ y, int rows, int cols, int64_t ld8, int rows_per_wg,
-                     int lds_bytes) {
+__global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs g) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int row_begin = blockIdx.x * rows_per_wg;
+  int mi = 0;
+  for (int i = 1; i < g.n; ++i) mi = (int)blockIdx.x >= g.m[i].wg_begin ? i : mi;
+  const uint4* __restrict__ W = g.m[mi].W;
+  const uint16_t* __restrict__ x = g.m[mi].x;
+  uint16_t* __restrict__ y = g.m[mi].y;
+  const int64_t ld8 = g.m[mi].ld8;
+  const int rows = g.m[mi].rows, cols = g.m[mi].cols, rows_per_wg = g.m[mi].rows_per_wg;
+  const int lds_bytes = (int)lds_bytes_for(cols);
+  const int row_begin = ((int)blockIdx.x - g.m[mi].wg_begin) * rows_per_wg;
   const int row_end = min(rows, row_begin + rows_per_wg);
   const int nwaves = blockDim.x >> 6;
   const uint4* xs = reinterpret_cast<const uint4*>(lds + kFrontPad);
@@ -136,40 +154,58 @@ gemv_generic_kernel(const uint16_t* __restrict__ W, const uint16_t* __restrict__
 
 }  // namespace
 
-int launch_dense_gemv(const void* W, int64_t rows, int64_t cols, int64_t ld, const void* x, void* y,
-                      hipStream_t stream) {
+int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
+  if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;
   const Tuning& t = tuning();
   const int cus = device_cu_count();
-  const int64_t lds_bytes = lds_bytes_for(cols);
-  const bool fast = cols > 0 && (cols % 8 == 0) && (ld % 8 == 0) &&
-                    (reinterpret_cast<uintptr_t>(W) & 15) == 0 && lds_bytes <= 160 * 1024 - 64;
-  const uint16_t* xp = static_cast<const uint16_t*>(x);
-  uint16_t* yp = static_cast<uint16_t*>(y);
-  if (fast) {
-    const int block = t.gemv_block ? (int)t.gemv_block : 512;
-    const int nwaves = block / 64;
+  const int block = t.gemv_block ? (int)t.gemv_block : 512;
+  const int nwaves = block / 64;
+  GemvGroupArgs args{};
+  int64_t total_wgs = 0, max_lds = 0;
+  for (int i = 0; i < n; ++i) {
+    const GemvProblem& p = problems[i];
+    if (p.rows == 0) continue;
+    const int64_t lds_bytes = lds_bytes_for(p.cols);
+    const bool fast = p.cols > 0 && (p.cols % 8 == 0) && (p.ld % 8 == 0) &&
+                      (reinterpret_cast<uintptr_t>(p.W) & 15) == 0 && lds_bytes <= 160 * 1024 - 64;
+    if (!fast) {                                        // any shape / alignment: own launch
+      const int64_t grid = std::min<int64_t>((p.rows + 3) / 4, (int64_t)cus * 8);
+      hipLaunchKernelGGL(gemv_generic_kernel, dim3((unsigned)std::max<int64_t>(grid, 1)), dim3(256), 0,
+                         stream, static_cast<const uint16_t*>(p.W), static_cast<const uint16_t*>(p.x),
+                         static_cast<uint16_t*>(p.y), (int)p.rows, (int)p.cols, p.ld);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return hip_fail(e);
+      continue;
+    }
     int64_t rpw = t.gemv_rows_per_wg;
     if (rpw == 0) {
       const int64_t target_wgs = (int64_t)cus * 16;
-      rpw = std::max<int64_t>((rows + target_wgs - 1) / target_wgs, nwaves);
+      rpw = std::max<int64_t>((p.rows + target_wgs - 1) / target_wgs, nwaves);
     }
-    const int64_t grid = (rows + rpw - 1) / rpw;
+    GemvMat& m = args.m[args.n++];
+    m.W = static_cast<const uint4*>(p.W);
+    m.x = static_cast<const uint16_t*>(p.x);
+    m.y = static_cast<uint16_t*>(p.y);
+    m.ld8 = p.ld / 8;
+    m.rows = (int)p.rows;
+    m.cols = (int)p.cols;
+    m.rows_per_wg = (int)rpw;
+    m.wg_begin = (int)total_wgs;
+    total_wgs += (p.rows + rpw - 1) / rpw;
+    max_lds = std::max(max_lds, lds_bytes);
+    if (total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  }
+  if (args.n > 0) {
     auto kfn = gemv_wave_row_kernel<4>;
-    if (lds_bytes > 64 * 1024) {
+    if (max_lds > 64 * 1024) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
       if (e != hipSuccess) return hip_fail(e);
     }
-    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds_bytes, stream,
-                       static_cast<const uint4*>(W), xp, yp, (int)rows, (int)cols, ld / 8, (int)rpw,
-                       (int)lds_bytes);
-  } else {
-    const int64_t grid = std::min<int64_t>((rows + 3) / 4, (int64_t)cus * 8);
-    hipLaunchKernelGGL(gemv_generic_kernel, dim3((unsigned)std::max<int64_t>(grid, 1)), dim3(256), 0,
-                       stream, static_cast<const uint16_t*>(W), xp, yp, (int)rows, (int)cols, ld);
+    hipLaunchKernelGGL(kfn, dim3((unsigned)total_wgs), dim3(block), (size_t)max_lds, stream, args);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
   }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return hip_fail(e);
   return MACKO_OK;
 }
 

@@ -343,27 +343,58 @@ int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld) {
   return MACKO_OK;
 }
 
-int macko_spmv(macko_handle_t h, const void* x_dev, void* y_dev, void* stream) {
-  if (!h) return MACKO_E_INVALID_ARG;
-  if (!h->bound) return MACKO_E_NOT_BOUND;
-  if (h->rows == 0) return MACKO_OK;
-  if (!y_dev || (!x_dev && h->cols > 0)) return MACKO_E_INVALID_ARG;
+static int check_vec_ptrs(const void* x_dev, const void* y_dev, int64_t cols) {
+  if (!y_dev || (!x_dev && cols > 0)) return MACKO_E_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(x_dev) & 1) || (reinterpret_cast<uintptr_t>(y_dev) & 1))
     return MACKO_E_INVALID_ARG;
-  return macko::launch_spmv(h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
-                            h->report.max_row_entries, x_dev, y_dev, static_cast<hipStream_t>(stream));
+  return MACKO_OK;
+}
+
+int macko_spmv(macko_handle_t h, const void* x_dev, void* y_dev, void* stream) {
+  return macko_spmv_group(1, &h, &x_dev, &y_dev, stream);
+}
+
+int macko_spmv_group(int n, const macko_handle_t* handles, const void* const* x_dev, void* const* y_dev,
+                     void* stream) {
+  if (n < 1 || n > MACKO_MAX_GROUP || !handles || !x_dev || !y_dev) return MACKO_E_INVALID_ARG;
+  macko::SpmvProblem p[MACKO_MAX_GROUP];
+  int m = 0;
+  for (int i = 0; i < n; ++i) {
+    macko_handle_t h = handles[i];
+    if (!h) return MACKO_E_INVALID_ARG;
+    if (!h->bound) return MACKO_E_NOT_BOUND;
+    if (h->rows == 0) continue;
+    int st = check_vec_ptrs(x_dev[i], y_dev[i], h->cols);
+    if (st != MACKO_OK) return st;
+    p[m++] = macko::SpmvProblem{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
+                                x_dev[i], y_dev[i]};
+  }
+  if (m == 0) return MACKO_OK;
+  return macko::launch_spmv_group(m, p, static_cast<hipStream_t>(stream));
 }
 
 int macko_dense_gemv(const void* W_dev, int64_t rows, int64_t cols, int64_t ld, const void* x_dev,
                      void* y_dev, void* stream) {
-  if (rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
-  if (rows == 0) return MACKO_OK;
-  if (!y_dev || (cols > 0 && (!W_dev || !x_dev))) return MACKO_E_INVALID_ARG;
-  if ((reinterpret_cast<uintptr_t>(x_dev) & 1) || (reinterpret_cast<uintptr_t>(y_dev) & 1) ||
-      (reinterpret_cast<uintptr_t>(W_dev) & 1))
+  return macko_dense_gemv_group(1, &W_dev, &rows, &cols, &ld, &x_dev, &y_dev, stream);
+}
+
+int macko_dense_gemv_group(int n, const void* const* W_dev, const int64_t* rows, const int64_t* cols,
+                           const int64_t* ld, const void* const* x_dev, void* const* y_dev, void* stream) {
+  if (n < 1 || n > MACKO_MAX_GROUP || !W_dev || !rows || !cols || !ld || !x_dev || !y_dev)
     return MACKO_E_INVALID_ARG;
-  if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
-  return macko::launch_dense_gemv(W_dev, rows, cols, ld, x_dev, y_dev, static_cast<hipStream_t>(stream));
+  macko::GemvProblem p[MACKO_MAX_GROUP];
+  int m = 0;
+  for (int i = 0; i < n; ++i) {
+    if (rows[i] < 0 || cols[i] < 0 || ld[i] < cols[i]) return MACKO_E_INVALID_ARG;
+    if (rows[i] == 0) continue;
+    int st = check_vec_ptrs(x_dev[i], y_dev[i], cols[i]);
+    if (st != MACKO_OK) return st;
+    if (cols[i] > 0 && (!W_dev[i] || (reinterpret_cast<uintptr_t>(W_dev[i]) & 1))) return MACKO_E_INVALID_ARG;
+    if (cols[i] >= (int64_t{1} << 31) || rows[i] >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+    p[m++] = macko::GemvProblem{W_dev[i], rows[i], cols[i], ld[i], x_dev[i], y_dev[i]};
+  }
+  if (m == 0) return MACKO_OK;
+  return macko::launch_gemv_group(m, p, static_cast<hipStream_t>(stream));
 }
 
 void macko_destroy(macko_handle_t h) {
@@ -399,6 +430,7 @@ static int64_t* tuning_slot(const char* name) {
   if (n == "spmv_lanes") return &t.spmv_lanes;
   if (n == "spmv_block") return &t.spmv_block;
   if (n == "spmv_rows_per_wg") return &t.spmv_rows_per_wg;
+  if (n == "spmv_ring") return &t.spmv_ring;
   if (n == "gemv_block") return &t.gemv_block;
   if (n == "gemv_rows_per_wg") return &t.gemv_rows_per_wg;
   return nullptr;
@@ -409,6 +441,7 @@ int macko_set_tuning(const char* name, int64_t value) {
   if (!slot || value < 0) return MACKO_E_INVALID_ARG;
   const std::string n(name);
   if (n == "spmv_kernel" && value > 2) return MACKO_E_INVALID_ARG;
+  if (n == "spmv_ring" && value != 0 && value != 2 && value != 3 && value != 4 && value != 8) return MACKO_E_INVALID_ARG;
   if (n == "spmv_lanes" && value != 0 && value != 16 && value != 32 && value != 64) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_block" || n == "gemv_block") && value != 0 && (value % 64 != 0 || value > 1024))
     return MACKO_E_INVALID_ARG;

@@ -19,6 +19,7 @@ struct Tuning {
   int64_t spmv_lanes = 0;
   int64_t spmv_block = 0;
   int64_t spmv_rows_per_wg = 0;
+  int64_t spmv_ring = 0;
   int64_t gemv_block = 0;
   int64_t gemv_rows_per_wg = 0;
 };
@@ -35,11 +36,25 @@ int hip_fail(hipError_t e);
 int device_cu_count();
 
 // launchers implemented in the .hip files; all return a macko_status
-int launch_spmv(const uint16_t* values, const uint8_t* deltas, const uint32_t* row_ptr, int64_t rows,
-                int64_t cols, int64_t pad_nnz, int64_t max_row_entries, const void* x, void* y,
-                hipStream_t stream);
-int launch_dense_gemv(const void* W, int64_t rows, int64_t cols, int64_t ld, const void* x, void* y,
-                      hipStream_t stream);
+constexpr int kMaxGroup = 8;            // MACKO_MAX_GROUP
+
+struct SpmvProblem {
+  const uint16_t* values;
+  const uint8_t* deltas;
+  const uint32_t* row_ptr;
+  int64_t rows, cols, pad_nnz;
+  const void* x;
+  void* y;
+};
+struct GemvProblem {
+  const void* W;
+  int64_t rows, cols, ld;
+  const void* x;
+  void* y;
+};
+// n independent products, as few kernel launches as the shapes allow (1 <= n <= kMaxGroup)
+int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream);
+int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream);
 // GPU encoder: counting pass + fill pass.  Allocates *values, *deltas, *row_ptr with hipMalloc.
 int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, hipStream_t stream,
                      uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,

@@ -106,7 +106,7 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
 // ahead of the arithmetic and cross row boundaries, so the memory pipeline does
 // not drain between rows.  Every item issues exactly one deltas load and one
 // values load, unconditionally (lanes past the row end re-read the row's last
-// chunk, items past the block's last row re-read the previous address), which
+// chunk, items past the block's last row read chunk 0 of the arrays), which
 // lets the compiler count outstanding loads exactly.
 //
 // Entries of neighbouring rows that share a lane's 8-entry chunk:
@@ -144,13 +144,34 @@ __device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t r
   cur.step = 0;
 }
 
+// One matrix of a grouped launch: workgroups [wg_begin, next wg_begin) work on it.
+struct SpmvMat {
+  const uint4* values;
+  const uint32_t* deltas;
+  const uint32_t* row_ptr;
+  const uint16_t* x;
+  uint16_t* y;
+  int rows, cols, rows_per_wg, wg_begin;
+};
+struct SpmvGroupArgs {
+  int n;
+  SpmvMat m[kMaxGroup];
+};
+
 template <int RING>
-__global__ void __launch_bounds__(1024)
-spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
-                     const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
-                     uint16_t* __restrict__ y, int rows, int cols, int rows_per_wg, int lds_bytes) {
+__global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs g) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int row_begin = blockIdx.x * rows_per_wg;
+  // which matrix of the group this workgroup belongs to (uniform)
+  int mi = 0;
+  for (int i = 1; i < g.n; ++i) mi = (int)blockIdx.x >= g.m[i].wg_begin ? i : mi;
+  const uint4* __restrict__ values = g.m[mi].values;
+  const uint32_t* __restrict__ deltas = g.m[mi].deltas;
+  const uint32_t* __restrict__ row_ptr = g.m[mi].row_ptr;
+  const uint16_t* __restrict__ x = g.m[mi].x;
+  uint16_t* __restrict__ y = g.m[mi].y;
+  const int rows = g.m[mi].rows, cols = g.m[mi].cols, rows_per_wg = g.m[mi].rows_per_wg;
+  const int lds_bytes = (int)lds_bytes_for(cols);
+  const int row_begin = ((int)blockIdx.x - g.m[mi].wg_begin) * rows_per_wg;
   const int row_end = min(rows, row_begin + rows_per_wg);
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
@@ -177,6 +198,8 @@ spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
         ++ld.i;
         seek_nonempty(ld, nb, rp_lo, rp_hi);
       }
+    } else {
+      chunk = 0;       // padding item: every lane re-reads the first 16 bytes (one hot cache line)
     }
     wq[j] = deltas[chunk];
     vq[j] = values[chunk];
@@ -303,84 +326,126 @@ constexpr int64_t kMaxLdsBytes = 160 * 1024 - 64;   // 160 KB per CU minus the s
 
 }  // namespace
 
-int launch_spmv(const uint16_t* values, const uint8_t* deltas, const uint32_t* row_ptr, int64_t rows,
-                int64_t cols, int64_t pad_nnz, int64_t max_row_entries, const void* x, void* y,
-                hipStream_t stream) {
-  (void)max_row_entries;
+namespace {
+
+int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
   const Tuning& t = tuning();
   const int cus = device_cu_count();
-  const int64_t lds_bytes = lds_bytes_for(cols);
+  const int64_t lds_bytes = lds_bytes_for(p.cols);
   const bool lds_ok = lds_bytes <= kMaxLdsBytes;
-  const int64_t avg = rows > 0 ? pad_nnz / rows : 0;
-
-  if (pad_nnz == 0) {                                  // nothing stored: y = 0
-    hipLaunchKernelGGL(zero_y_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, stream,
-                       static_cast<uint16_t*>(y), (int)rows);
-    hipError_t e0 = hipGetLastError();
-    return e0 == hipSuccess ? MACKO_OK : hip_fail(e0);
+  const int64_t avg = p.rows > 0 ? p.pad_nnz / p.rows : 0;
+  const uint4* v4 = reinterpret_cast<const uint4*>(p.values);
+  const uint32_t* d4 = reinterpret_cast<const uint32_t*>(p.deltas);
+  const uint16_t* xp = static_cast<const uint16_t*>(p.x);
+  uint16_t* yp = static_cast<uint16_t*>(p.y);
+  int lanes = kernel_lanes;
+  if (lanes == 0) lanes = avg >= 384 ? 64 : (avg >= 192 ? 32 : 16);
+  const int block = t.spmv_block ? (int)t.spmv_block : 256;
+  const int groups = block / lanes;
+  int64_t rpw = t.spmv_rows_per_wg;
+  if (rpw == 0) {
+    const int64_t target_wgs = (int64_t)cus * 4;
+    rpw = (p.rows + target_wgs - 1) / target_wgs;
+    rpw = (std::max<int64_t>(rpw, groups) + groups - 1) / groups * groups;
   }
-
-  int kernel = (int)t.spmv_kernel;
-  if (kernel == 0) kernel = (avg >= 384 && lds_ok) ? 2 : 1;
-  if (kernel == 2 && !lds_ok) return MACKO_E_UNSUPPORTED;
-
-  const uint4* v4 = reinterpret_cast<const uint4*>(values);
-  const uint32_t* d4 = reinterpret_cast<const uint32_t*>(deltas);
-  const uint16_t* xp = static_cast<const uint16_t*>(x);
-  uint16_t* yp = static_cast<uint16_t*>(y);
-
-  if (kernel == 2) {
-    const int block = t.spmv_block ? (int)t.spmv_block : 512;
-    const int nwaves = block / 64;
-    int64_t rpw = t.spmv_rows_per_wg;
-    if (rpw == 0) {
-      // A wavefront should own about 16 steps of work so that its load pipeline
-      // runs in steady state (short rows: several rows per wavefront), but never
-      // so much that fewer than ~16 wavefronts per CU remain.
-      const int64_t steps_per_row = std::max<int64_t>(1, (avg + 511) / 512);
-      const int64_t want = (16 + steps_per_row - 1) / steps_per_row;
-      const int64_t cap = std::max<int64_t>(1, rows / ((int64_t)cus * 16));
-      rpw = std::min(want, cap) * nwaves;
-    }
-    const int64_t grid = (rows + rpw - 1) / rpw;
-    auto kfn = spmv_wave_row_kernel<4>;
-    int st = set_lds_limit(kfn, lds_bytes);
-    if (st != MACKO_OK) return st;
-    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds_bytes, stream, v4, d4,
-                       row_ptr, xp, yp, (int)rows, (int)cols, (int)rpw, (int)lds_bytes);
-  } else {
-    int lanes = (int)t.spmv_lanes;
-    if (lanes == 0) lanes = avg >= 384 ? 64 : (avg >= 192 ? 32 : 16);
-    const int block = t.spmv_block ? (int)t.spmv_block : 256;
-    const int groups = block / lanes;
-    int64_t rpw = t.spmv_rows_per_wg;
-    if (rpw == 0) {
-      const int64_t target_wgs = (int64_t)cus * 4;
-      rpw = (rows + target_wgs - 1) / target_wgs;
-      rpw = (std::max<int64_t>(rpw, groups) + groups - 1) / groups * groups;
-    }
-    const int64_t grid = (rows + rpw - 1) / rpw;
-    const size_t shm = lds_ok ? (size_t)lds_bytes : 0;
+  const int64_t grid = (p.rows + rpw - 1) / rpw;
+  const size_t shm = lds_ok ? (size_t)lds_bytes : 0;
 #define MACKO_LAUNCH_SUB(L)                                                                          \
   do {                                                                                               \
     if (lds_ok) {                                                                                    \
       auto kfn = spmv_subwave_kernel<L, true>;                                                       \
       int st = set_lds_limit(kfn, lds_bytes);                                                        \
       if (st != MACKO_OK) return st;                                                                 \
-      hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), shm, stream, v4, d4, row_ptr, xp,   \
-                         yp, (int)rows, (int)cols, (int)rpw, (int)lds_bytes);                        \
+      hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), shm, stream, v4, d4, p.row_ptr, xp, \
+                         yp, (int)p.rows, (int)p.cols, (int)rpw, (int)lds_bytes);                    \
     } else {                                                                                         \
       hipLaunchKernelGGL((spmv_subwave_kernel<L, false>), dim3((unsigned)grid), dim3(block), 0,      \
-                         stream, v4, d4, row_ptr, xp, yp, (int)rows, (int)cols, (int)rpw, 0);        \
+                         stream, v4, d4, p.row_ptr, xp, yp, (int)p.rows, (int)p.cols, (int)rpw, 0);  \
     }                                                                                                \
   } while (0)
-    if (lanes == 64) MACKO_LAUNCH_SUB(64);
-    else if (lanes == 32) MACKO_LAUNCH_SUB(32);
-    else MACKO_LAUNCH_SUB(16);
+  if (lanes == 64) MACKO_LAUNCH_SUB(64);
+  else if (lanes == 32) MACKO_LAUNCH_SUB(32);
+  else MACKO_LAUNCH_SUB(16);
 #undef MACKO_LAUNCH_SUB
-  }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return hip_fail(e);
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
+
+}  // namespace
+
+int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
+  if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;
+  const Tuning& t = tuning();
+  const int cus = device_cu_count();
+  const int block = t.spmv_block ? (int)t.spmv_block : 512;
+  const int nwaves = block / 64;
+
+  // rows that will share the grouped launch (decides how much work a wavefront gets)
+  auto wants_wave_row = [&](const SpmvProblem& p) {
+    if (p.rows == 0 || p.pad_nnz == 0) return false;
+    if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
+    return p.pad_nnz / p.rows >= 384 && lds_bytes_for(p.cols) <= kMaxLdsBytes;
+  };
+  int64_t group_rows = 0;
+  for (int i = 0; i < n; ++i) group_rows += wants_wave_row(problems[i]) ? problems[i].rows : 0;
+
+  SpmvGroupArgs args{};
+  int64_t total_wgs = 0, max_lds = 0;
+  for (int i = 0; i < n; ++i) {
+    const SpmvProblem& p = problems[i];
+    if (p.rows == 0) continue;
+    if (p.pad_nnz == 0) {                               // nothing stored: y = 0
+      hipLaunchKernelGGL(zero_y_kernel, dim3((unsigned)((p.rows + 255) / 256)), dim3(256), 0, stream,
+                         static_cast<uint16_t*>(p.y), (int)p.rows);
+      hipError_t e0 = hipGetLastError();
+      if (e0 != hipSuccess) return hip_fail(e0);
+      continue;
+    }
+    const int64_t lds_bytes = lds_bytes_for(p.cols);
+    const bool lds_ok = lds_bytes <= kMaxLdsBytes;
+    const int64_t avg = p.pad_nnz / p.rows;
+    if (!wants_wave_row(p)) {                           // short rows or x larger than LDS: own launch
+      int st = launch_subwave(p, (int)t.spmv_lanes, stream);
+      if (st != MACKO_OK) return st;
+      continue;
+    }
+    if (!lds_ok) return MACKO_E_UNSUPPORTED;
+    int64_t rpw = t.spmv_rows_per_wg;
+    if (rpw == 0) {
+      // A wavefront should own about 16 steps of work so that its load pipeline
+      // runs in steady state (short rows: several rows per wavefront), but never
+      // so much that the launch as a whole has fewer than ~16 wavefronts per CU.
+      const int64_t steps_per_row = std::max<int64_t>(1, (avg + 511) / 512);
+      const int64_t want = (16 + steps_per_row - 1) / steps_per_row;
+      const int64_t cap = std::max<int64_t>(1, group_rows / ((int64_t)cus * 16));
+      rpw = std::min(want, cap) * nwaves;
+    }
+    SpmvMat& m = args.m[args.n++];
+    m.values = reinterpret_cast<const uint4*>(p.values);
+    m.deltas = reinterpret_cast<const uint32_t*>(p.deltas);
+    m.row_ptr = p.row_ptr;
+    m.x = static_cast<const uint16_t*>(p.x);
+    m.y = static_cast<uint16_t*>(p.y);
+    m.rows = (int)p.rows;
+    m.cols = (int)p.cols;
+    m.rows_per_wg = (int)rpw;
+    m.wg_begin = (int)total_wgs;
+    total_wgs += (p.rows + rpw - 1) / rpw;
+    max_lds = std::max(max_lds, lds_bytes);
+    if (total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  }
+  if (args.n > 0) {
+    // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
+    // CU, and the smaller loop body matters when a wavefront runs it only a few times.
+    auto kfn = t.spmv_ring == 4 ? spmv_wave_row_kernel<4>
+               : t.spmv_ring == 8 ? spmv_wave_row_kernel<8>
+               : t.spmv_ring == 3 ? spmv_wave_row_kernel<3> : spmv_wave_row_kernel<2>;
+    int st = set_lds_limit(kfn, max_lds);
+    if (st != MACKO_OK) return st;
+    hipLaunchKernelGGL(kfn, dim3((unsigned)total_wgs), dim3(block), (size_t)max_lds, stream, args);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+  }
   return MACKO_OK;
 }
 

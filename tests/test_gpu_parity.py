@@ -186,6 +186,62 @@ def test_wrap_device_reuses_an_existing_encoding():
     assert torch.equal(y, m.spmv(to_dev(x)))
 
 
+# ------------------------------------------------------------------ grouped launches
+
+def test_spmv_group_mixed_shapes_one_call():
+    specs = [(300, 2048, 0.5), (64, 4096, 0.5), (500, 1000, 0.3), (40, 8000, 0.9),   # wave-per-row kernel
+             (200, 300, 0.5),                                                         # short rows: own launch
+             (77, 640, 0.0),                                                          # nothing stored
+             (10, 100000, 0.2),                                                       # x larger than LDS
+             (129, 5000, 1.0)]
+    Ws = [wl.bernoulli(r, c, d, 0.02, 31, i) if d > 0 else np.zeros((r, c), dtype=np.uint16)
+          for i, (r, c, d) in enumerate(specs)]
+    xs = [wl.x_vector(c, 31, i) for i, (_, c, _) in enumerate(specs)]
+    ms = [M.encode(W).to_device() for W in Ws]
+    xd = [to_dev(x) for x in xs]
+    ys = M.spmv_group(ms, xd)
+    torch.cuda.synchronize()
+    for i, (W, x, y) in enumerate(zip(Ws, xs, ys)):
+        check_y(y, W, x, f"group member {i} {specs[i]}")
+    # the single-product call gives bit-identical results (same kernel, same order of operations)
+    for m, x, y in zip(ms, xd, ys):
+        assert torch.equal(m.spmv(x), y)
+    # q/k/v style: three matrices, one shared x
+    q = [M.encode(wl.half_row_matrix(256, 4096, 60 + i)).to_device() for i in range(3)]
+    xq = to_dev(wl.x_vector(4096, 31, 99))
+    yq = M.spmv_group(q, [xq, xq, xq])
+    torch.cuda.synchronize()
+    for i in range(3):
+        check_y(yq[i], wl.half_row_matrix(256, 4096, 60 + i), wl.x_vector(4096, 31, 99), f"qkv {i}")
+
+
+def test_group_argument_errors():
+    lib = M.load_library()
+    m = M.encode(wl.config1().W).to_device()
+    x = to_dev(wl.config1().x)
+    y = torch.empty(512, dtype=torch.float16, device="cuda")
+    import ctypes
+    VP = ctypes.c_void_p * 9
+    hs = VP(*[m._h.value] * 9); xs = VP(*[x.data_ptr()] * 9); ys = VP(*[y.data_ptr()] * 9)
+    assert lib.macko_spmv_group(0, hs, xs, ys, None) == -1
+    assert lib.macko_spmv_group(9, hs, xs, ys, None) == -1
+    unbound = M.encode(wl.config1().W)
+    hs2 = VP(*([m._h.value] * 8 + [unbound._h.value]))
+    hs2[1] = unbound._h.value
+    assert lib.macko_spmv_group(2, hs2, xs, ys, None) == -5
+    torch.cuda.synchronize()
+
+
+def test_dense_gemv_group():
+    shapes = [(300, 1024), (64, 4096), (33, 777), (128, 8200)]
+    Ws = [wl.bernoulli(r, c, 1.0, 0.02, 41, i) for i, (r, c) in enumerate(shapes)]
+    xs = [wl.x_vector(c, 41, i) for i, (_, c) in enumerate(shapes)]
+    ys = M.dense_gemv_group([to_dev(W) for W in Ws], [to_dev(x) for x in xs])
+    torch.cuda.synchronize()
+    for W, x, y, shp in zip(Ws, xs, ys, shapes):
+        check_y(y, W, x, f"gemv group {shp}")
+
+
 # ------------------------------------------------------------------ GPU encoder
 
 ENC_CASES = {
