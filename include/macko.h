@@ -172,8 +172,8 @@ MACKO_API int macko_last_hip_error(void);
  *   "spmv_lanes"        0 auto, else lanes per row for the generic kernel (16/32/64)
  *   "spmv_block"        threads per workgroup for spmv (multiple of 64, <= 1024), 0 auto
  *   "spmv_rows_per_wg"  rows handled by one workgroup, 0 auto
- *   "spmv_ring"         steps of loads kept in flight per wavefront (2, 3, 4 or 8), 0 auto
- *   "gemv_block", "gemv_rows_per_wg"  the same for the dense GEMV
+ *   "spmv_ring"         steps of loads kept in flight per wavefront (2 or 4), 0 auto
+ *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8)  the same for the dense GEMV
  * Settings are process wide and not thread safe. */
 MACKO_API int macko_set_tuning(const char* name, int64_t value);
 MACKO_API int macko_get_tuning(const char* name, int64_t* value);

@@ -15,8 +15,13 @@ constexpr int kWave = 64;
 // Entries that a lane loads but that belong to a neighbouring row decode to
 // positions just before column 0 or after the row's last column; the guards
 // make those reads return +0 so that they contribute nothing.
-constexpr int kFrontPad = 2048;  // bytes
-constexpr int kBackPad = 2048;   // bytes
+// Front guard: a row's first chunk holds at most 7 entries of the previous row,
+// each at most 16 columns wide (224 bytes before x[0]).  Back guard: in a row's
+// last step the lanes past the row end advance by one column per entry, plus at
+// most 7 real deltas in the lane that straddles the end (at most 616 columns);
+// the dense kernel reads at most 62 16-byte chunks past the end.
+constexpr int kFrontPad = 256;   // bytes
+constexpr int kBackPad = 1280;   // bytes
 
 __host__ __device__ inline int64_t lds_bytes_for(int64_t cols) {
   return kFrontPad + 16 * ((cols + 7) / 8) + kBackPad;
@@ -107,6 +112,10 @@ __device__ __forceinline__ void stage_x_begin(XStage& st, const uint16_t* __rest
   }
 }
 
+// SIMPLE promises: x is 16-byte aligned, cols is a multiple of 8 and x fits the
+// staging registers (cols <= 8 * kXStageRegs * blockDim.x).  The general version
+// also copies what did not fit, the ragged tail, or all of an unaligned x.
+template <bool SIMPLE>
 __device__ __forceinline__ void stage_x_finish(unsigned char* lds, const XStage& st,
                                                const uint16_t* __restrict__ x, int cols, int lds_bytes) {
   const int tid = threadIdx.x;
@@ -115,30 +124,39 @@ __device__ __forceinline__ void stage_x_finish(unsigned char* lds, const XStage&
   uint4* lds16 = reinterpret_cast<uint4*>(lds);
   const int chunks = cols >> 3;
   const int tail_chunks = (cols + 7) >> 3;            // chunks touched by x
-  for (int i = tid; i < kFrontPad / 16; i += nt) lds16[i] = zero;
-  for (int i = kFrontPad / 16 + tail_chunks + tid; i < lds_bytes / 16; i += nt) lds16[i] = zero;
+  // guards: kFrontPad/16 chunks in front, kBackPad/16 behind
+  constexpr int kGuardChunks = (kFrontPad + kBackPad) / 16;
+  for (int i = tid; i < kGuardChunks; i += nt)
+    lds16[i < kFrontPad / 16 ? i : i + tail_chunks] = zero;
   uint16_t* xs = reinterpret_cast<uint16_t*>(lds + kFrontPad);
   uint4* xd = reinterpret_cast<uint4*>(xs);
-  if ((reinterpret_cast<uintptr_t>(x) & 15) == 0) {
-    const uint4* xg = reinterpret_cast<const uint4*>(x);
+  if (SIMPLE || (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
 #pragma unroll
     for (int k = 0; k < kXStageRegs; ++k) {
       const int i = tid + k * nt;
       if (i < chunks) xd[i] = st.r[k];
     }
-    for (int i = tid + kXStageRegs * nt; i < chunks; i += nt) xd[i] = xg[i];
-    for (int i = chunks * 8 + tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
+    if (!SIMPLE) {
+      const uint4* xg = reinterpret_cast<const uint4*>(x);
+      for (int i = tid + kXStageRegs * nt; i < chunks; i += nt) xd[i] = xg[i];
+      for (int i = chunks * 8 + tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
+    }
   } else {
     for (int i = tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
   }
   __syncthreads();
 }
 
+__host__ __device__ inline bool stage_x_is_simple(const void* x, int64_t cols, int block) {
+  return (reinterpret_cast<uintptr_t>(x) & 15) == 0 && cols % 8 == 0 &&
+         cols <= (int64_t)8 * kXStageRegs * block;
+}
+
 __device__ __forceinline__ void stage_x_to_lds(unsigned char* lds, const uint16_t* __restrict__ x,
                                                int cols, int lds_bytes) {
   XStage st;
   stage_x_begin(st, x, cols);
-  stage_x_finish(lds, st, x, cols, lds_bytes);
+  stage_x_finish<false>(lds, st, x, cols, lds_bytes);
 }
 
 }  // namespace macko

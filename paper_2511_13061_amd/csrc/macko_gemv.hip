@@ -85,7 +85,7 @@ __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs
   XStage xst;
   stage_x_begin(xst, x, cols);
   open_block();
-  stage_x_finish(lds, xst, x, cols, lds_bytes);        // ends with a barrier
+  stage_x_finish<false>(lds, xst, x, cols, lds_bytes);        // ends with a barrier
 
   while (true) {
     float yv = 0.0f;                                   // lane i: result of row blk + i
@@ -196,7 +196,8 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
     if (total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
   }
   if (args.n > 0) {
-    auto kfn = gemv_wave_row_kernel<4>;
+    auto kfn = t.gemv_ring == 2 ? gemv_wave_row_kernel<2>
+               : t.gemv_ring == 8 ? gemv_wave_row_kernel<8> : gemv_wave_row_kernel<4>;
     if (max_lds > 64 * 1024) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);

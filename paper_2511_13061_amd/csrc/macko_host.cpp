@@ -433,6 +433,7 @@ static int64_t* tuning_slot(const char* name) {
   if (n == "spmv_ring") return &t.spmv_ring;
   if (n == "gemv_block") return &t.gemv_block;
   if (n == "gemv_rows_per_wg") return &t.gemv_rows_per_wg;
+  if (n == "gemv_ring") return &t.gemv_ring;
   return nullptr;
 }
 
@@ -441,7 +442,8 @@ int macko_set_tuning(const char* name, int64_t value) {
   if (!slot || value < 0) return MACKO_E_INVALID_ARG;
   const std::string n(name);
   if (n == "spmv_kernel" && value > 2) return MACKO_E_INVALID_ARG;
-  if (n == "spmv_ring" && value != 0 && value != 2 && value != 3 && value != 4 && value != 8) return MACKO_E_INVALID_ARG;
+  if (n == "gemv_ring" && value != 0 && value != 2 && value != 4 && value != 8) return MACKO_E_INVALID_ARG;
+  if (n == "spmv_ring" && value != 0 && value != 2 && value != 4) return MACKO_E_INVALID_ARG;
   if (n == "spmv_lanes" && value != 0 && value != 16 && value != 32 && value != 64) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_block" || n == "gemv_block") && value != 0 && (value % 64 != 0 || value > 1024))
     return MACKO_E_INVALID_ARG;

@@ -22,6 +22,7 @@ struct Tuning {
   int64_t spmv_ring = 0;
   int64_t gemv_block = 0;
   int64_t gemv_rows_per_wg = 0;
+  int64_t gemv_ring = 0;
 };
 Tuning& tuning();
 

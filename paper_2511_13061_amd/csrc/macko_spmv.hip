@@ -91,22 +91,21 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
 // Position arithmetic is done in units of bytes of the LDS copy of x, i.e.
 // doubled: an entry with code c advances the position by 2c + 2.  Within a lane
 // the 8 doubled code prefixes (at most 2*15*8 = 240) fit the bytes of two 32-bit
-// words; the constant part 2(k+1) of entry k goes into the immediate offset of
-// the LDS read.
+// words; the constant part 2k of entry k is added bytewise to those words.
 //
 // A workgroup owns rows [row_begin, row_end); each of its wavefronts owns a
-// contiguous share of them and works through it in blocks of up to 64 rows.
-// For a block, lane i fetches row i's pointers once (one coalesced load); the
+// contiguous share of them, at most 64 rows (the launcher sees to that).
+// Lane i fetches row i's pointers once (one coalesced load); the
 // scalar row bounds are then picked out of that register with v_readlane, and
-// the 64 results are collected in a register (v_writelane) and stored with one
-// coalesced store.  The steady-state loop therefore contains no memory
+// the results are collected in a register (lane i keeps row i's) and stored
+// with one coalesced store.  The steady-state loop therefore contains no memory
 // instruction other than the two streaming loads per item.
 //
-// The block's rows form one stream of (row, step) items.  Loads run RING items
+// The wavefront's rows form one stream of (row, step) items.  Loads run RING items
 // ahead of the arithmetic and cross row boundaries, so the memory pipeline does
 // not drain between rows.  Every item issues exactly one deltas load and one
 // values load, unconditionally (lanes past the row end re-read the row's last
-// chunk, items past the block's last row read chunk 0 of the arrays), which
+// chunk, items past the wavefront's last row read chunk 0 of the arrays), which
 // lets the compiler count outstanding loads exactly.
 //
 // Entries of neighbouring rows that share a lane's 8-entry chunk:
@@ -130,7 +129,7 @@ struct RowCursor {
 };
 
 // Move the cursor to the first non-empty row at or after cur.i.  Only lanes
-// below nb hold pointers of the block's rows; others are never selected.
+// below nb hold pointers of the wavefront's rows; others are never selected.
 __device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t rp_lo, uint32_t rp_hi) {
   cur.start = cur.end = 0;
   while (cur.i < nb) {
@@ -158,7 +157,7 @@ struct SpmvGroupArgs {
   SpmvMat m[kMaxGroup];
 };
 
-template <int RING>
+template <int RING, bool SIMPLE>
 __global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs g) {
   extern __shared__ __align__(16) unsigned char lds[];
   // which matrix of the group this workgroup belongs to (uniform)
@@ -183,8 +182,8 @@ __global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs
   const int wrow_end = min(row_end, wrow_begin + per_wave);
 
   uint32_t chunk = 0;      // 8-entry chunk index this lane loads next (chunk 0 exists: pad_nnz > 0)
-  int blk = wrow_begin;
-  int nb = max(0, min(64, wrow_end - blk));
+  const int blk = wrow_begin;
+  const int nb = wrow_end - wrow_begin;                // at most 64: the host caps rows_per_wg
   uint32_t rp_lo = 0, rp_hi = 0;
   RowCursor ld, cp;                                    // load side, compute side
   uint32_t wq[RING];
@@ -224,9 +223,9 @@ __global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs
   fetch_row_ptrs();
   stage_x_begin(xst, x, cols);
   prime_ring();
-  stage_x_finish(lds, xst, x, cols, lds_bytes);        // ends with a barrier
+  stage_x_finish<SIMPLE>(lds, xst, x, cols, lds_bytes);  // ends with a barrier
 
-  while (true) {
+  {
     float yv = 0.0f;                                   // lane i: result of row blk + i
     float acc = 0.0f;
     int base2 = 0;                                     // doubled position before this step (uniform)
@@ -298,11 +297,6 @@ __global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs
       }
     }
     if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
-    blk += 64;
-    if (blk >= wrow_end) break;
-    nb = min(64, wrow_end - blk);
-    fetch_row_ptrs();
-    prime_ring();
   }
 }
 
@@ -420,6 +414,7 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
       const int64_t cap = std::max<int64_t>(1, group_rows / ((int64_t)cus * 16));
       rpw = std::min(want, cap) * nwaves;
     }
+    rpw = std::min<int64_t>(rpw, 64 * nwaves);          // a wavefront keeps at most 64 rows' results
     SpmvMat& m = args.m[args.n++];
     m.values = reinterpret_cast<const uint4*>(p.values);
     m.deltas = reinterpret_cast<const uint32_t*>(p.deltas);
@@ -436,10 +431,13 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   }
   if (args.n > 0) {
     // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
-    // CU, and the smaller loop body matters when a wavefront runs it only a few times.
-    auto kfn = t.spmv_ring == 4 ? spmv_wave_row_kernel<4>
-               : t.spmv_ring == 8 ? spmv_wave_row_kernel<8>
-               : t.spmv_ring == 3 ? spmv_wave_row_kernel<3> : spmv_wave_row_kernel<2>;
+    // CU, and the smaller loop body matters when a wavefront runs it only a few
+    // times (instruction fetch is cold at every launch).  The lean start-up path
+    // needs an aligned x whose length is a multiple of 8 and fits the staging registers.
+    bool simple = true;
+    for (int i = 0; i < args.n; ++i) simple = simple && stage_x_is_simple(args.m[i].x, args.m[i].cols, block);
+    auto kfn = t.spmv_ring == 4 ? (simple ? spmv_wave_row_kernel<4, true> : spmv_wave_row_kernel<4, false>)
+                                : (simple ? spmv_wave_row_kernel<2, true> : spmv_wave_row_kernel<2, false>);
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     hipLaunchKernelGGL(kfn, dim3((unsigned)total_wgs), dim3(block), (size_t)max_lds, stream, args);
