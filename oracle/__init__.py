@@ -22,6 +22,11 @@ from . import closed_forms  # noqa: F401  (re-export)
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "macko_oracle.c")
 _LIB = os.path.join(_HERE, "libmacko_oracle.so")
+# The mutation tests point this at a deliberately broken copy of the source to
+# show that the pins notice; nothing else sets it.
+if os.environ.get("MACKO_ORACLE_SRC"):
+    _SRC = os.environ["MACKO_ORACLE_SRC"]
+    _LIB = os.path.splitext(_SRC)[0] + ".so"
 _lib = None
 
 
