@@ -52,6 +52,17 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
   return v;
 }
 
+// Inclusive running maximum over the 64 lanes (unsigned; lanes without a source read 0).
+__device__ __forceinline__ uint32_t wave_incl_scan_max_u32(uint32_t v) {
+  MACKO_DPP_ADD("v_max_u32_dpp", v, "row_shr:1", "0xf");
+  MACKO_DPP_ADD("v_max_u32_dpp", v, "row_shr:2", "0xf");
+  MACKO_DPP_ADD("v_max_u32_dpp", v, "row_shr:4", "0xf");
+  MACKO_DPP_ADD("v_max_u32_dpp", v, "row_shr:8", "0xf");
+  MACKO_DPP_ADD("v_max_u32_dpp", v, "row_bcast:15", "0xa");
+  MACKO_DPP_ADD("v_max_u32_dpp", v, "row_bcast:31", "0xc");
+  return v;
+}
+
 // Sum over the 64 lanes; the total ends up in lane 63 (other lanes hold prefixes).
 __device__ __forceinline__ float wave_sum_to_last_lane(float v) {
   MACKO_DPP_ADD("v_add_f32_dpp", v, "row_shr:1", "0xf");

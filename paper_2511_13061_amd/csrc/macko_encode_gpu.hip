@@ -4,10 +4,12 @@
 // output is bit-identical to the host encoder's.
 //
 // One wavefront works on one row; per step a lane looks at 8 consecutive
-// columns.  The column of the previous stored entry is carried across lanes
-// with a max-scan and across steps in a register, so each lane can price its own
-// non-zeros: a non-zero at distance g from the previously stored column costs
-// (g-1)/16 padding entries plus itself.
+// columns (one 16-byte load, issued one step ahead).  The position of the
+// previous stored entry is carried across lanes with a DPP max-scan and across
+// steps in a register, so each lane can price its own non-zeros: a non-zero at
+// distance g from the previously stored column costs (g-1)/16 padding entries
+// plus itself, and inside a chunk of 8 columns only the first non-zero can cost
+// any.  Per-row counts go to arrays that the scan kernel totals (no atomics).
 #include "macko_device.h"
 #include "macko_internal.h"
 
@@ -21,105 +23,142 @@ struct EncodeStats {
   unsigned int max_row_entries;
 };
 
+// 8 consecutive columns as loaded (4 x 2 fp16), and the same with the non-zero mask.
+struct RawChunk {
+  uint32_t u[4];
+};
 struct Chunk {
   uint16_t h[8];
   unsigned mask;   // bit k set iff h[k] is neither +0 nor -0
 };
 
-__device__ __forceinline__ Chunk load_chunk(const uint16_t* __restrict__ row, int col0, int cols,
-                                            bool vec_ok) {
-  Chunk c;
+// Loads only; columns at or beyond `cols` read as +0.  The caller decodes the
+// result one loop iteration later, so the load is in flight behind the work on
+// the current chunk.
+__device__ __forceinline__ RawChunk load_raw(const uint16_t* __restrict__ row, int col0, int cols,
+                                             bool vec_ok) {
+  RawChunk r;
   if (vec_ok && col0 + 8 <= cols) {
     const uint4 q = *reinterpret_cast<const uint4*>(row + col0);
-    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int k = 0; k < 8; ++k) c.h[k] = (uint16_t)(u[k >> 1] >> (16 * (k & 1)));
+    r.u[0] = q.x; r.u[1] = q.y; r.u[2] = q.z; r.u[3] = q.w;
   } else {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) c.h[k] = (col0 + k < cols) ? row[col0 + k] : (uint16_t)0;
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t lo = (col0 + 2 * k < cols) ? row[col0 + 2 * k] : 0u;
+      const uint32_t hi = (col0 + 2 * k + 1 < cols) ? row[col0 + 2 * k + 1] : 0u;
+      r.u[k] = lo | (hi << 16);
+    }
   }
+  return r;
+}
+
+__device__ __forceinline__ Chunk decode_chunk(const RawChunk& r) {
+  Chunk c;
   c.mask = 0;
 #pragma unroll
-  for (int k = 0; k < 8; ++k) c.mask |= ((c.h[k] & 0x7FFFu) != 0 ? 1u : 0u) << k;
+  for (int k = 0; k < 8; ++k) {
+    c.h[k] = (uint16_t)(r.u[k >> 1] >> (16 * (k & 1)));
+    c.mask |= ((c.h[k] & 0x7FFFu) != 0 ? 1u : 0u) << k;
+  }
   return c;
 }
 
-// column of the last stored entry before this lane's chunk
-__device__ __forceinline__ int prev_stored_column(unsigned mask, int col0, int lane, int* carry) {
-  const int last_in = mask ? col0 + (31 - __clz((int)mask)) : -1;
-  int incl = last_in;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int t = __shfl_up(incl, off);
-    if (lane >= off) incl = max(incl, t);
-  }
-  int prev = __shfl_up(incl, 1);
-  if (lane == 0) prev = -1;
-  prev = max(prev, *carry);
-  *carry = max(*carry, __shfl(incl, 63));
-  return prev;
+// What a lane needs to know about its 8 columns.  Two non-zeros inside one
+// chunk are at most 7 columns apart, so only the first non-zero of a chunk can
+// need padding entries in front of it.
+struct LaneView {
+  unsigned entries;   // stored entries this chunk contributes (non-zeros + padding)
+  unsigned nnz;       // non-zeros in the chunk
+  int lead;           // (gap - 1) of the chunk's first non-zero: column - previous stored column - 1
+};
+
+// `carry` is the position (column + 1, 0 = none) of the last stored entry of the
+// steps already consumed; it is advanced over this step.
+__device__ __forceinline__ LaneView view_chunk(unsigned mask, int col0, int lane, uint32_t* carry) {
+  const uint32_t lastpos = mask ? (uint32_t)(col0 + 32 - __clz((int)mask)) : 0u;
+  const uint32_t incl = wave_incl_scan_max_u32(lastpos);
+  uint32_t prevpos = (uint32_t)__shfl_up((int)incl, 1);
+  if (lane == 0) prevpos = 0;
+  prevpos = max(prevpos, *carry);
+  *carry = max(*carry, (uint32_t)__builtin_amdgcn_readlane((int)incl, 63));
+  LaneView v;
+  v.nnz = (unsigned)__popc(mask);
+  v.lead = mask ? col0 + (__ffs((int)mask) - 1) - (int)prevpos : 0;
+  v.entries = mask ? v.nnz + (unsigned)(v.lead >> kDeltaBits) : 0u;
+  return v;
 }
 
 __global__ void __launch_bounds__(256)
 encode_count_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok,
-                    uint32_t* __restrict__ row_entries, EncodeStats* __restrict__ stats) {
+                    uint32_t* __restrict__ row_entries, uint32_t* __restrict__ row_nnz) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nwaves = blockDim.x >> 6;
   for (int row = blockIdx.x * nwaves + wave; row < rows; row += gridDim.x * nwaves) {
     const uint16_t* src = dense + (int64_t)row * ld;
-    int carry = -1;
+    uint32_t carry = 0;
     unsigned entries = 0, nnz = 0;
+    RawChunk nxt = load_raw(src, lane * 8, cols, vec_ok);
     for (int base = 0; base < cols; base += 512) {
       const int col0 = base + lane * 8;
-      const Chunk c = load_chunk(src, col0, cols, vec_ok);
-      int p = prev_stored_column(c.mask, col0, lane, &carry);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        if ((c.mask >> k) & 1u) {
-          const int col = col0 + k;
-          entries += 1u + (unsigned)((col - p - 1) >> kDeltaBits);
-          ++nnz;
-          p = col;
-        }
-      }
+      const Chunk c = decode_chunk(nxt);
+      nxt = load_raw(src, col0 + 512, cols, vec_ok);                 // next step's columns, in flight
+      const LaneView v = view_chunk(c.mask, col0, lane, &carry);
+      entries += v.entries;
+      nnz += v.nnz;
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      entries += __shfl_xor(entries, off);
-      nnz += __shfl_xor(nnz, off);
-    }
-    if (lane == 0) {
+    entries = wave_incl_scan_u32(entries);
+    nnz = wave_incl_scan_u32(nnz);
+    if (lane == 63) {
       row_entries[row] = entries;
-      atomicAdd(&stats->nnz, (unsigned long long)nnz);
-      if (entries == 0) atomicAdd(&stats->empty_rows, 1u);
-      atomicMax(&stats->max_row_entries, entries);
+      row_nnz[row] = nnz;
     }
   }
 }
 
-// row_ptr[r] = sum of row_entries[0..r); one workgroup.  The total goes to
-// stats->pad_nnz as a 64-bit number so that the host can detect overflow of the
-// 32-bit row pointers before anything is written through them.
+// row_ptr[r] = sum of row_entries[0..r); one workgroup.  Also totals the
+// statistics of the storage report.  The entry total is kept as a 64-bit number
+// so that the host can detect overflow of the 32-bit row pointers before
+// anything is written through them.
 __global__ void __launch_bounds__(1024)
-encode_scan_kernel(const uint32_t* __restrict__ row_entries, int rows, uint32_t* __restrict__ row_ptr,
-                   EncodeStats* __restrict__ stats) {
+encode_scan_kernel(const uint32_t* __restrict__ row_entries, const uint32_t* __restrict__ row_nnz,
+                   int rows, uint32_t* __restrict__ row_ptr, EncodeStats* __restrict__ stats) {
   __shared__ unsigned long long part[1024];
+  __shared__ unsigned long long part_nnz[1024];
+  __shared__ unsigned int part_empty[1024];
+  __shared__ unsigned int part_max[1024];
   const int t = threadIdx.x;
   const int seg = (rows + 1023) / 1024;
   const int lo = min(rows, t * seg), hi = min(rows, lo + seg);
-  unsigned long long s = 0;
-  for (int r = lo; r < hi; ++r) s += row_entries[r];
+  unsigned long long s = 0, n = 0;
+  unsigned int empty = 0, longest = 0;
+  for (int r = lo; r < hi; ++r) {
+    const uint32_t e = row_entries[r];
+    s += e;
+    n += row_nnz[r];
+    empty += e == 0;
+    longest = max(longest, e);
+  }
   part[t] = s;
+  part_nnz[t] = n;
+  part_empty[t] = empty;
+  part_max[t] = longest;
   __syncthreads();
   if (t == 0) {
-    unsigned long long run = 0;
+    unsigned long long run = 0, nn = 0;
+    unsigned int em = 0, mx = 0;
     for (int i = 0; i < 1024; ++i) {
       const unsigned long long v = part[i];
       part[i] = run;
       run += v;
+      nn += part_nnz[i];
+      em += part_empty[i];
+      mx = max(mx, part_max[i]);
     }
     stats->pad_nnz = run;
+    stats->nnz = nn;
+    stats->empty_rows = em;
+    stats->max_row_entries = mx;
     row_ptr[rows] = (uint32_t)run;
   }
   __syncthreads();
@@ -139,45 +178,36 @@ encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64
   const int nwaves = blockDim.x >> 6;
   for (int row = blockIdx.x * nwaves + wave; row < rows; row += gridDim.x * nwaves) {
     const uint16_t* src = dense + (int64_t)row * ld;
-    int carry = -1;
+    uint32_t carry = 0;
     uint32_t cursor = row_ptr[row];              // first entry of this step
+    RawChunk nxt = load_raw(src, lane * 8, cols, vec_ok);
     for (int base = 0; base < cols; base += 512) {
       const int col0 = base + lane * 8;
-      const Chunk c = load_chunk(src, col0, cols, vec_ok);
-      const int prev = prev_stored_column(c.mask, col0, lane, &carry);
-      unsigned mine = 0;
-      int p = prev;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        if ((c.mask >> k) & 1u) {
-          mine += 1u + (unsigned)((col0 + k - p - 1) >> kDeltaBits);
-          p = col0 + k;
-        }
-      }
-      unsigned incl = mine;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const unsigned t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-      }
-      size_t o = (size_t)cursor + (incl - mine);
-      p = prev;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        if ((c.mask >> k) & 1u) {
-          const int g1 = col0 + k - p - 1;       // gap - 1
-          for (int pads = g1 >> kDeltaBits; pads > 0; --pads) {
-            values[o] = 0;
-            codes8[o] = kMaxDelta - 1;
-            ++o;
-          }
-          values[o] = c.h[k];
-          codes8[o] = (uint8_t)(g1 & (kMaxDelta - 1));
+      const Chunk c = decode_chunk(nxt);
+      nxt = load_raw(src, col0 + 512, cols, vec_ok);                 // next step's columns, in flight
+      const LaneView v = view_chunk(c.mask, col0, lane, &carry);
+      const uint32_t incl = wave_incl_scan_u32(v.entries);
+      size_t o = (size_t)cursor + (incl - v.entries);
+      if (c.mask) {
+        for (int pads = v.lead >> kDeltaBits; pads > 0; --pads) {   // padding entries, greedy
+          values[o] = 0;
+          codes8[o] = kMaxDelta - 1;
           ++o;
-          p = col0 + k;
+        }
+        unsigned m = c.mask;
+        int g1 = v.lead & (kMaxDelta - 1);       // (delta - 1) of the next stored entry
+        int prevk = -1;
+        while (m) {
+          const int k = __ffs((int)m) - 1;
+          m &= m - 1;
+          if (prevk >= 0) g1 = k - prevk - 1;
+          values[o] = c.h[k];
+          codes8[o] = (uint8_t)g1;
+          ++o;
+          prevk = k;
         }
       }
-      cursor += __shfl(incl, 63);
+      cursor += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
     }
   }
 }
@@ -219,21 +249,21 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
                      int64_t* max_row_entries) {
   const int cus = device_cu_count();
   const bool vec_ok = (ld % 8 == 0) && (reinterpret_cast<uintptr_t>(dense) & 15) == 0;
-  DeviceBuf counts, stats_d, rp, vals, dels, codes;
-  if (counts.alloc(4 * (size_t)rows) != hipSuccess || stats_d.alloc(sizeof(EncodeStats)) != hipSuccess ||
+  DeviceBuf counts, nnzs, stats_d, rp, vals, dels, codes;
+  if (counts.alloc(4 * (size_t)rows) != hipSuccess || nnzs.alloc(4 * (size_t)rows) != hipSuccess || stats_d.alloc(sizeof(EncodeStats)) != hipSuccess ||
       rp.alloc(4 * (size_t)(rows + 1)) != hipSuccess) {
     (void)hipGetLastError();
     return MACKO_E_OUT_OF_MEMORY;
   }
-  MACKO_HIP_TRY(hipMemsetAsync(stats_d.p, 0, sizeof(EncodeStats), stream));
   const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((rows + 3) / 4, (int64_t)cus * 16));
   if (rows > 0) {
     hipLaunchKernelGGL(encode_count_kernel, dim3(grid), dim3(256), 0, stream, dense, (int)rows,
                        (int)cols, ld, vec_ok, static_cast<uint32_t*>(counts.p),
-                       static_cast<EncodeStats*>(stats_d.p));
+                       static_cast<uint32_t*>(nnzs.p));
   }
   hipLaunchKernelGGL(encode_scan_kernel, dim3(1), dim3(1024), 0, stream,
-                     static_cast<const uint32_t*>(counts.p), (int)rows, static_cast<uint32_t*>(rp.p),
+                     static_cast<const uint32_t*>(counts.p), static_cast<const uint32_t*>(nnzs.p),
+                     (int)rows, static_cast<uint32_t*>(rp.p),
                      static_cast<EncodeStats*>(stats_d.p));
   MACKO_HIP_TRY(hipGetLastError());
   EncodeStats st{};
