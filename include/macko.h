@@ -142,6 +142,16 @@ MACKO_API int macko_spmv(macko_handle_t h, const void* x_dev, void* y_dev, void*
 MACKO_API int macko_dense_gemv(const void* W_dev, int64_t rows, int64_t cols, int64_t ld,
                                const void* x_dev, void* y_dev, void* stream);
 
+/* Small-batch product with one matrix (decode shared by the batch):
+ * Y[b][r] = sum_k values[k] * X[b][column(k)] for b < batch, 0 <= batch <= MACKO_MAX_BATCH.
+ * X_dev: fp16, batch vectors of `cols` elements, vector b at X_dev + b*ldx
+ * (ldx >= cols); Y_dev: fp16, vector b at Y_dev + b*ldy (ldy >= rows).  fp32
+ * accumulation, fp16 results.  The paper names small-batch products as future
+ * work (Section 7); the format and the accuracy contract are those of macko_spmv. */
+#define MACKO_MAX_BATCH 64
+MACKO_API int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void* Y_dev,
+                         int64_t ldy, void* stream);
+
 /* Grouped forms: n independent products (1 <= n <= MACKO_MAX_GROUP) enqueued
  * with as few kernel launches as possible -- one, when every matrix takes the
  * wavefront-per-row kernel.  Intended for products that share an input or have

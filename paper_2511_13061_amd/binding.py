@@ -15,7 +15,7 @@ _lib = None
 EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -98,6 +98,7 @@ def load_library():
     vpp = ctypes.POINTER(vp)
     lib.macko_spmv_group.argtypes = [ci, vpp, vpp, vpp, vp]
     lib.macko_dense_gemv_group.argtypes = [ci, vpp, i64p, i64p, i64p, vpp, vpp, vp]
+    lib.macko_spmm.argtypes = [vp, ci, vp, i64, vp, i64, vp]
     lib.macko_destroy.argtypes = [vp]
     lib.macko_destroy.restype = None
     lib.macko_status_string.argtypes = [ci]
@@ -254,6 +255,19 @@ class MackoMatrix:
         _check(load_library().macko_spmv(self._h, _dev_ptr(x_dev), _dev_ptr(y_dev), _stream_ptr(stream)),
                "macko_spmv")
         return y_dev
+
+    def spmm(self, X_dev, Y_dev=None, stream=None):
+        """Y[b] = W X[b] for a torch float16 CUDA matrix X_dev [batch, cols]; returns [batch, rows]."""
+        import torch
+        if X_dev.dim() != 2 or X_dev.stride(1) != 1:
+            raise ValueError("X_dev must be a row-major [batch, cols] tensor")
+        batch = X_dev.shape[0]
+        if Y_dev is None:
+            Y_dev = torch.empty((batch, self.rows), dtype=torch.float16, device=X_dev.device)
+        _check(load_library().macko_spmm(self._h, batch, _dev_ptr(X_dev), X_dev.stride(0) if batch > 1 else max(X_dev.shape[1], 1),
+                                         _dev_ptr(Y_dev), Y_dev.stride(0) if batch > 1 else max(Y_dev.shape[1], 1),
+                                         _stream_ptr(stream)), "macko_spmm")
+        return Y_dev
 
     def spmv_raw(self, x_ptr: int, y_ptr: int, stream_ptr: int) -> int:
         """Unchecked call for timing loops; returns the status."""

@@ -93,6 +93,31 @@ __device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
   return (float)__builtin_bit_cast(_Float16, b);
 }
 
+// ---- row cursor of the wavefront-per-row kernels ------------------------------
+// A wavefront keeps the pointers of its (at most 64) rows in two registers, lane i
+// holding row i's; the scalar bounds of the current row are read out of them.
+struct RowCursor {
+  int i;               // row index within the block (== nb when exhausted)
+  uint32_t start, end; // its entry range
+  uint32_t a0;         // start rounded down to 8 entries (reverse-offset alignment)
+  int nsteps, step;
+};
+
+// Move the cursor to the first non-empty row at or after cur.i.  Only lanes
+// below nb hold pointers of the wavefront's rows; others are never selected.
+__device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t rp_lo, uint32_t rp_hi) {
+  cur.start = cur.end = 0;
+  while (cur.i < nb) {
+    cur.start = (uint32_t)__builtin_amdgcn_readlane((int)rp_lo, cur.i);
+    cur.end = (uint32_t)__builtin_amdgcn_readlane((int)rp_hi, cur.i);
+    if (cur.end > cur.start) break;
+    ++cur.i;
+  }
+  cur.a0 = cur.start & ~7u;
+  cur.nsteps = (int)((cur.end - cur.a0 + 511u) >> 9);
+  cur.step = 0;
+}
+
 // Staging of x (fp16[cols], global) into the LDS layout described above, split
 // in two so that a kernel can put its own first loads between the halves:
 // stage_x_begin only issues global loads into registers (up to XR 16-byte chunks

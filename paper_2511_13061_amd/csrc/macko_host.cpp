@@ -373,6 +373,18 @@ int macko_spmv_group(int n, const macko_handle_t* handles, const void* const* x_
   return macko::launch_spmv_group(m, p, static_cast<hipStream_t>(stream));
 }
 
+int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void* Y_dev, int64_t ldy,
+               void* stream) {
+  if (!h || batch < 0 || batch > MACKO_MAX_BATCH) return MACKO_E_INVALID_ARG;
+  if (!h->bound) return MACKO_E_NOT_BOUND;
+  if (h->rows == 0 || batch == 0) return MACKO_OK;
+  if (ldx < h->cols || ldy < h->rows) return MACKO_E_INVALID_ARG;
+  int st = check_vec_ptrs(X_dev, Y_dev, h->cols);
+  if (st != MACKO_OK) return st;
+  macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz, nullptr, nullptr};
+  return macko::launch_spmm(p, X_dev, ldx, Y_dev, ldy, batch, static_cast<hipStream_t>(stream));
+}
+
 int macko_dense_gemv(const void* W_dev, int64_t rows, int64_t cols, int64_t ld, const void* x_dev,
                      void* y_dev, void* stream) {
   return macko_dense_gemv_group(1, &W_dev, &rows, &cols, &ld, &x_dev, &y_dev, stream);

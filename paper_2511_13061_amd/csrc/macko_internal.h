@@ -56,6 +56,9 @@ struct GemvProblem {
 // n independent products, as few kernel launches as the shapes allow (1 <= n <= kMaxGroup)
 int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream);
 int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream);
+// batch products with one matrix: Y[b] = W X[b], vectors ldx / ldy elements apart (p.x, p.y unused)
+int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64_t ldy, int batch,
+                hipStream_t stream);
 // GPU encoder: counting pass + fill pass.  Allocates *values, *deltas, *row_ptr with hipMalloc.
 int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, hipStream_t stream,
                      uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,

@@ -1,0 +1,286 @@
+// Small-batch product Y = W X^T for the MACKO format on gfx950: the same
+// wavefront-per-row streaming kernel as the matrix-vector product (Section 4.4
+// of the paper), with the decode done once per stored entry and reused for
+// BT = 2, 4 or 8 activation vectors.  The paper leaves matrix-matrix products
+// with small batch dimensions as future work (Section 7); this is the natural
+// extension: the streamed bytes per entry stay 2.5, the arithmetic per byte
+// grows with the batch.
+//
+// LDS holds the activations interleaved by column: the BT values of column c
+// are adjacent (2*BT bytes), so one gather address per entry fetches all of
+// them with a single ds_read_b32 / b64 / b128.  Guards of zeros in front of and
+// behind the columns play the same role as in the matrix-vector kernel.
+#include "macko_device.h"
+#include "macko_internal.h"
+
+namespace macko {
+namespace {
+
+template <int BT> struct XVec;
+template <> struct XVec<2> { using type = uint32_t; };
+template <> struct XVec<4> { using type = uint2; };
+template <> struct XVec<8> { using type = uint4; };
+
+template <int BT>
+__device__ __forceinline__ void unpack_x(const typename XVec<BT>::type& v, float* out);
+template <>
+__device__ __forceinline__ void unpack_x<2>(const uint32_t& v, float* out) {
+  out[0] = f16_bits_to_f32((uint16_t)(v & 0xFFFFu));
+  out[1] = f16_bits_to_f32((uint16_t)(v >> 16));
+}
+template <>
+__device__ __forceinline__ void unpack_x<4>(const uint2& v, float* out) {
+  unpack_x<2>(v.x, out);
+  unpack_x<2>(v.y, out + 2);
+}
+template <>
+__device__ __forceinline__ void unpack_x<8>(const uint4& v, float* out) {
+  unpack_x<2>(v.x, out);
+  unpack_x<2>(v.y, out + 2);
+  unpack_x<2>(v.z, out + 4);
+  unpack_x<2>(v.w, out + 6);
+}
+
+// Copy X (batch vectors of `cols` fp16, vector b at X + b*ldx) into LDS, interleaved
+// by column, between zero guards of kFrontPad*BT and kBackPad*BT bytes.  Vectors
+// b >= batch are filled with zeros.  Ends with a barrier.
+template <int BT>
+__device__ __forceinline__ void stage_X_interleaved(unsigned char* lds, const uint16_t* __restrict__ X,
+                                                    int64_t ldx, int batch, int cols) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int chunks = (cols + 7) >> 3;
+  const bool vec_ok = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && (ldx & 7) == 0;
+  uint4* lds16 = reinterpret_cast<uint4*>(lds);
+  const uint4 zero = make_uint4(0, 0, 0, 0);
+  const int front16 = kFrontPad * BT / 16, back16 = kBackPad * BT / 16, body16 = chunks * BT;   // 16-byte units
+  for (int i = tid; i < front16 + back16; i += nt) lds16[i < front16 ? i : i + body16] = zero;
+  uint16_t* xs = reinterpret_cast<uint16_t*>(lds + kFrontPad * BT);
+  for (int t = tid; t < chunks; t += nt) {
+    uint16_t h[BT][8];
+#pragma unroll
+    for (int b = 0; b < BT; ++b) {
+      const uint16_t* src = X + (int64_t)b * ldx + 8 * t;
+      if (b < batch && vec_ok && 8 * t + 8 <= cols) {
+        const uint4 q = *reinterpret_cast<const uint4*>(src);
+        const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) h[b][k] = (uint16_t)(u[k >> 1] >> (16 * (k & 1)));
+      } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) h[b][k] = (b < batch && 8 * t + k < cols) ? src[k] : (uint16_t)0;
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      uint32_t* dst = reinterpret_cast<uint32_t*>(xs + (size_t)(8 * t + k) * BT);
+#pragma unroll
+      for (int b = 0; b < BT; b += 2) dst[b >> 1] = (uint32_t)h[b][k] | ((uint32_t)h[b + 1][k] << 16);
+    }
+  }
+  __syncthreads();
+}
+
+template <int BT>
+__global__ void __launch_bounds__(1024)
+spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
+                     const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ X, int64_t ldx,
+                     uint16_t* __restrict__ Y, int64_t ldy, int batch, int rows, int cols, int rows_per_wg) {
+  constexpr int RING = 2;
+  using XV = typename XVec<BT>::type;
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int row_begin = (int)blockIdx.x * rows_per_wg;
+  const int row_end = min(rows, row_begin + rows_per_wg);
+  const int nwaves = blockDim.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned char* xbase = lds + kFrontPad * BT;   // LDS address of column 0
+  const uint32_t lane8 = 8u * lane;
+  const int per_wave = (row_end - row_begin + nwaves - 1) / nwaves;
+  const int blk = min(row_end, row_begin + wave * per_wave);
+  const int nb = min(row_end, blk + per_wave) - blk;   // at most 64: the host caps rows_per_wg
+
+  uint32_t chunk = 0;
+  RowCursor ld, cp;
+  uint32_t wq[RING];
+  uint4 vq[RING];
+  const int r = min(blk + lane, rows - 1);             // unconditional loads, clamped to the last row
+  const uint32_t rp_lo = row_ptr[r];
+  const uint32_t rp_hi = row_ptr[r + 1];
+
+  auto issue = [&](int j) {
+    if (ld.i < nb) {
+      const uint32_t e0 = ld.a0 + 512u * ld.step + lane8;
+      chunk = min(e0, ld.end - 1u) >> 3;
+      if (++ld.step == ld.nsteps) {
+        ++ld.i;
+        seek_nonempty(ld, nb, rp_lo, rp_hi);
+      }
+    } else {
+      chunk = 0;
+    }
+    wq[j] = deltas[chunk];
+    vq[j] = values[chunk];
+  };
+  ld.i = 0;
+  seek_nonempty(ld, nb, rp_lo, rp_hi);
+  cp = ld;
+#pragma unroll
+  for (int j = 0; j < RING; ++j) issue(j);
+  stage_X_interleaved<BT>(lds, X, ldx, batch, cols);    // ends with a barrier
+
+  float yv[BT], acc[BT];
+#pragma unroll
+  for (int b = 0; b < BT; ++b) yv[b] = acc[b] = 0.0f;
+  int base2 = 0;
+  while (cp.i < nb) {
+#pragma unroll
+    for (int j = 0; j < RING; ++j) {
+      uint32_t w = wq[j];
+      uint4 v = vq[j];
+      const bool live = cp.i < nb;
+      if (!live) base2 = 0;
+      const uint32_t end_eff = live ? cp.end : 0u;
+      const uint32_t e0 = cp.a0 + 512u * cp.step + lane8;
+      if (!live || cp.step == cp.nsteps - 1) {
+        const uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;
+        w = nv != 0 ? w : 0u;
+        v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
+        v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
+        v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
+        v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
+      }
+      const uint32_t lo2 = (w << 1) & 0x1E1E1E1Eu;
+      const uint32_t hi2 = (w >> 3) & 0x1E1E1E1Eu;
+      uint32_t P = lo2 + hi2;
+      P = lshl_add<8>(P, P);
+      P = lshl_add<16>(P, P);
+      const uint32_t E = lshl_add<8>(P, lo2);
+      const uint32_t tot = (P >> 24) + 16u;
+      const uint32_t incl = wave_incl_scan_u32(tot);
+      if (live && cp.step == 0) {
+        base2 = 0;
+        const int before = (int)(cp.start - cp.a0);
+        if (before > 0) {
+          const int k = before - 1;
+          const uint32_t src = __builtin_amdgcn_readfirstlane((k & 1) ? P : E);
+          base2 = -(int)(((src >> (8 * (k >> 1))) & 0xFFu) + 2u * (uint32_t)(k + 1));
+        }
+      }
+      const uint32_t E2 = E + 0x0C080400u;
+      const uint32_t P2 = P + 0x0E0A0602u;
+      const int lanebase = base2 + (int)(incl - tot);
+      const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const uint32_t word = (k & 1) ? P2 : E2;
+        const int q = lanebase + (int)((word >> (8 * (k >> 1))) & 0xFFu);   // byte offset for one vector
+        const XV xraw = *reinterpret_cast<const XV*>(xbase + q * BT);
+        float xf[BT];
+        unpack_x<BT>(xraw, xf);
+        const float wk = f16_bits_to_f32((uint16_t)(vv[k >> 1] >> (16 * (k & 1))));
+#pragma unroll
+        for (int b = 0; b < BT; ++b) acc[b] = fmaf(wk, xf[b], acc[b]);
+      }
+      issue(j);
+      base2 += (int)__builtin_amdgcn_readlane((int)incl, 63);
+      if (live && ++cp.step == cp.nsteps) {
+#pragma unroll
+        for (int b = 0; b < BT; ++b) {
+          const float total = wave_sum_to_last_lane(acc[b]);
+          const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), 63);
+          yv[b] = lane == cp.i ? __builtin_bit_cast(float, tbits) : yv[b];
+          acc[b] = 0.0f;
+        }
+        ++cp.i;
+        seek_nonempty(cp, nb, rp_lo, rp_hi);
+      }
+    }
+  }
+  if (lane < nb) {
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+      if (b < batch) Y[(int64_t)b * ldy + blk + lane] = f32_to_f16_bits(yv[b]);
+  }
+}
+
+__global__ void __launch_bounds__(256) zero_Y_kernel(uint16_t* __restrict__ Y, int64_t ldy, int batch, int rows) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows)
+    for (int b = 0; b < batch; ++b) Y[(int64_t)b * ldy + i] = 0;
+}
+
+template <int BT>
+int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y, int64_t ldy, int batch,
+              hipStream_t stream) {
+  const int cus = device_cu_count();
+  const int64_t lds = (int64_t)BT * lds_bytes_for(p.cols);
+  const int block = lds > 48 * 1024 ? 1024 : 512;
+  const int nwaves = block / 64;
+  const int64_t avg = p.pad_nnz / p.rows;
+  const int64_t steps_per_row = std::max<int64_t>(1, (avg + 511) / 512);
+  const int64_t want = (16 + steps_per_row - 1) / steps_per_row;
+  const int64_t cap = std::max<int64_t>(1, p.rows / ((int64_t)cus * 16));
+  const int64_t rpw = std::min<int64_t>(std::min(want, cap) * nwaves, 64 * nwaves);
+  const int64_t grid = (p.rows + rpw - 1) / rpw;
+  auto kfn = spmm_wave_row_kernel<BT>;
+  if (lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds, stream,
+                     reinterpret_cast<const uint4*>(p.values), reinterpret_cast<const uint32_t*>(p.deltas),
+                     p.row_ptr, X, ldx, Y, ldy, batch, (int)p.rows, (int)p.cols, (int)rpw);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
+
+}  // namespace
+
+// Y[b][r] = sum over row r of W * X[b][column], b < batch.  The batch is cut into
+// pieces of 8, 4, 2 or 1 vectors, each the largest that fits LDS; single vectors
+// (and matrices with short rows) go through the matrix-vector path.
+int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64_t ldy, int batch,
+                hipStream_t stream) {
+  const uint16_t* Xp = static_cast<const uint16_t*>(X);
+  uint16_t* Yp = static_cast<uint16_t*>(Y);
+  if (p.rows == 0 || batch == 0) return MACKO_OK;
+  if (p.pad_nnz == 0) {
+    hipLaunchKernelGGL(zero_Y_kernel, dim3((unsigned)((p.rows + 255) / 256)), dim3(256), 0, stream, Yp, ldy,
+                       batch, (int)p.rows);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? MACKO_OK : hip_fail(e);
+  }
+  const int64_t one = lds_bytes_for(p.cols);
+  const int64_t limit = 160 * 1024 - 64;
+  const bool long_rows = p.pad_nnz / p.rows >= 384;
+  int done = 0;
+  while (done < batch) {
+    const int left = batch - done;
+    const uint16_t* Xb = Xp + (int64_t)done * ldx;
+    uint16_t* Yb = Yp + (int64_t)done * ldy;
+    int st;
+    int take;
+    if (long_rows && left >= 5 && 8 * one <= limit) {
+      take = std::min(left, 8);
+      st = launch_bt<8>(p, Xb, ldx, Yb, ldy, take, stream);
+    } else if (long_rows && left >= 3 && 4 * one <= limit) {
+      take = std::min(left, 4);
+      st = launch_bt<4>(p, Xb, ldx, Yb, ldy, take, stream);
+    } else if (long_rows && left >= 2 && 2 * one <= limit) {
+      take = 2;
+      st = launch_bt<2>(p, Xb, ldx, Yb, ldy, take, stream);
+    } else {
+      take = 1;
+      SpmvProblem q = p;
+      q.x = Xb;
+      q.y = Yb;
+      st = launch_spmv_group(1, &q, stream);
+    }
+    if (st != MACKO_OK) return st;
+    done += take;
+  }
+  return MACKO_OK;
+}
+
+}  // namespace macko

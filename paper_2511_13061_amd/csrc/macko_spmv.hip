@@ -121,28 +121,6 @@ __device__ __forceinline__ float gather_x(const unsigned char* xbase, int q) {
   return f16_bits_to_f32(*reinterpret_cast<const uint16_t*>(xbase + q));
 }
 
-struct RowCursor {
-  int i;               // row index within the block (== nb when exhausted)
-  uint32_t start, end; // its entry range
-  uint32_t a0;         // start rounded down to 8 entries (reverse-offset alignment)
-  int nsteps, step;
-};
-
-// Move the cursor to the first non-empty row at or after cur.i.  Only lanes
-// below nb hold pointers of the wavefront's rows; others are never selected.
-__device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t rp_lo, uint32_t rp_hi) {
-  cur.start = cur.end = 0;
-  while (cur.i < nb) {
-    cur.start = (uint32_t)__builtin_amdgcn_readlane((int)rp_lo, cur.i);
-    cur.end = (uint32_t)__builtin_amdgcn_readlane((int)rp_hi, cur.i);
-    if (cur.end > cur.start) break;
-    ++cur.i;
-  }
-  cur.a0 = cur.start & ~7u;
-  cur.nsteps = (int)((cur.end - cur.a0 + 511u) >> 9);
-  cur.step = 0;
-}
-
 // One matrix of a grouped launch: workgroups [wg_begin, next wg_begin) work on it.
 struct SpmvMat {
   const uint4* values;
@@ -371,17 +349,23 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;
   const Tuning& t = tuning();
   const int cus = device_cu_count();
-  const int block = t.spmv_block ? (int)t.spmv_block : 512;
-  const int nwaves = block / 64;
-
   // rows that will share the grouped launch (decides how much work a wavefront gets)
   auto wants_wave_row = [&](const SpmvProblem& p) {
     if (p.rows == 0 || p.pad_nnz == 0) return false;
     if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
     return p.pad_nnz / p.rows >= 384 && lds_bytes_for(p.cols) <= kMaxLdsBytes;
   };
-  int64_t group_rows = 0;
-  for (int i = 0; i < n; ++i) group_rows += wants_wave_row(problems[i]) ? problems[i].rows : 0;
+  int64_t group_rows = 0, group_lds = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!wants_wave_row(problems[i])) continue;
+    group_rows += problems[i].rows;
+    group_lds = std::max(group_lds, lds_bytes_for(problems[i].cols));
+  }
+  // Every workgroup holds its own copy of x in LDS.  When that copy is large
+  // (more than ~24 K columns) only one to three workgroups fit a CU, so each one
+  // brings 16 wavefronts instead of 8 to keep the CU's load queues full.
+  const int block = t.spmv_block ? (int)t.spmv_block : (group_lds > 48 * 1024 ? 1024 : 512);
+  const int nwaves = block / 64;
 
   SpmvGroupArgs args{};
   int64_t total_wgs = 0, max_lds = 0;

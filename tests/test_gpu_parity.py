@@ -242,6 +242,64 @@ def test_dense_gemv_group():
         check_y(y, W, x, f"gemv group {shp}")
 
 
+# ------------------------------------------------------------------ small-batch products
+
+def check_Y(Y_dev, W, X, what):
+    for b in range(X.shape[0]):
+        check_y(Y_dev[b], W, X[b], f"{what} vector {b}")
+
+
+@pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 7, 8, 11, 16])
+def test_spmm_batches(batch):
+    W = wl.bernoulli(333, 2000, 0.5, 0.02, 51, 1)
+    W[5] = 0
+    W[100:110] = 0
+    X = np.stack([wl.x_vector(2000, 51, 10 + b) for b in range(batch)])
+    m = M.encode(W).to_device()
+    Y = m.spmm(to_dev(X))
+    torch.cuda.synchronize()
+    assert Y.shape == (batch, 333)
+    check_Y(Y, W, X, f"batch {batch}")
+    assert (Y[:, 5] == 0).all() and (Y[:, 100:110] == 0).all()
+    # each vector agrees with the matrix-vector kernel to within both tolerances
+    y0 = m.spmv(to_dev(X[0]))
+    assert torch.allclose(Y[0].float(), y0.float(), atol=2e-3, rtol=2e-2)
+
+
+def test_spmm_shapes_strides_and_fallbacks():
+    cases = [
+        (wl.bernoulli(70, 5000, 0.6, 0.02, 52, 1), 8),        # long rows
+        (wl.bernoulli(40, 12000, 0.3, 0.02, 52, 2), 8),       # 8 vectors do not fit LDS: pieces of 4
+        (wl.bernoulli(24, 30000, 0.2, 0.02, 52, 3), 6),       # pieces of 2
+        (wl.bernoulli(10, 100000, 0.2, 0.02, 52, 4), 3),      # x larger than LDS: vector by vector
+        (wl.bernoulli(200, 300, 0.5, 0.02, 52, 5), 4),        # short rows: vector by vector
+        (wl.config4(rows=128, cols=2048).W, 8),
+        (np.zeros((50, 640), dtype=np.uint16), 5),
+        (wl.bernoulli(129, 1001, 1.0, 0.02, 52, 6), 8),       # dense, odd column count
+    ]
+    for i, (W, batch) in enumerate(cases):
+        C = W.shape[1]
+        X = np.stack([wl.x_vector(C, 52, 100 * i + b) for b in range(batch)])
+        m = M.encode(W).to_device()
+        # strided, unaligned X and Y
+        Xbuf = torch.zeros((batch, C + 9), dtype=torch.float16, device="cuda")
+        Xbuf[:, 1:C + 1] = to_dev(X)
+        Ybuf = torch.full((batch, W.shape[0] + 5), 7.0, dtype=torch.float16, device="cuda")
+        m.spmm(Xbuf[:, 1:C + 1], Ybuf[:, 3:3 + W.shape[0]])
+        torch.cuda.synchronize()
+        check_Y(Ybuf[:, 3:3 + W.shape[0]], W, X, f"case {i}")
+        assert (Ybuf[:, :3] == 7).all() and (Ybuf[:, 3 + W.shape[0]:] == 7).all()
+
+
+def test_spmm_llama_shape_full_size():
+    case = next(iter(wl.config2()))
+    X = np.stack([wl.x_vector(case.cols, 53, b) for b in range(8)])
+    m = M.encode(case.W).to_device()
+    Y = m.spmm(to_dev(X))
+    torch.cuda.synchronize()
+    check_Y(Y, case.W, X, case.name)
+
+
 # ------------------------------------------------------------------ GPU encoder
 
 ENC_CASES = {

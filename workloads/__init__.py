@@ -189,3 +189,19 @@ def config5_layer(seed: int = BASE_SEED):
     for i, (tag, r, c) in enumerate(LLAMA2_13B_SHAPES):
         yield Case(f"c5_{tag}_{r}x{c}_s50", half_row_matrix(r, c, 500 + i, seed=seed),
                    x_vector(c, seed, 500 + i))
+
+
+# Appendix D of the paper: the matrix shapes (rows, cols) its runtime sweep uses.
+APPENDIX_D_SHAPES = [
+    (4096, 4096), (8192, 8192), (8192, 29568), (32000, 5120), (32000, 8192), (28672, 8192), (5120, 5120),
+    (5120, 13824), (3584, 20480), (4096, 11008), (13824, 5120), (18944, 3584), (14336, 4096), (4096, 14336),
+    (8192, 28672), (11008, 4096), (32000, 4096), (20480, 3584), (3584, 18944), (21504, 7168), (7168, 7168),
+    (28672, 7168), (7168, 28672), (27648, 9216), (9216, 9216), (36864, 9216), (9216, 36864), (36864, 12288),
+    (12288, 12288), (49152, 12288), (12288, 49152),
+]
+
+
+def appendix_d_case(rows: int, cols: int, sparsity_pct: int = 50, seed: int = BASE_SEED) -> Case:
+    """One shape of the Appendix-D list with exactly (1 - s) * cols kept per row."""
+    W = half_row_matrix(rows, cols, 7000 + (rows * 31 + cols) % 997, sparsity=sparsity_pct / 100.0, seed=seed)
+    return Case(f"appD_{rows}x{cols}_s{sparsity_pct}", W, x_vector(cols, seed, 7000))
