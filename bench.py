@@ -149,6 +149,7 @@ def main():
     ap.add_argument("--stack", action="store_true", help="also time the Llama2-13B-shaped 32-layer stack")
     ap.add_argument("--shapes", action="store_true",
                     help="also time every shape of the paper's Appendix D at 50 %% sparsity")
+    ap.add_argument("--spmm", action="store_true", help="also time the small-batch product macko_spmm")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe for rocprofv3 --pmc: a 1 GiB device copy of known size, then a "
@@ -357,6 +358,37 @@ def main():
             torch.cuda.empty_cache()
         extra["sweep_36864x12288"] = sweep
 
+    # ---- optional: small-batch products (batch 1..8) on the layer's shapes --------
+    if args.spmm:
+        lib = M.load_library()
+        table = {}
+        for case, (tag, _) in zip(cases, layer_plan):
+            so = sparse_ops[tag]
+            copies = len(so.handles)
+            Wd = [torch.from_numpy(case.W.view(np.float16)).cuda() for _ in range(8)]
+            row = {}
+            for B in (1, 2, 4, 8):
+                X = torch.randn(B, case.cols, device="cuda", dtype=torch.float16)
+                Y = torch.empty(B, case.rows, device="cuda", dtype=torch.float16)
+
+                def f(i):
+                    st = lib.macko_spmm(so.handles[i % copies]._h, B, X.data_ptr(), X.stride(0), Y.data_ptr(),
+                                        Y.stride(0), stream_ptr)
+                    if st != 0:
+                        raise RuntimeError(f"macko_spmm failed with status {st}")
+
+                def g(i):
+                    torch.matmul(X, Wd[i % 8].t(), out=Y)          # library GEMM on the dense matrix
+
+                ts = time_region(torch, f, 10, 200) / 200
+                td = time_region(torch, g, 10, 200) / 200
+                row[f"batch{B}"] = {"macko_us": round(ts * 1e6, 2), "dense_library_gemm_us": round(td * 1e6, 2),
+                                    "format_GBps": round(so.bytes / ts / 1e9)}
+            table[f"{case.rows}x{case.cols}"] = row
+            log(f"  spmm {case.rows}x{case.cols}: {row}")
+            del Wd
+        extra["spmm_small_batch"] = table
+
     # ---- optional: every shape of Appendix D at 50 % --------------------------
     if args.shapes:
         table = {}
@@ -393,12 +425,33 @@ def main():
                         for k in range(mult):
                             ops[tag].launch(layer * mult + k, stream_ptr)
             return run
-        ts = time_region(torch, stack_pass(ops13), 2, 10) / 10
-        td = time_region(torch, stack_pass(dops13), 2, 10) / 10
+
+        def grouped_stack(kind):
+            groups = []
+            for layer in range(32):
+                def pick(tag, ks):
+                    op = (ops13 if kind == "sparse" else dops13)[tag]
+                    mult = dict(plan13)[tag]
+                    mats = [(op.handles if kind == "sparse" else op.W)[layer * mult + k] for k in ks]
+                    return mats, [op.x] * len(ks), [torch.empty_like(op.y) for _ in ks]
+                Group = M.SpmvGroup if kind == "sparse" else M.GemvGroup
+                groups += [Group(*pick("qkvo", [0, 1, 2])), Group(*pick("qkvo", [3])),
+                           Group(*pick("gate_up", [0, 1])), Group(*pick("down", [0]))]
+
+            def run(_i):
+                for g in groups:
+                    g.launch_raw(stream_ptr)
+            return run
+
+        ts1 = time_region(torch, stack_pass(ops13), 2, 10) / 10
+        td1 = time_region(torch, stack_pass(dops13), 2, 10) / 10
+        ts = time_region(torch, grouped_stack("sparse"), 2, 10) / 10
+        td = time_region(torch, grouped_stack("dense"), 2, 10) / 10
         sb = 32 * sum(m * ops13[t].bytes for t, m in plan13)
         db = 32 * sum(m * dops13[t].bytes for t, m in plan13)
         extra["stack_llama2_13b_32layers"] = {
-            "launches": 224, "macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
+            "launches": 128, "macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
+            "separate_launches_224": {"macko_us": round(ts1 * 1e6, 1), "dense_us": round(td1 * 1e6, 1)},
             "macko_GB": round(sb / 1e9, 3), "dense_GB": round(db / 1e9, 3),
             "macko_GBps": round(sb / ts / 1e9, 1), "dense_GBps": round(db / td / 1e9, 1),
             "speedup_vs_dense": round(td / ts, 3),
