@@ -183,7 +183,11 @@ MACKO_API int macko_last_hip_error(void);
  *   "spmv_block"        threads per workgroup for spmv (multiple of 64, <= 1024), 0 auto
  *   "spmv_rows_per_wg"  rows handled by one workgroup, 0 auto
  *   "spmv_ring"         steps of loads kept in flight per wavefront (2 or 4), 0 auto
- *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8)  the same for the dense GEMV
+ *   "spmv_resident"     0 auto, 1 never, 2 always: launch exactly one resident round of
+ *                       workgroups (a multiple of the compute-unit count) shaped to the row counts
+ *   "spmv_wgs_per_cu"   workgroups per compute unit of such a round (1..4), 0 auto
+ *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8), "gemv_resident",
+ *   "gemv_wgs_per_cu"   the same for the dense GEMV
  * Settings are process wide and not thread safe. */
 MACKO_API int macko_set_tuning(const char* name, int64_t value);
 MACKO_API int macko_get_tuning(const char* name, int64_t* value);

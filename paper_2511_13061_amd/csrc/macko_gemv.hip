@@ -5,9 +5,15 @@
 // compared with.
 #include "macko_device.h"
 #include "macko_internal.h"
+#include "macko_plan.h"
+
+#include <climits>
 
 namespace macko {
 namespace {
+
+// launches with at most this many wavefront steps per compute unit run as one resident round
+constexpr int64_t kResidentStepsPerCu = 256;
 
 // Fast path: cols and ld multiples of 8, W 16-byte aligned.  One wavefront per
 // row; per step a lane multiplies 8 consecutive weights with 8 consecutive x.
@@ -16,32 +22,44 @@ namespace {
 // and cross row boundaries, every item issues exactly one load, and the results
 // of up to 64 rows are collected in a register and stored with one coalesced
 // store.
-// One matrix of a grouped launch: workgroups [wg_begin, next wg_begin) work on it.
+// One matrix of a grouped launch.  Its rows are dealt out evenly over its
+// workgroups: q rows each, one more for the first r of them.
 struct GemvMat {
   const uint4* W;
   const uint16_t* x;
   uint16_t* y;
   int64_t ld8;
-  int rows, cols, rows_per_wg, wg_begin;
+  int rows, cols, q, r;
+  int pad[4];
 };
+// Workgroups [wg_begin[i], wg_begin[i+1]) work on matrix i; unused slots hold INT_MAX.
 struct GemvGroupArgs {
-  int n;
+  int wg_begin[kMaxGroup];
+  int inv_nwaves;          // floor(2^20 / wavefronts per workgroup) + 1
+  int pad[7];
   GemvMat m[kMaxGroup];
 };
 
 template <int RING>
 __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs g) {
   extern __shared__ __align__(16) unsigned char lds[];
-  int mi = 0;
-  for (int i = 1; i < g.n; ++i) mi = (int)blockIdx.x >= g.m[i].wg_begin ? i : mi;
+  int mi = 0, wg0 = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) {
+    const bool in = (int)blockIdx.x >= g.wg_begin[i];
+    mi = in ? i : mi;
+    wg0 = in ? g.wg_begin[i] : wg0;
+  }
   const uint4* __restrict__ W = g.m[mi].W;
   const uint16_t* __restrict__ x = g.m[mi].x;
   uint16_t* __restrict__ y = g.m[mi].y;
   const int64_t ld8 = g.m[mi].ld8;
-  const int rows = g.m[mi].rows, cols = g.m[mi].cols, rows_per_wg = g.m[mi].rows_per_wg;
+  const int cols = g.m[mi].cols;
   const int lds_bytes = (int)lds_bytes_for(cols);
-  const int row_begin = ((int)blockIdx.x - g.m[mi].wg_begin) * rows_per_wg;
-  const int row_end = min(rows, row_begin + rows_per_wg);
+  // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
+  const int wg = (int)blockIdx.x - wg0;
+  const int row_begin = wg * g.m[mi].q + min(wg, g.m[mi].r);
+  const int wg_rows = g.m[mi].q + (wg < g.m[mi].r ? 1 : 0);
   const int nwaves = blockDim.x >> 6;
   const uint4* xs = reinterpret_cast<const uint4*>(lds + kFrontPad);
 
@@ -50,9 +68,11 @@ __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs
   const int c8 = cols >> 3;                            // 16-byte chunks per row
   const int nsteps = (c8 + 63) >> 6;
   const bool ragged = (c8 & 63) != 0;                  // last step only partly inside the row
-  const int per_wave = (row_end - row_begin + nwaves - 1) / nwaves;
-  const int wrow_begin = min(row_end, row_begin + wave * per_wave);
-  const int wrow_end = min(row_end, wrow_begin + per_wave);
+  // wg_rows / nwaves, exact for wg_rows < 2^16 (the host keeps it below)
+  const int per_wave = (int)(((uint64_t)(uint32_t)wg_rows * (uint32_t)g.inv_nwaves) >> 20);
+  const int extra = wg_rows - per_wave * nwaves;
+  const int wrow_begin = row_begin + wave * per_wave + min(wave, extra);
+  const int wrow_end = wrow_begin + per_wave + (wave < extra ? 1 : 0);
 
   int blk = wrow_begin;
   int nb = max(0, min(64, wrow_end - blk));
@@ -158,10 +178,10 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
   if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;
   const Tuning& t = tuning();
   const int cus = device_cu_count();
-  const int block = t.gemv_block ? (int)t.gemv_block : 512;
-  const int nwaves = block / 64;
-  GemvGroupArgs args{};
-  int64_t total_wgs = 0, max_lds = 0;
+  const GemvProblem* wr[kMaxGroup];
+  PlanInput in[kMaxGroup];
+  int nwr = 0;
+  int64_t max_lds = 0, total_steps = 0;
   for (int i = 0; i < n; ++i) {
     const GemvProblem& p = problems[i];
     if (p.rows == 0) continue;
@@ -177,37 +197,72 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
       if (e != hipSuccess) return hip_fail(e);
       continue;
     }
-    int64_t rpw = t.gemv_rows_per_wg;
-    if (rpw == 0) {
-      const int64_t target_wgs = (int64_t)cus * 16;
-      rpw = std::max<int64_t>((p.rows + target_wgs - 1) / target_wgs, nwaves);
+    wr[nwr] = &p;
+    in[nwr].rows = p.rows;
+    in[nwr].steps_per_row = (p.cols / 8 + 63) / 64;
+    in[nwr].lds_bytes = lds_bytes;
+    total_steps += in[nwr].rows * in[nwr].steps_per_row;
+    max_lds = std::max(max_lds, lds_bytes);
+    ++nwr;
+  }
+  if (nwr == 0) return MACKO_OK;
+
+  // same two regimes as the sparse product: one resident round of workgroups
+  // shaped to the row counts when there is little work, many workgroups otherwise
+  Plan plan;
+  bool planned = false;
+  const bool small = total_steps <= (int64_t)cus * kResidentStepsPerCu;
+  if (t.gemv_rows_per_wg == 0 && (t.gemv_resident == 2 || (t.gemv_resident == 0 && small)))
+    planned = plan_resident(plan, nwr, in, cus, (int)t.gemv_block, (int)t.gemv_wgs_per_cu);
+  if (!planned) {
+    const int block = t.gemv_block ? (int)t.gemv_block : 512;
+    const int nwaves = block / 64;
+    int64_t rpw[kMaxGroup];
+    for (int i = 0; i < nwr; ++i) {
+      rpw[i] = t.gemv_rows_per_wg;
+      if (rpw[i] == 0) {
+        const int64_t target_wgs = (int64_t)cus * 16;
+        rpw[i] = std::max<int64_t>((in[i].rows + target_wgs - 1) / target_wgs, nwaves);
+      }
+      rpw[i] = std::min<int64_t>(rpw[i], 65535);        // the kernel's division by the wavefront count
     }
-    GemvMat& m = args.m[args.n++];
+    plan.block = block;
+    plan.total_wgs = 0;
+    for (int i = 0; i < nwr; ++i) {
+      plan_split(plan.m[i], in[i].rows, (in[i].rows + rpw[i] - 1) / rpw[i]);
+      plan.total_wgs += plan.m[i].nwg;
+    }
+  }
+  if (plan.total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+
+  GemvGroupArgs args{};
+  args.inv_nwaves = (1 << 20) / (plan.block / 64) + 1;
+  int64_t wg_begin = 0;
+  for (int i = 0; i < kMaxGroup; ++i) args.wg_begin[i] = INT32_MAX;
+  for (int i = 0; i < nwr; ++i) {
+    const GemvProblem& p = *wr[i];
+    GemvMat& m = args.m[i];
     m.W = static_cast<const uint4*>(p.W);
     m.x = static_cast<const uint16_t*>(p.x);
     m.y = static_cast<uint16_t*>(p.y);
     m.ld8 = p.ld / 8;
     m.rows = (int)p.rows;
     m.cols = (int)p.cols;
-    m.rows_per_wg = (int)rpw;
-    m.wg_begin = (int)total_wgs;
-    total_wgs += (p.rows + rpw - 1) / rpw;
-    max_lds = std::max(max_lds, lds_bytes);
-    if (total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+    m.q = plan.m[i].q;
+    m.r = plan.m[i].r;
+    args.wg_begin[i] = (int)wg_begin;
+    wg_begin += plan.m[i].nwg;
   }
-  if (args.n > 0) {
-    auto kfn = t.gemv_ring == 2 ? gemv_wave_row_kernel<2>
-               : t.gemv_ring == 8 ? gemv_wave_row_kernel<8> : gemv_wave_row_kernel<4>;
-    if (max_lds > 64 * 1024) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
-      if (e != hipSuccess) return hip_fail(e);
-    }
-    hipLaunchKernelGGL(kfn, dim3((unsigned)total_wgs), dim3(block), (size_t)max_lds, stream, args);
-    hipError_t e = hipGetLastError();
+  auto kfn = t.gemv_ring == 2 ? gemv_wave_row_kernel<2>
+             : t.gemv_ring == 8 ? gemv_wave_row_kernel<8> : gemv_wave_row_kernel<4>;
+  if (max_lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
     if (e != hipSuccess) return hip_fail(e);
   }
-  return MACKO_OK;
+  hipLaunchKernelGGL(kfn, dim3((unsigned)plan.total_wgs), dim3(plan.block), (size_t)max_lds, stream, args);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
 }
 
 }  // namespace macko

@@ -9,6 +9,9 @@
 // LDS, products are accumulated in fp32 and reduced over the wavefront with DPP.
 #include "macko_device.h"
 #include "macko_internal.h"
+#include "macko_plan.h"
+
+#include <climits>
 
 namespace macko {
 namespace {
@@ -105,7 +108,7 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
 // ahead of the arithmetic and cross row boundaries, so the memory pipeline does
 // not drain between rows.  Every item issues exactly one deltas load and one
 // values load, unconditionally (lanes past the row end re-read the row's last
-// chunk, items past the wavefront's last row read chunk 0 of the arrays), which
+// chunk, items past the wavefront's last row re-read the last chunk once more), which
 // lets the compiler count outstanding loads exactly.
 //
 // Entries of neighbouring rows that share a lane's 8-entry chunk:
@@ -121,17 +124,23 @@ __device__ __forceinline__ float gather_x(const unsigned char* xbase, int q) {
   return f16_bits_to_f32(*reinterpret_cast<const uint16_t*>(xbase + q));
 }
 
-// One matrix of a grouped launch: workgroups [wg_begin, next wg_begin) work on it.
+// One matrix of a grouped launch.  Its rows are dealt out evenly over its
+// workgroups: q rows each, one more for the first r of them.
 struct SpmvMat {
   const uint4* values;
   const uint32_t* deltas;
   const uint32_t* row_ptr;
   const uint16_t* x;
   uint16_t* y;
-  int rows, cols, rows_per_wg, wg_begin;
+  int rows, cols, q, r;
+  int pad[2];
 };
+// Workgroups [wg_begin[i], wg_begin[i+1]) work on matrix i; unused slots hold
+// INT_MAX.  The header comes first so that one scalar load fetches all of it.
 struct SpmvGroupArgs {
-  int n;
+  int wg_begin[kMaxGroup];
+  int inv_nwaves;          // floor(65536 / wavefronts per workgroup) + 1
+  int pad[7];
   SpmvMat m[kMaxGroup];
 };
 
@@ -139,25 +148,33 @@ template <int RING, bool SIMPLE>
 __global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs g) {
   extern __shared__ __align__(16) unsigned char lds[];
   // which matrix of the group this workgroup belongs to (uniform)
-  int mi = 0;
-  for (int i = 1; i < g.n; ++i) mi = (int)blockIdx.x >= g.m[i].wg_begin ? i : mi;
+  int mi = 0, wg0 = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) {
+    const bool in = (int)blockIdx.x >= g.wg_begin[i];
+    mi = in ? i : mi;
+    wg0 = in ? g.wg_begin[i] : wg0;
+  }
   const uint4* __restrict__ values = g.m[mi].values;
   const uint32_t* __restrict__ deltas = g.m[mi].deltas;
   const uint32_t* __restrict__ row_ptr = g.m[mi].row_ptr;
   const uint16_t* __restrict__ x = g.m[mi].x;
   uint16_t* __restrict__ y = g.m[mi].y;
-  const int rows = g.m[mi].rows, cols = g.m[mi].cols, rows_per_wg = g.m[mi].rows_per_wg;
+  const int rows = g.m[mi].rows, cols = g.m[mi].cols;
   const int lds_bytes = (int)lds_bytes_for(cols);
-  const int row_begin = ((int)blockIdx.x - g.m[mi].wg_begin) * rows_per_wg;
-  const int row_end = min(rows, row_begin + rows_per_wg);
+  // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
+  const int wg = (int)blockIdx.x - wg0;
+  const int row_begin = wg * g.m[mi].q + min(wg, g.m[mi].r);
+  const int wg_rows = g.m[mi].q + (wg < g.m[mi].r ? 1 : 0);
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const unsigned char* xbase = lds + kFrontPad;       // LDS address of x[0]
   const uint32_t lane8 = 8u * lane;
-  const int per_wave = (row_end - row_begin + nwaves - 1) / nwaves;
-  const int wrow_begin = min(row_end, row_begin + wave * per_wave);
-  const int wrow_end = min(row_end, wrow_begin + per_wave);
+  const int per_wave = (wg_rows * g.inv_nwaves) >> 16;   // wg_rows / nwaves (exact for wg_rows <= 1024)
+  const int extra = wg_rows - per_wave * nwaves;         // wg_rows % nwaves
+  const int wrow_begin = row_begin + wave * per_wave + min(wave, extra);
+  const int wrow_end = wrow_begin + per_wave + (wave < extra ? 1 : 0);
 
   uint32_t chunk = 0;      // 8-entry chunk index this lane loads next (chunk 0 exists: pad_nnz > 0)
   const int blk = wrow_begin;
@@ -175,9 +192,8 @@ __global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs
         ++ld.i;
         seek_nonempty(ld, nb, rp_lo, rp_hi);
       }
-    } else {
-      chunk = 0;       // padding item: every lane re-reads the first 16 bytes (one hot cache line)
-    }
+    }                  // else a padding item: every lane re-reads its previous chunk (a line it has just
+                       // used; one fixed address would make every wavefront queue at the same L2 channel)
     wq[j] = deltas[chunk];
     vq[j] = values[chunk];
   };
@@ -295,6 +311,8 @@ int set_lds_limit(K kernel, int64_t bytes) {
 }
 
 constexpr int64_t kMaxLdsBytes = 160 * 1024 - 64;   // 160 KB per CU minus the static row counter
+// launches with at most this many wavefront steps per compute unit run as one resident round
+constexpr int64_t kResidentStepsPerCu = 768;
 
 }  // namespace
 
@@ -349,26 +367,17 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;
   const Tuning& t = tuning();
   const int cus = device_cu_count();
-  // rows that will share the grouped launch (decides how much work a wavefront gets)
   auto wants_wave_row = [&](const SpmvProblem& p) {
     if (p.rows == 0 || p.pad_nnz == 0) return false;
     if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
     return p.pad_nnz / p.rows >= 384 && lds_bytes_for(p.cols) <= kMaxLdsBytes;
   };
-  int64_t group_rows = 0, group_lds = 0;
-  for (int i = 0; i < n; ++i) {
-    if (!wants_wave_row(problems[i])) continue;
-    group_rows += problems[i].rows;
-    group_lds = std::max(group_lds, lds_bytes_for(problems[i].cols));
-  }
-  // Every workgroup holds its own copy of x in LDS.  When that copy is large
-  // (more than ~24 K columns) only one to three workgroups fit a CU, so each one
-  // brings 16 wavefronts instead of 8 to keep the CU's load queues full.
-  const int block = t.spmv_block ? (int)t.spmv_block : (group_lds > 48 * 1024 ? 1024 : 512);
-  const int nwaves = block / 64;
 
-  SpmvGroupArgs args{};
-  int64_t total_wgs = 0, max_lds = 0;
+  // matrices that do not go into the grouped wave-per-row launch
+  const SpmvProblem* wr[kMaxGroup];
+  PlanInput in[kMaxGroup];
+  int nwr = 0;
+  int64_t max_lds = 0, total_steps = 0;
   for (int i = 0; i < n; ++i) {
     const SpmvProblem& p = problems[i];
     if (p.rows == 0) continue;
@@ -379,27 +388,61 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
       if (e0 != hipSuccess) return hip_fail(e0);
       continue;
     }
-    const int64_t lds_bytes = lds_bytes_for(p.cols);
-    const bool lds_ok = lds_bytes <= kMaxLdsBytes;
-    const int64_t avg = p.pad_nnz / p.rows;
     if (!wants_wave_row(p)) {                           // short rows or x larger than LDS: own launch
       int st = launch_subwave(p, (int)t.spmv_lanes, stream);
       if (st != MACKO_OK) return st;
       continue;
     }
-    if (!lds_ok) return MACKO_E_UNSUPPORTED;
-    int64_t rpw = t.spmv_rows_per_wg;
-    if (rpw == 0) {
-      // A wavefront should own about 16 steps of work so that its load pipeline
-      // runs in steady state (short rows: several rows per wavefront), but never
-      // so much that the launch as a whole has fewer than ~16 wavefronts per CU.
-      const int64_t steps_per_row = std::max<int64_t>(1, (avg + 511) / 512);
-      const int64_t want = (16 + steps_per_row - 1) / steps_per_row;
-      const int64_t cap = std::max<int64_t>(1, group_rows / ((int64_t)cus * 16));
-      rpw = std::min(want, cap) * nwaves;
+    const int64_t lds_bytes = lds_bytes_for(p.cols);
+    if (lds_bytes > kMaxLdsBytes) return MACKO_E_UNSUPPORTED;
+    wr[nwr] = &p;
+    in[nwr].rows = p.rows;
+    in[nwr].steps_per_row = std::max<int64_t>(1, (p.pad_nnz / p.rows + 511) / 512);
+    in[nwr].lds_bytes = lds_bytes;
+    total_steps += in[nwr].rows * in[nwr].steps_per_row;
+    max_lds = std::max(max_lds, lds_bytes);
+    ++nwr;
+  }
+  if (nwr == 0) return MACKO_OK;
+
+  Plan plan;
+  bool planned = false;
+  // Little work: one resident round of workgroups, shaped to the row counts.
+  const bool small = total_steps <= (int64_t)cus * kResidentStepsPerCu;
+  if (t.spmv_rows_per_wg == 0 && (t.spmv_resident == 2 || (t.spmv_resident == 0 && small)))
+    planned = plan_resident(plan, nwr, in, cus, (int)t.spmv_block, (int)t.spmv_wgs_per_cu);
+  if (!planned) {
+    // Plenty of work: many workgroups, about 16 steps per wavefront (short rows:
+    // several rows per wavefront), but never so few workgroups that the launch
+    // has under ~16 wavefronts per compute unit.  Every workgroup holds its own
+    // copy of x in LDS; when that copy is large (more than ~24 K columns) only
+    // one to three fit a compute unit, so each brings 16 wavefronts instead of 8.
+    const int block = t.spmv_block ? (int)t.spmv_block : (max_lds > 48 * 1024 ? 1024 : 512);
+    const int nwaves = block / 64;
+    int64_t group_rows = 0;
+    for (int i = 0; i < nwr; ++i) group_rows += in[i].rows;
+    int64_t rpw[kMaxGroup];
+    for (int i = 0; i < nwr; ++i) {
+      rpw[i] = t.spmv_rows_per_wg;
+      if (rpw[i] == 0) {
+        const int64_t want = (16 + in[i].steps_per_row - 1) / in[i].steps_per_row;
+        const int64_t cap = std::max<int64_t>(1, group_rows / ((int64_t)cus * 16));
+        rpw[i] = std::min(want, cap) * nwaves;
+      }
     }
-    rpw = std::min<int64_t>(rpw, 64 * nwaves);          // a wavefront keeps at most 64 rows' results
-    SpmvMat& m = args.m[args.n++];
+    plan_by_rows_per_wg(plan, nwr, in, block, rpw);
+  }
+  if (plan.total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+
+  SpmvGroupArgs args{};
+  const int nwaves = plan.block / 64;
+  args.inv_nwaves = 65536 / nwaves + 1;
+  int64_t wg_begin = 0;
+  bool simple = true;
+  for (int i = 0; i < kMaxGroup; ++i) args.wg_begin[i] = INT32_MAX;
+  for (int i = 0; i < nwr; ++i) {
+    const SpmvProblem& p = *wr[i];
+    SpmvMat& m = args.m[i];
     m.values = reinterpret_cast<const uint4*>(p.values);
     m.deltas = reinterpret_cast<const uint32_t*>(p.deltas);
     m.row_ptr = p.row_ptr;
@@ -407,28 +450,23 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
     m.y = static_cast<uint16_t*>(p.y);
     m.rows = (int)p.rows;
     m.cols = (int)p.cols;
-    m.rows_per_wg = (int)rpw;
-    m.wg_begin = (int)total_wgs;
-    total_wgs += (p.rows + rpw - 1) / rpw;
-    max_lds = std::max(max_lds, lds_bytes);
-    if (total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+    m.q = plan.m[i].q;
+    m.r = plan.m[i].r;
+    args.wg_begin[i] = (int)wg_begin;
+    wg_begin += plan.m[i].nwg;
+    // the lean start-up path needs an aligned x whose length is a multiple of 8 and fits the staging registers
+    simple = simple && stage_x_is_simple(m.x, m.cols, plan.block);
   }
-  if (args.n > 0) {
-    // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
-    // CU, and the smaller loop body matters when a wavefront runs it only a few
-    // times (instruction fetch is cold at every launch).  The lean start-up path
-    // needs an aligned x whose length is a multiple of 8 and fits the staging registers.
-    bool simple = true;
-    for (int i = 0; i < args.n; ++i) simple = simple && stage_x_is_simple(args.m[i].x, args.m[i].cols, block);
-    auto kfn = t.spmv_ring == 4 ? (simple ? spmv_wave_row_kernel<4, true> : spmv_wave_row_kernel<4, false>)
-                                : (simple ? spmv_wave_row_kernel<2, true> : spmv_wave_row_kernel<2, false>);
-    int st = set_lds_limit(kfn, max_lds);
-    if (st != MACKO_OK) return st;
-    hipLaunchKernelGGL(kfn, dim3((unsigned)total_wgs), dim3(block), (size_t)max_lds, stream, args);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e);
-  }
-  return MACKO_OK;
+  // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
+  // compute unit, and the smaller loop body matters when a wavefront runs it only
+  // a few times (instruction fetch is cold at every launch).
+  auto kfn = t.spmv_ring == 4 ? (simple ? spmv_wave_row_kernel<4, true> : spmv_wave_row_kernel<4, false>)
+                              : (simple ? spmv_wave_row_kernel<2, true> : spmv_wave_row_kernel<2, false>);
+  int st = set_lds_limit(kfn, max_lds);
+  if (st != MACKO_OK) return st;
+  hipLaunchKernelGGL(kfn, dim3((unsigned)plan.total_wgs), dim3(plan.block), (size_t)max_lds, stream, args);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
 }
 
 }  // namespace macko
