@@ -10,12 +10,14 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmacko.so")
 SOURCES = ["macko_host.cpp", "macko_spmv.hip", "macko_gemv.hip", "macko_encode_gpu.hip", "macko_spmm.hip"]
-HEADERS = ["macko_internal.h", "macko_device.h"]
+HEADERS = ["macko_internal.h", "macko_device.h", "macko_plan.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     # keep the compiler from forming packed fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # leading scalar kernel arguments arrive in registers instead of through a load
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
     "-Wall", "-Wno-unused-function",
 ]
 

@@ -32,34 +32,29 @@ struct GemvMat {
   int rows, cols, q, r;
   int pad[4];
 };
-// Workgroups [wg_begin[i], wg_begin[i+1]) work on matrix i; unused slots hold INT_MAX.
 struct GemvGroupArgs {
-  int wg_begin[kMaxGroup];
-  int inv_nwaves;          // floor(2^20 / wavefronts per workgroup) + 1
-  int pad[7];
   GemvMat m[kMaxGroup];
 };
+// Workgroups [wg_begin[i], wg_begin[i+1]) work on matrix i (wg_begin[0] = 0); unused
+// slots hold INT_MAX.  Passed, with inv_nwaves, as separate scalar kernel arguments in
+// front of the descriptors so that they can reach a starting wavefront in registers.
+struct GemvGroupHeader {
+  int wg_begin[kMaxGroup];
+  int inv_nwaves;          // floor(2^20 / wavefronts per workgroup) + 1
+};
 
+// The work of one workgroup: workgroup number `wg` of the given matrix, whose
+// rows are dealt out q (+1 for the first r workgroups) at a time.
 template <int RING>
-__global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs g) {
+__device__ __forceinline__ void gemv_wave_row_body(const uint4* __restrict__ W, const uint16_t* __restrict__ x,
+                                                   uint16_t* __restrict__ y, const int64_t ld8, const int cols,
+                                                   const int q, const int r, const int wg,
+                                                   const int inv_nwaves) {
   extern __shared__ __align__(16) unsigned char lds[];
-  int mi = 0, wg0 = 0;
-#pragma unroll
-  for (int i = 1; i < kMaxGroup; ++i) {
-    const bool in = (int)blockIdx.x >= g.wg_begin[i];
-    mi = in ? i : mi;
-    wg0 = in ? g.wg_begin[i] : wg0;
-  }
-  const uint4* __restrict__ W = g.m[mi].W;
-  const uint16_t* __restrict__ x = g.m[mi].x;
-  uint16_t* __restrict__ y = g.m[mi].y;
-  const int64_t ld8 = g.m[mi].ld8;
-  const int cols = g.m[mi].cols;
   const int lds_bytes = (int)lds_bytes_for(cols);
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
-  const int wg = (int)blockIdx.x - wg0;
-  const int row_begin = wg * g.m[mi].q + min(wg, g.m[mi].r);
-  const int wg_rows = g.m[mi].q + (wg < g.m[mi].r ? 1 : 0);
+  const int row_begin = wg * q + min(wg, r);
+  const int wg_rows = q + (wg < r ? 1 : 0);
   const int nwaves = blockDim.x >> 6;
   const uint4* xs = reinterpret_cast<const uint4*>(lds + kFrontPad);
 
@@ -69,7 +64,7 @@ __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs
   const int nsteps = (c8 + 63) >> 6;
   const bool ragged = (c8 & 63) != 0;                  // last step only partly inside the row
   // wg_rows / nwaves, exact for wg_rows < 2^16 (the host keeps it below)
-  const int per_wave = (int)(((uint64_t)(uint32_t)wg_rows * (uint32_t)g.inv_nwaves) >> 20);
+  const int per_wave = (int)(((uint64_t)(uint32_t)wg_rows * (uint32_t)inv_nwaves) >> 20);
   const int extra = wg_rows - per_wave * nwaves;
   const int wrow_begin = row_begin + wave * per_wave + min(wave, extra);
   const int wrow_end = wrow_begin + per_wave + (wave < extra ? 1 : 0);
@@ -81,7 +76,7 @@ __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs
   const uint4* src = W;                                // row the next load reads from
   const uint4* src_next = W;
   int chunk = min(lane, c8 - 1);
-  uint4 q[RING];
+  uint4 ring[RING];
   auto issue = [&](int j) {
     src = src_next;
     if (ld_i < nb) {
@@ -91,7 +86,7 @@ __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs
         if (++ld_i < nb) src_next = src + ld8;
       }
     }
-    q[j] = src[chunk];                                 // padding items re-read the previous address
+    ring[j] = src[chunk];                                 // padding items re-read the previous address
   };
   auto open_block = [&]() {
     ld_i = ld_step = cp_i = cp_step = 0;
@@ -113,7 +108,7 @@ __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs
     while (cp_i < nb) {
 #pragma unroll
       for (int j = 0; j < RING; ++j) {
-        uint4 w = q[j];
+        uint4 w = ring[j];
         const bool live = cp_i < nb;
         if (!live) cp_step = 0;
         const int idx = cp_step * 64 + lane;
@@ -154,6 +149,32 @@ __global__ void __launch_bounds__(1024) gemv_wave_row_kernel(const GemvGroupArgs
     nb = min(64, wrow_end - blk);
     open_block();
   }
+}
+
+// Grouped launch: the workgroup first finds its matrix.
+template <int RING>
+__global__ void __launch_bounds__(1024)
+gemv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4, const int wb5, const int wb6,
+                     const int wb7, const int inv_nwaves, const GemvGroupArgs g) {
+  static_assert(kMaxGroup == 8, "one scalar argument per group slot");
+  int mi = 0, wg0 = 0;
+  const int wbs[kMaxGroup] = {0, wb1, wb2, wb3, wb4, wb5, wb6, wb7};
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) {
+    const bool in = (int)blockIdx.x >= wbs[i];
+    mi = in ? i : mi;
+    wg0 = in ? wbs[i] : wg0;
+  }
+  gemv_wave_row_body<RING>(g.m[mi].W, g.m[mi].x, g.m[mi].y, g.m[mi].ld8, g.m[mi].cols, g.m[mi].q, g.m[mi].r,
+                           (int)blockIdx.x - wg0, inv_nwaves);
+}
+
+// One matrix: all scalar arguments, no argument load before the first weights are requested.
+template <int RING>
+__global__ void __launch_bounds__(1024)
+gemv_wave_row_kernel(const uint4* __restrict__ W, const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
+                     const int64_t ld8, const int cols, const int q, const int r, const int inv_nwaves) {
+  gemv_wave_row_body<RING>(W, x, y, ld8, cols, q, r, (int)blockIdx.x, inv_nwaves);
 }
 
 // Any shape / alignment: one wavefront per row, 2-byte loads, x from global.
@@ -236,9 +257,10 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
   if (plan.total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
 
   GemvGroupArgs args{};
-  args.inv_nwaves = (1 << 20) / (plan.block / 64) + 1;
+  GemvGroupHeader head{};
+  head.inv_nwaves = (1 << 20) / (plan.block / 64) + 1;
   int64_t wg_begin = 0;
-  for (int i = 0; i < kMaxGroup; ++i) args.wg_begin[i] = INT32_MAX;
+  for (int i = 0; i < kMaxGroup; ++i) head.wg_begin[i] = INT32_MAX;
   for (int i = 0; i < nwr; ++i) {
     const GemvProblem& p = *wr[i];
     GemvMat& m = args.m[i];
@@ -250,17 +272,34 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
     m.cols = (int)p.cols;
     m.q = plan.m[i].q;
     m.r = plan.m[i].r;
-    args.wg_begin[i] = (int)wg_begin;
+    head.wg_begin[i] = (int)wg_begin;
     wg_begin += plan.m[i].nwg;
   }
-  auto kfn = t.gemv_ring == 2 ? gemv_wave_row_kernel<2>
-             : t.gemv_ring == 8 ? gemv_wave_row_kernel<8> : gemv_wave_row_kernel<4>;
-  if (max_lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
-    if (e != hipSuccess) return hip_fail(e);
+  const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
+  auto lds_limit = [&](const void* fn) -> int {
+    if (max_lds <= 64 * 1024) return MACKO_OK;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
+    return e == hipSuccess ? MACKO_OK : hip_fail(e);
+  };
+  if (nwr == 1) {
+    using K1 = void (*)(const uint4*, const uint16_t*, uint16_t*, int64_t, int, int, int, int);
+    K1 kfn = t.gemv_ring == 2 ? (K1)gemv_wave_row_kernel<2>
+             : t.gemv_ring == 8 ? (K1)gemv_wave_row_kernel<8> : (K1)gemv_wave_row_kernel<4>;
+    int st = lds_limit(reinterpret_cast<const void*>(kfn));
+    if (st != MACKO_OK) return st;
+    const GemvMat& m = args.m[0];
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.W, m.x, m.y, m.ld8, m.cols, m.q, m.r,
+                       head.inv_nwaves);
+  } else {
+    using KG = void (*)(int, int, int, int, int, int, int, int, GemvGroupArgs);
+    KG kfn = t.gemv_ring == 2 ? (KG)gemv_wave_row_kernel<2>
+             : t.gemv_ring == 8 ? (KG)gemv_wave_row_kernel<8> : (KG)gemv_wave_row_kernel<4>;
+    int st = lds_limit(reinterpret_cast<const void*>(kfn));
+    if (st != MACKO_OK) return st;
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
+                       head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
+                       head.inv_nwaves, args);
   }
-  hipLaunchKernelGGL(kfn, dim3((unsigned)plan.total_wgs), dim3(plan.block), (size_t)max_lds, stream, args);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
 }

@@ -135,43 +135,39 @@ struct SpmvMat {
   int rows, cols, q, r;
   int pad[2];
 };
-// Workgroups [wg_begin[i], wg_begin[i+1]) work on matrix i; unused slots hold
-// INT_MAX.  The header comes first so that one scalar load fetches all of it.
 struct SpmvGroupArgs {
-  int wg_begin[kMaxGroup];
-  int inv_nwaves;          // floor(65536 / wavefronts per workgroup) + 1
-  int pad[7];
   SpmvMat m[kMaxGroup];
 };
+// Workgroups [wg_begin[i], wg_begin[i+1]) work on matrix i (wg_begin[0] = 0); unused
+// slots hold INT_MAX.  These and inv_nwaves are separate scalar kernel arguments in
+// front of the descriptors: scalar arguments at the start of the argument list can be
+// handed to a wavefront in registers when it starts, which saves one dependent load
+// on the way to the first row pointer.
+struct SpmvGroupHeader {
+  int wg_begin[kMaxGroup];
+  int inv_nwaves;          // floor(65536 / wavefronts per workgroup) + 1
+};
 
+// The work of one workgroup: workgroup number `wg` of the matrix given by the
+// pointers, whose rows are dealt out q (+1 for the first r workgroups) at a time.
 template <int RING, bool SIMPLE>
-__global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs g) {
+__device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ values,
+                                                   const uint32_t* __restrict__ deltas,
+                                                   const uint32_t* __restrict__ row_ptr,
+                                                   const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
+                                                   const int rows, const int cols, const int q, const int r,
+                                                   const int wg, const int inv_nwaves) {
   extern __shared__ __align__(16) unsigned char lds[];
-  // which matrix of the group this workgroup belongs to (uniform)
-  int mi = 0, wg0 = 0;
-#pragma unroll
-  for (int i = 1; i < kMaxGroup; ++i) {
-    const bool in = (int)blockIdx.x >= g.wg_begin[i];
-    mi = in ? i : mi;
-    wg0 = in ? g.wg_begin[i] : wg0;
-  }
-  const uint4* __restrict__ values = g.m[mi].values;
-  const uint32_t* __restrict__ deltas = g.m[mi].deltas;
-  const uint32_t* __restrict__ row_ptr = g.m[mi].row_ptr;
-  const uint16_t* __restrict__ x = g.m[mi].x;
-  uint16_t* __restrict__ y = g.m[mi].y;
-  const int rows = g.m[mi].rows, cols = g.m[mi].cols;
   const int lds_bytes = (int)lds_bytes_for(cols);
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
-  const int wg = (int)blockIdx.x - wg0;
-  const int row_begin = wg * g.m[mi].q + min(wg, g.m[mi].r);
-  const int wg_rows = g.m[mi].q + (wg < g.m[mi].r ? 1 : 0);
+  const int row_begin = wg * q + min(wg, r);
+  const int wg_rows = q + (wg < r ? 1 : 0);
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const unsigned char* xbase = lds + kFrontPad;       // LDS address of x[0]
   const uint32_t lane8 = 8u * lane;
-  const int per_wave = (wg_rows * g.inv_nwaves) >> 16;   // wg_rows / nwaves (exact for wg_rows <= 1024)
+  const int per_wave = (wg_rows * inv_nwaves) >> 16;   // wg_rows / nwaves (exact for wg_rows <= 1024)
   const int extra = wg_rows - per_wave * nwaves;         // wg_rows % nwaves
   const int wrow_begin = row_begin + wave * per_wave + min(wave, extra);
   const int wrow_end = wrow_begin + per_wave + (wave < extra ? 1 : 0);
@@ -292,6 +288,36 @@ __global__ void __launch_bounds__(1024) spmv_wave_row_kernel(const SpmvGroupArgs
     }
     if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
   }
+}
+
+// Grouped launch: the workgroup first finds its matrix.
+template <int RING, bool SIMPLE>
+__global__ void __launch_bounds__(1024)
+spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4, const int wb5, const int wb6,
+                     const int wb7, const int inv_nwaves, const SpmvGroupArgs g) {
+  static_assert(kMaxGroup == 8, "one scalar argument per group slot");
+  int mi = 0, wg0 = 0;
+  const int wbs[kMaxGroup] = {0, wb1, wb2, wb3, wb4, wb5, wb6, wb7};
+#pragma unroll
+  for (int i = 1; i < kMaxGroup; ++i) {
+    const bool in = (int)blockIdx.x >= wbs[i];
+    mi = in ? i : mi;
+    wg0 = in ? wbs[i] : wg0;
+  }
+  spmv_wave_row_body<RING, SIMPLE>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
+                                   g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
+                                   inv_nwaves);
+}
+
+// One matrix: everything the workgroup needs is a scalar argument (15 registers),
+// so a starting wavefront goes straight to its row pointers without any argument load.
+template <int RING, bool SIMPLE>
+__global__ void __launch_bounds__(1024)
+spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
+                     const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
+                     uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
+                     const int inv_nwaves) {
+  spmv_wave_row_body<RING, SIMPLE>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x, inv_nwaves);
 }
 
 // y = 0 for a matrix without stored entries
@@ -435,11 +461,12 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   if (plan.total_wgs >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
 
   SpmvGroupArgs args{};
+  SpmvGroupHeader head{};
   const int nwaves = plan.block / 64;
-  args.inv_nwaves = 65536 / nwaves + 1;
+  head.inv_nwaves = 65536 / nwaves + 1;
   int64_t wg_begin = 0;
   bool simple = true;
-  for (int i = 0; i < kMaxGroup; ++i) args.wg_begin[i] = INT32_MAX;
+  for (int i = 0; i < kMaxGroup; ++i) head.wg_begin[i] = INT32_MAX;
   for (int i = 0; i < nwr; ++i) {
     const SpmvProblem& p = *wr[i];
     SpmvMat& m = args.m[i];
@@ -452,7 +479,7 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
     m.cols = (int)p.cols;
     m.q = plan.m[i].q;
     m.r = plan.m[i].r;
-    args.wg_begin[i] = (int)wg_begin;
+    head.wg_begin[i] = (int)wg_begin;
     wg_begin += plan.m[i].nwg;
     // the lean start-up path needs an aligned x whose length is a multiple of 8 and fits the staging registers
     simple = simple && stage_x_is_simple(m.x, m.cols, plan.block);
@@ -460,11 +487,28 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
   // compute unit, and the smaller loop body matters when a wavefront runs it only
   // a few times (instruction fetch is cold at every launch).
-  auto kfn = t.spmv_ring == 4 ? (simple ? spmv_wave_row_kernel<4, true> : spmv_wave_row_kernel<4, false>)
-                              : (simple ? spmv_wave_row_kernel<2, true> : spmv_wave_row_kernel<2, false>);
-  int st = set_lds_limit(kfn, max_lds);
-  if (st != MACKO_OK) return st;
-  hipLaunchKernelGGL(kfn, dim3((unsigned)plan.total_wgs), dim3(plan.block), (size_t)max_lds, stream, args);
+  const bool ring4 = t.spmv_ring == 4;
+  const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
+  if (nwr == 1) {
+    using K1 = void (*)(const uint4*, const uint32_t*, const uint32_t*, const uint16_t*, uint16_t*, int, int, int,
+                        int, int);
+    K1 kfn = ring4 ? (simple ? (K1)spmv_wave_row_kernel<4, true> : (K1)spmv_wave_row_kernel<4, false>)
+                   : (simple ? (K1)spmv_wave_row_kernel<2, true> : (K1)spmv_wave_row_kernel<2, false>);
+    int st = set_lds_limit(kfn, max_lds);
+    if (st != MACKO_OK) return st;
+    const SpmvMat& m = args.m[0];
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.values, m.deltas, m.row_ptr, m.x, m.y,
+                       m.rows, m.cols, m.q, m.r, head.inv_nwaves);
+  } else {
+    using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
+    KG kfn = ring4 ? (simple ? (KG)spmv_wave_row_kernel<4, true> : (KG)spmv_wave_row_kernel<4, false>)
+                   : (simple ? (KG)spmv_wave_row_kernel<2, true> : (KG)spmv_wave_row_kernel<2, false>);
+    int st = set_lds_limit(kfn, max_lds);
+    if (st != MACKO_OK) return st;
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
+                       head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
+                       head.inv_nwaves, args);
+  }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
 }
