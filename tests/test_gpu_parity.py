@@ -24,8 +24,9 @@ def _need_gpu_and_library():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     M.load_library()          # raises if libmacko.so is missing: no fallback
     yield
-    for knob in ("spmv_kernel", "spmv_lanes", "spmv_block", "spmv_rows_per_wg", "gemv_block",
-                 "gemv_rows_per_wg"):
+    for knob in ("spmv_kernel", "spmv_lanes", "spmv_block", "spmv_rows_per_wg", "spmv_ring", "spmv_resident",
+                 "spmv_wgs_per_cu", "gemv_block", "gemv_rows_per_wg", "gemv_ring", "gemv_resident",
+                 "gemv_wgs_per_cu"):
         M.set_tuning(knob, 0)
 
 
@@ -118,6 +119,84 @@ def test_spmv_empty_rows_mixed_with_full_rows_and_row_boundaries_inside_chunks()
         y = spmv_case(W, x, **VARIANTS[variant])
         check_y(y, W, x, variant)
         assert (y[10:30] == 0).all() and (y[395:] == 0).all()
+
+
+RESIDENT_VARIANTS = {
+    "auto": {},
+    "never": {"spmv_resident": 1},
+    "k1": {"spmv_resident": 2, "spmv_wgs_per_cu": 1},
+    "k2_ring4": {"spmv_resident": 2, "spmv_wgs_per_cu": 2, "spmv_ring": 4},
+    "k3_b320": {"spmv_resident": 2, "spmv_wgs_per_cu": 3, "spmv_block": 320},
+    "k4": {"spmv_resident": 2, "spmv_wgs_per_cu": 4},
+    "k1_b1024": {"spmv_resident": 2, "spmv_wgs_per_cu": 1, "spmv_block": 1024},
+    "k2_b704": {"spmv_resident": 2, "spmv_wgs_per_cu": 2, "spmv_block": 704},
+}
+
+
+@pytest.mark.parametrize("variant", list(RESIDENT_VARIANTS))
+def test_spmv_resident_round_launch_shapes(variant):
+    """One resident round of workgroups (a multiple of the compute-unit count) with row counts
+    that do not divide evenly: every row must still be computed exactly once, single and grouped."""
+    W = wl.bernoulli(2311, 1536, 0.5, 0.02, 41, 1)
+    W[100:140] = 0                                        # a run of empty rows inside one workgroup's share
+    x = wl.x_vector(1536, 41, 1)
+    y = spmv_case(W, x, spmv_kernel=2, **RESIDENT_VARIANTS[variant])
+    check_y(y, W, x, variant)
+    # grouped: three matrices of different heights and widths share the round
+    specs = [(1500, 2048, 0.5), (1031, 1024, 0.6), (777, 4096, 0.4)]
+    Ws = [wl.bernoulli(r, c, d, 0.02, 42, i) for i, (r, c, d) in enumerate(specs)]
+    xs = [wl.x_vector(c, 42, i) for i, (_, c, _) in enumerate(specs)]
+    for k, v in dict(spmv_kernel=2, **RESIDENT_VARIANTS[variant]).items():
+        M.set_tuning(k, v)
+    try:
+        ms = [M.encode(Wi).to_device() for Wi in Ws]
+        ys = M.spmv_group(ms, [to_dev(xi) for xi in xs])
+        torch.cuda.synchronize()
+    finally:
+        for k in dict(spmv_kernel=2, **RESIDENT_VARIANTS[variant]):
+            M.set_tuning(k, 0)
+    for i, (Wi, xi, yi) in enumerate(zip(Ws, xs, ys)):
+        check_y(yi, Wi, xi, f"{variant} group member {i}")
+
+
+def test_spmv_under_graph_capture_and_on_two_streams():
+    """The products only enqueue kernels, so they can be captured into a HIP graph and replayed,
+    and one handle can be used from two streams at once."""
+    W = wl.half_row_matrix(1024, 4096, 77)
+    x1, x2 = wl.x_vector(4096, 43, 1), wl.x_vector(4096, 43, 2)
+    m = M.encode(W).to_device()
+    xd = to_dev(x1)
+    y = torch.empty(1024, dtype=torch.float16, device="cuda")
+    eager1 = m.spmv(to_dev(x1)).clone()
+    eager2 = m.spmv(to_dev(x2)).clone()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        m.spmv(xd, y, stream=side)                       # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            m.spmv(xd, y, stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep, (xv, want) in enumerate([(x1, eager1), (x2, eager2), (x1, eager1), (x2, eager2)]):
+        xd.copy_(to_dev(xv))
+        y.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want), f"replay {rep}"
+    # two streams, same handle, different vectors
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    xa, xb = to_dev(x1), to_dev(x2)
+    ya = torch.empty(1024, dtype=torch.float16, device="cuda")
+    yb = torch.empty(1024, dtype=torch.float16, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(20):
+        m.spmv(xa, ya, stream=s1)
+        m.spmv(xb, yb, stream=s2)
+    torch.cuda.synchronize()
+    assert torch.equal(ya, eager1) and torch.equal(yb, eager2)
 
 
 def test_spmv_all_zero_matrix_and_zero_sized():
