@@ -150,6 +150,8 @@ def main():
     ap.add_argument("--shapes", action="store_true",
                     help="also time every shape of the paper's Appendix D at 50 %% sparsity")
     ap.add_argument("--spmm", action="store_true", help="also time the small-batch product macko_spmm")
+    ap.add_argument("--widths", action="store_true",
+                    help="also time 2-, 4- and 8-bit codes on the 36864x12288 matrix (Appendix C of the paper)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe for rocprofv3 --pmc: a 1 GiB device copy of known size, then a "
@@ -386,6 +388,34 @@ def main():
             del so, case
             torch.cuda.empty_cache()
         extra["sweep_36864x12288"] = sweep
+
+    # ---- optional: other code widths (Appendix C) on the sweep matrix ---------------
+    if args.widths:
+        table = {}
+        for s in (25, 40, 50, 70, 90, 97):
+            W = wl.bernoulli(36864, 12288, 1.0 - s / 100.0, 0.02, wl.BASE_SEED, 300 + s)
+            Wd = torch.from_numpy(W.view(np.float16)).cuda()
+            x = torch.from_numpy(wl.x_vector(12288).view(np.float16)).cuda()
+            y = torch.empty(36864, dtype=torch.float16, device="cuda")
+            row = {}
+            for b in (2, 4, 8):
+                ms = [M.encode_device(Wd, b_delta=b) for _ in range(3)]      # three copies, rotated
+                rep = ms[0].get_report()
+
+                def f(i):
+                    st = ms[i % 3].spmv_raw(x.data_ptr(), y.data_ptr(), stream_ptr)
+                    if st != 0:
+                        raise RuntimeError(f"macko_spmv failed with status {st}")
+                t = time_region(torch, f, 5, 30) / 30
+                row[f"b_delta_{b}"] = {"macko_us": round(t * 1e6, 1), "GBps": round(spmv_bytes(rep) / t / 1e9),
+                                       "effd": round(rep.effd, 4),
+                                       "padding_per_nnz": round(rep.padding_entries / max(rep.nnz, 1), 4)}
+                del ms
+            table[f"sparsity_{s}"] = row
+            log(f"  widths {s}%: {row}")
+            del Wd
+            torch.cuda.empty_cache()
+        extra["code_widths_36864x12288"] = table
 
     # ---- optional: small-batch products (batch 1..8) on the layer's shapes --------
     if args.spmm:

@@ -4,8 +4,9 @@
  * C ABI.  Implements the storage format of Section 4.1 of "MACKO: Sparse
  * Matrix-Vector Multiplication for Low Sparsity" (arXiv 2511.13061) for
  * b_val = 16 (fp16 values) and b_delta = 4 (4-bit delta-coded column
- * coordinates), and the product Y = M V of its Appendix A / Section 4.4, plus
- * the dense fp16 GEMV of Section 4.3 that the paper measures speedups against.
+ * coordinates; 1, 2 and 8 bits through the _ex entry points, Appendix C), and
+ * the product Y = M V of its Appendix A / Section 4.4, plus the dense fp16 GEMV
+ * of Section 4.3 that the paper measures speedups against.
  *
  * Conventions
  *   - Every function returns MACKO_OK (0) or a negative macko_status code; no
@@ -28,6 +29,11 @@
  *   bridged by zero-valued entries with delta 16 placed greedily.  An element
  *   is a zero iff its bits are +0 or -0.  alloc_nnz = pad_nnz rounded up to 32
  *   (both arrays are multiples of 16 bytes, Section 4.5).
+ *   With b_delta bits per code (1, 2, 4 or 8): entry k is the code (delta-1) in
+ *   bits [k*b_delta, (k+1)*b_delta) of the deltas array, low bits first (the
+ *   "bit shifting" packing of Section 4.1); the largest delta is 2^b_delta; the
+ *   array is alloc_nnz*b_delta/8 bytes and alloc_nnz = pad_nnz rounded up to
+ *   128/b_delta entries (16 bytes of codes).
  */
 #ifndef MACKO_H_
 #define MACKO_H_
@@ -70,7 +76,7 @@ typedef struct macko_report {
   double effd_best;         /* eq. 8  at this d                                        */
   double effd_expected;     /* eq. 10 at this d                                        */
   double effd_worst;        /* eq. 9  at this d                                        */
-  int32_t b_val, b_delta;   /* 16, 4                                                   */
+  int32_t b_val, b_delta;   /* 16; 4 unless an _ex call chose 1, 2 or 8                */
 } macko_report_t;
 
 /* ---- encoding (Section 4.1) ---------------------------------------------- */
@@ -96,6 +102,21 @@ MACKO_API int macko_encode_device(const void* dense_dev, int64_t rows, int64_t c
  * row_ptr[rows].  The contents are trusted, not validated. */
 MACKO_API int macko_wrap_device(int64_t rows, int64_t cols, int64_t pad_nnz, const void* values_dev,
                                 const void* deltas_dev, const void* rowptr_dev, macko_handle_t* out);
+
+/* The same three calls for another code width b_delta in {1, 2, 4, 8} (Section
+ * 4.1 allows exactly these; Appendix C: 2 bits store less below ~45 % sparsity,
+ * 8 bits above ~95 %).  Everything else -- handles, binding, decode, the report,
+ * macko_spmv and macko_spmv_group -- works for every width; macko_spmm takes
+ * 4-bit handles only (MACKO_E_UNSUPPORTED otherwise).  Any other b_delta is
+ * MACKO_E_INVALID_ARG. */
+MACKO_API int macko_encode_ex(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
+                              int b_delta, macko_handle_t* out, macko_report_t* report);
+MACKO_API int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld,
+                                     int b_delta, void* stream, macko_handle_t* out,
+                                     macko_report_t* report);
+MACKO_API int macko_wrap_device_ex(int64_t rows, int64_t cols, int64_t pad_nnz, int b_delta,
+                                   const void* values_dev, const void* deltas_dev,
+                                   const void* rowptr_dev, macko_handle_t* out);
 
 /* Copy of the report computed at encode time (for wrapped handles only the
  * size fields are known; nnz-derived fields are -1 / NaN). */

@@ -13,7 +13,8 @@ _LIB_PATH = os.path.join(_HERE, "libmacko.so")
 _lib = None
 
 EXPORTED_SYMBOLS = [
-    "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_get_report",
+    "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
+    "macko_wrap_device_ex", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
     "macko_decode", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
@@ -87,6 +88,9 @@ def load_library():
     lib.macko_encode.argtypes = [vp, i64, i64, i64, hp, rp]
     lib.macko_encode_device.argtypes = [vp, i64, i64, i64, vp, hp, rp]
     lib.macko_wrap_device.argtypes = [i64, i64, i64, vp, vp, vp, hp]
+    lib.macko_encode_ex.argtypes = [vp, i64, i64, i64, ci, hp, rp]
+    lib.macko_encode_device_ex.argtypes = [vp, i64, i64, i64, ci, vp, hp, rp]
+    lib.macko_wrap_device_ex.argtypes = [i64, i64, i64, ci, vp, vp, vp, hp]
     lib.macko_get_report.argtypes = [vp, rp]
     lib.macko_device_bytes.argtypes = [vp, i64p, i64p, i64p]
     lib.macko_bind_device.argtypes = [vp, vp, vp, vp, vp]
@@ -274,34 +278,49 @@ class MackoMatrix:
         return load_library().macko_spmv(self._h, x_ptr, y_ptr, stream_ptr)
 
 
-def encode(dense) -> MackoMatrix:
-    """macko_encode on a host fp16 matrix (numpy float16 or uint16 bits)."""
+def encode(dense, b_delta: int = 4) -> MackoMatrix:
+    """macko_encode / macko_encode_ex on a host fp16 matrix (numpy float16 or uint16 bits)."""
     a = _host_u16_matrix(dense)
     h = ctypes.c_void_p()
     rep = _CReport()
     ld = a.strides[0] // 2 if a.size else a.shape[1]      # numpy reports zero strides for empty arrays
-    _check(load_library().macko_encode(a.ctypes.data, a.shape[0], a.shape[1], ld,
-                                       ctypes.byref(h), ctypes.byref(rep)), "macko_encode")
+    if b_delta == 4:
+        _check(load_library().macko_encode(a.ctypes.data, a.shape[0], a.shape[1], ld,
+                                           ctypes.byref(h), ctypes.byref(rep)), "macko_encode")
+    else:
+        _check(load_library().macko_encode_ex(a.ctypes.data, a.shape[0], a.shape[1], ld, int(b_delta),
+                                              ctypes.byref(h), ctypes.byref(rep)), "macko_encode_ex")
     return MackoMatrix(h.value, Report._from_c(rep))
 
 
-def encode_device(dense_dev, stream=None) -> MackoMatrix:
-    """macko_encode_device on a torch float16 CUDA matrix (row-major)."""
+def encode_device(dense_dev, stream=None, b_delta: int = 4) -> MackoMatrix:
+    """macko_encode_device / macko_encode_device_ex on a torch float16 CUDA matrix (row-major)."""
     if dense_dev.dim() != 2 or dense_dev.stride(1) != 1:
         raise ValueError("dense_dev must be a row-major 2-D tensor")
     h = ctypes.c_void_p()
     rep = _CReport()
-    _check(load_library().macko_encode_device(_dev_ptr(dense_dev), dense_dev.shape[0], dense_dev.shape[1],
-                                              dense_dev.stride(0), _stream_ptr(stream), ctypes.byref(h),
-                                              ctypes.byref(rep)), "macko_encode_device")
+    if b_delta == 4:
+        _check(load_library().macko_encode_device(_dev_ptr(dense_dev), dense_dev.shape[0], dense_dev.shape[1],
+                                                  dense_dev.stride(0), _stream_ptr(stream), ctypes.byref(h),
+                                                  ctypes.byref(rep)), "macko_encode_device")
+    else:
+        _check(load_library().macko_encode_device_ex(_dev_ptr(dense_dev), dense_dev.shape[0], dense_dev.shape[1],
+                                                     dense_dev.stride(0), int(b_delta), _stream_ptr(stream),
+                                                     ctypes.byref(h), ctypes.byref(rep)), "macko_encode_device_ex")
     return MackoMatrix(h.value, Report._from_c(rep))
 
 
-def wrap_device(rows: int, cols: int, pad_nnz: int, values_dev, deltas_dev, rowptr_dev) -> MackoMatrix:
-    """macko_wrap_device: adopt device arrays that already hold an encoding."""
+def wrap_device(rows: int, cols: int, pad_nnz: int, values_dev, deltas_dev, rowptr_dev,
+                b_delta: int = 4) -> MackoMatrix:
+    """macko_wrap_device / macko_wrap_device_ex: adopt device arrays that already hold an encoding."""
     h = ctypes.c_void_p()
-    _check(load_library().macko_wrap_device(rows, cols, pad_nnz, _dev_ptr(values_dev), _dev_ptr(deltas_dev),
-                                            _dev_ptr(rowptr_dev), ctypes.byref(h)), "macko_wrap_device")
+    if b_delta == 4:
+        _check(load_library().macko_wrap_device(rows, cols, pad_nnz, _dev_ptr(values_dev), _dev_ptr(deltas_dev),
+                                                _dev_ptr(rowptr_dev), ctypes.byref(h)), "macko_wrap_device")
+    else:
+        _check(load_library().macko_wrap_device_ex(rows, cols, pad_nnz, int(b_delta), _dev_ptr(values_dev),
+                                                   _dev_ptr(deltas_dev), _dev_ptr(rowptr_dev), ctypes.byref(h)),
+               "macko_wrap_device_ex")
     m = MackoMatrix(h.value, None)
     m._keep = [values_dev, deltas_dev, rowptr_dev]
     return m

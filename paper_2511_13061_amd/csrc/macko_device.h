@@ -11,20 +11,24 @@ namespace macko {
 constexpr int kWave = 64;
 
 // The activation vector x sits in LDS between two zero-filled guard regions:
-//   [0, kFrontPad) zeros | x[0 .. C) | zeros up to the end of the allocation.
+//   [0, front) zeros | x[0 .. C) | zeros up to the end of the allocation.
 // Entries that a lane loads but that belong to a neighbouring row decode to
 // positions just before column 0 or after the row's last column; the guards
 // make those reads return +0 so that they contribute nothing.
 // Front guard: a row's first chunk holds at most 7 entries of the previous row,
-// each at most 16 columns wide (224 bytes before x[0]).  Back guard: in a row's
-// last step the lanes past the row end advance by one column per entry, plus at
-// most 7 real deltas in the lane that straddles the end (at most 616 columns);
-// the dense kernel reads at most 62 16-byte chunks past the end.
-constexpr int kFrontPad = 256;   // bytes
+// each at most 2^b_delta columns wide (224 bytes before x[0] for 4-bit codes,
+// 3584 for 8-bit ones).  Back guard: in a row's last step the lanes past the row
+// end advance by one column per entry, plus at most 7 real deltas in the lane
+// that straddles the end (at most 504 + 7 * 2^b_delta columns); the dense kernel
+// reads at most 62 16-byte chunks past the end.
+constexpr int kFrontPad = 256;   // bytes, codes of up to 4 bits (and the dense kernel)
 constexpr int kBackPad = 1280;   // bytes
 
-__host__ __device__ inline int64_t lds_bytes_for(int64_t cols) {
-  return kFrontPad + 16 * ((cols + 7) / 8) + kBackPad;
+__host__ __device__ constexpr int front_pad_for(int b_delta) { return b_delta <= 4 ? kFrontPad : 3584; }
+__host__ __device__ constexpr int back_pad_for(int b_delta) { return b_delta <= 4 ? kBackPad : 4608; }
+
+__host__ __device__ inline int64_t lds_bytes_for(int64_t cols, int b_delta = 4) {
+  return front_pad_for(b_delta) + 16 * ((cols + 7) / 8) + back_pad_for(b_delta);
 }
 
 // ---- DPP cross-lane primitives (wave64, GCN DPP controls) --------------------
@@ -153,18 +157,19 @@ __device__ __forceinline__ void stage_x_begin(XStage& st, const uint16_t* __rest
 // also copies what did not fit, the ragged tail, or all of an unaligned x.
 template <bool SIMPLE>
 __device__ __forceinline__ void stage_x_finish(unsigned char* lds, const XStage& st,
-                                               const uint16_t* __restrict__ x, int cols, int lds_bytes) {
+                                               const uint16_t* __restrict__ x, int cols,
+                                               int front_pad = kFrontPad, int back_pad = kBackPad) {
   const int tid = threadIdx.x;
   const int nt = blockDim.x;
   const uint4 zero = make_uint4(0, 0, 0, 0);
   uint4* lds16 = reinterpret_cast<uint4*>(lds);
   const int chunks = cols >> 3;
   const int tail_chunks = (cols + 7) >> 3;            // chunks touched by x
-  // guards: kFrontPad/16 chunks in front, kBackPad/16 behind
-  constexpr int kGuardChunks = (kFrontPad + kBackPad) / 16;
-  for (int i = tid; i < kGuardChunks; i += nt)
-    lds16[i < kFrontPad / 16 ? i : i + tail_chunks] = zero;
-  uint16_t* xs = reinterpret_cast<uint16_t*>(lds + kFrontPad);
+  // guards: front_pad/16 chunks in front, back_pad/16 behind
+  const int guard_chunks = (front_pad + back_pad) / 16;
+  for (int i = tid; i < guard_chunks; i += nt)
+    lds16[i < front_pad / 16 ? i : i + tail_chunks] = zero;
+  uint16_t* xs = reinterpret_cast<uint16_t*>(lds + front_pad);
   uint4* xd = reinterpret_cast<uint4*>(xs);
   if (SIMPLE || (reinterpret_cast<uintptr_t>(x) & 15) == 0) {
 #pragma unroll
@@ -188,11 +193,10 @@ __host__ __device__ inline bool stage_x_is_simple(const void* x, int64_t cols, i
          cols <= (int64_t)8 * kXStageRegs * block;
 }
 
-__device__ __forceinline__ void stage_x_to_lds(unsigned char* lds, const uint16_t* __restrict__ x,
-                                               int cols, int lds_bytes) {
+__device__ __forceinline__ void stage_x_to_lds(unsigned char* lds, const uint16_t* __restrict__ x, int cols) {
   XStage st;
   stage_x_begin(st, x, cols);
-  stage_x_finish<false>(lds, st, x, cols, lds_bytes);
+  stage_x_finish<false>(lds, st, x, cols);
 }
 
 }  // namespace macko

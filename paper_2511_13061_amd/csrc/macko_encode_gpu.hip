@@ -7,9 +7,8 @@
 // columns (one 16-byte load, issued one step ahead).  The position of the
 // previous stored entry is carried across lanes with a DPP max-scan and across
 // steps in a register, so each lane can price its own non-zeros: a non-zero at
-// distance g from the previously stored column costs (g-1)/16 padding entries
-// plus itself, and inside a chunk of 8 columns only the first non-zero can cost
-// any.  Per-row counts go to arrays that the scan kernel totals (no atomics).
+// distance g from the previously stored column costs (g-1) / 2^b_delta padding
+// entries plus itself.  Per-row counts go to arrays that the scan kernel totals (no atomics).
 #include "macko_device.h"
 #include "macko_internal.h"
 
@@ -64,8 +63,9 @@ __device__ __forceinline__ Chunk decode_chunk(const RawChunk& r) {
 }
 
 // What a lane needs to know about its 8 columns.  Two non-zeros inside one
-// chunk are at most 7 columns apart, so only the first non-zero of a chunk can
-// need padding entries in front of it.
+// chunk are at most 7 columns apart, so with deltas of up to 8 or more only the
+// first non-zero of a chunk can need padding entries in front of it; for 1- and
+// 2-bit codes the gaps inside the chunk are priced one by one.
 struct LaneView {
   unsigned entries;   // stored entries this chunk contributes (non-zeros + padding)
   unsigned nnz;       // non-zeros in the chunk
@@ -74,7 +74,7 @@ struct LaneView {
 
 // `carry` is the position (column + 1, 0 = none) of the last stored entry of the
 // steps already consumed; it is advanced over this step.
-__device__ __forceinline__ LaneView view_chunk(unsigned mask, int col0, int lane, uint32_t* carry) {
+__device__ __forceinline__ LaneView view_chunk(unsigned mask, int col0, int lane, int b_delta, uint32_t* carry) {
   const uint32_t lastpos = mask ? (uint32_t)(col0 + 32 - __clz((int)mask)) : 0u;
   const uint32_t incl = wave_incl_scan_max_u32(lastpos);
   uint32_t prevpos = (uint32_t)__shfl_up((int)incl, 1);
@@ -84,12 +84,22 @@ __device__ __forceinline__ LaneView view_chunk(unsigned mask, int col0, int lane
   LaneView v;
   v.nnz = (unsigned)__popc(mask);
   v.lead = mask ? col0 + (__ffs((int)mask) - 1) - (int)prevpos : 0;
-  v.entries = mask ? v.nnz + (unsigned)(v.lead >> kDeltaBits) : 0u;
+  v.entries = mask ? v.nnz + (unsigned)(v.lead >> b_delta) : 0u;
+  if (b_delta < 3) {               // deltas of at most 2 or 4: gaps inside the chunk can need padding too
+    unsigned m = mask & (mask - 1);                      // every non-zero but the first
+    int prevk = mask ? __ffs((int)mask) - 1 : 0;
+    while (m) {
+      const int k = __ffs((int)m) - 1;
+      m &= m - 1;
+      v.entries += (unsigned)((k - prevk - 1) >> b_delta);
+      prevk = k;
+    }
+  }
   return v;
 }
 
 __global__ void __launch_bounds__(256)
-encode_count_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok,
+encode_count_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok, int b_delta,
                     uint32_t* __restrict__ row_entries, uint32_t* __restrict__ row_nnz) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -103,7 +113,7 @@ encode_count_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int6
       const int col0 = base + lane * 8;
       const Chunk c = decode_chunk(nxt);
       nxt = load_raw(src, col0 + 512, cols, vec_ok);                 // next step's columns, in flight
-      const LaneView v = view_chunk(c.mask, col0, lane, &carry);
+      const LaneView v = view_chunk(c.mask, col0, lane, b_delta, &carry);
       entries += v.entries;
       nnz += v.nnz;
     }
@@ -123,11 +133,12 @@ encode_count_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int6
 __global__ void __launch_bounds__(1024)
 encode_scan_kernel(const uint32_t* __restrict__ row_entries, const uint32_t* __restrict__ row_nnz,
                    int rows, uint32_t* __restrict__ row_ptr, EncodeStats* __restrict__ stats) {
-  __shared__ unsigned long long part[1024];
-  __shared__ unsigned long long part_nnz[1024];
-  __shared__ unsigned int part_empty[1024];
-  __shared__ unsigned int part_max[1024];
+  __shared__ unsigned long long wave_sum[16];
+  __shared__ unsigned long long wave_nnz[16];
+  __shared__ unsigned int wave_empty[16];
+  __shared__ unsigned int wave_max[16];
   const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
   const int seg = (rows + 1023) / 1024;
   const int lo = min(rows, t * seg), hi = min(rows, lo + seg);
   unsigned long long s = 0, n = 0;
@@ -139,30 +150,44 @@ encode_scan_kernel(const uint32_t* __restrict__ row_entries, const uint32_t* __r
     empty += e == 0;
     longest = max(longest, e);
   }
-  part[t] = s;
-  part_nnz[t] = n;
-  part_empty[t] = empty;
-  part_max[t] = longest;
+  // inclusive scan of the segment sums over the wavefront, totals of the rest
+  unsigned long long incl = s;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned long long up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    n += __shfl_xor(n, off);
+    empty += __shfl_xor(empty, off);
+    longest = max(longest, __shfl_xor(longest, off));
+  }
+  if (lane == 63) {
+    wave_sum[wave] = incl;
+    wave_nnz[wave] = n;
+    wave_empty[wave] = empty;
+    wave_max[wave] = longest;
+  }
   __syncthreads();
-  if (t == 0) {
-    unsigned long long run = 0, nn = 0;
+  unsigned long long before = 0;                       // entries of the wavefronts in front of this one
+  for (int i = 0; i < wave; ++i) before += wave_sum[i];
+  if (t == 1023) {
+    unsigned long long nn = 0;
     unsigned int em = 0, mx = 0;
-    for (int i = 0; i < 1024; ++i) {
-      const unsigned long long v = part[i];
-      part[i] = run;
-      run += v;
-      nn += part_nnz[i];
-      em += part_empty[i];
-      mx = max(mx, part_max[i]);
+    for (int i = 0; i < 16; ++i) {
+      nn += wave_nnz[i];
+      em += wave_empty[i];
+      mx = max(mx, wave_max[i]);
     }
-    stats->pad_nnz = run;
+    const unsigned long long total = before + incl;
+    stats->pad_nnz = total;
     stats->nnz = nn;
     stats->empty_rows = em;
     stats->max_row_entries = mx;
-    row_ptr[rows] = (uint32_t)run;
+    row_ptr[rows] = (uint32_t)total;
   }
-  __syncthreads();
-  unsigned long long run = part[t];
+  unsigned long long run = before + incl - s;
   for (int r = lo; r < hi; ++r) {
     row_ptr[r] = (uint32_t)run;
     run += row_entries[r];
@@ -170,9 +195,10 @@ encode_scan_kernel(const uint32_t* __restrict__ row_entries, const uint32_t* __r
 }
 
 __global__ void __launch_bounds__(256)
-encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok,
+encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok, int b_delta,
                    const uint32_t* __restrict__ row_ptr, uint16_t* __restrict__ values,
                    uint8_t* __restrict__ codes8) {
+  const int full = (1 << b_delta) - 1;             // code of the largest delta
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nwaves = blockDim.x >> 6;
@@ -185,24 +211,24 @@ encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64
       const int col0 = base + lane * 8;
       const Chunk c = decode_chunk(nxt);
       nxt = load_raw(src, col0 + 512, cols, vec_ok);                 // next step's columns, in flight
-      const LaneView v = view_chunk(c.mask, col0, lane, &carry);
+      const LaneView v = view_chunk(c.mask, col0, lane, b_delta, &carry);
       const uint32_t incl = wave_incl_scan_u32(v.entries);
       size_t o = (size_t)cursor + (incl - v.entries);
       if (c.mask) {
-        for (int pads = v.lead >> kDeltaBits; pads > 0; --pads) {   // padding entries, greedy
-          values[o] = 0;
-          codes8[o] = kMaxDelta - 1;
-          ++o;
-        }
         unsigned m = c.mask;
-        int g1 = v.lead & (kMaxDelta - 1);       // (delta - 1) of the next stored entry
+        int g1 = v.lead;                         // (gap - 1) in front of the next stored non-zero
         int prevk = -1;
         while (m) {
           const int k = __ffs((int)m) - 1;
           m &= m - 1;
           if (prevk >= 0) g1 = k - prevk - 1;
+          for (int pads = g1 >> b_delta; pads > 0; --pads) {        // padding entries, greedy
+            values[o] = 0;
+            codes8[o] = (uint8_t)full;
+            ++o;
+          }
           values[o] = c.h[k];
-          codes8[o] = (uint8_t)g1;
+          codes8[o] = (uint8_t)(g1 & full);
           ++o;
           prevk = k;
         }
@@ -212,17 +238,19 @@ encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64
   }
 }
 
-// deltas word i packs the codes of entries 8i .. 8i+7, entry k in bits 4(k&7)..
+// Packed word i holds the codes of entries (32 / b_delta) i ..., entry k in bits
+// b_delta (k mod (32 / b_delta)) upwards; one code byte per entry comes in.
 __global__ void __launch_bounds__(256)
-encode_pack_kernel(const uint8_t* __restrict__ codes8, int64_t words, uint32_t* __restrict__ deltas) {
+encode_pack_kernel(const uint8_t* __restrict__ codes8, int64_t words, int b_delta, uint32_t* __restrict__ deltas) {
+  const int per_word = 32 / b_delta;                 // 32, 16, 8 or 4 entries: a multiple of 4 bytes of input
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < words;
        i += (int64_t)gridDim.x * blockDim.x) {
-    const uint2 c = *reinterpret_cast<const uint2*>(codes8 + 8 * i);
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(codes8 + (int64_t)per_word * i);
     uint32_t w = 0;
+    for (int q = 0; q < per_word / 4; ++q) {
+      const uint32_t c = src[q];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      w |= ((c.x >> (8 * k)) & 15u) << (4 * k);
-      w |= ((c.y >> (8 * k)) & 15u) << (4 * k + 16);
+      for (int k = 0; k < 4; ++k) w |= ((c >> (8 * k)) & 0xFFu) << (b_delta * (4 * q + k));
     }
     deltas[i] = w;
   }
@@ -243,7 +271,8 @@ struct DeviceBuf {
 
 }  // namespace
 
-int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, hipStream_t stream,
+int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta,
+                     hipStream_t stream,
                      uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
                      int64_t* pad_nnz, int64_t* alloc_nnz, int64_t* empty_rows,
                      int64_t* max_row_entries) {
@@ -258,7 +287,7 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
   const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((rows + 3) / 4, (int64_t)cus * 16));
   if (rows > 0) {
     hipLaunchKernelGGL(encode_count_kernel, dim3(grid), dim3(256), 0, stream, dense, (int)rows,
-                       (int)cols, ld, vec_ok, static_cast<uint32_t*>(counts.p),
+                       (int)cols, ld, vec_ok, b_delta, static_cast<uint32_t*>(counts.p),
                        static_cast<uint32_t*>(nnzs.p));
   }
   hipLaunchKernelGGL(encode_scan_kernel, dim3(1), dim3(1024), 0, stream,
@@ -271,9 +300,10 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
   MACKO_HIP_TRY(hipStreamSynchronize(stream));
   if (st.pad_nnz >= (1ull << 32)) return MACKO_E_OVERFLOW;
   const int64_t pad = (int64_t)st.pad_nnz;
-  const int64_t alloc = (pad + kAllocGranule - 1) / kAllocGranule * kAllocGranule;
+  const int64_t granule = alloc_granule(b_delta);
+  const int64_t alloc = (pad + granule - 1) / granule * granule;
   if (alloc >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
-  if (vals.alloc((size_t)alloc * 2) != hipSuccess || dels.alloc((size_t)alloc / 2) != hipSuccess ||
+  if (vals.alloc((size_t)alloc * 2) != hipSuccess || dels.alloc((size_t)alloc * b_delta / 8) != hipSuccess ||
       codes.alloc((size_t)alloc) != hipSuccess) {
     (void)hipGetLastError();
     return MACKO_E_OUT_OF_MEMORY;
@@ -284,14 +314,14 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
   }
   if (rows > 0 && pad > 0) {
     hipLaunchKernelGGL(encode_fill_kernel, dim3(grid), dim3(256), 0, stream, dense, (int)rows, (int)cols,
-                       ld, vec_ok, static_cast<const uint32_t*>(rp.p), static_cast<uint16_t*>(vals.p),
+                       ld, vec_ok, b_delta, static_cast<const uint32_t*>(rp.p), static_cast<uint16_t*>(vals.p),
                        static_cast<uint8_t*>(codes.p));
   }
   if (alloc > 0) {
-    const int64_t words = alloc / 8;
+    const int64_t words = alloc * b_delta / 32;
     const unsigned pgrid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((words + 255) / 256, (int64_t)cus * 16));
     hipLaunchKernelGGL(encode_pack_kernel, dim3(pgrid), dim3(256), 0, stream,
-                       static_cast<const uint8_t*>(codes.p), words, static_cast<uint32_t*>(dels.p));
+                       static_cast<const uint8_t*>(codes.p), words, b_delta, static_cast<uint32_t*>(dels.p));
   }
   MACKO_HIP_TRY(hipGetLastError());
   MACKO_HIP_TRY(hipStreamSynchronize(stream));

@@ -51,7 +51,6 @@ __device__ __forceinline__ void gemv_wave_row_body(const uint4* __restrict__ W, 
                                                    const int q, const int r, const int wg,
                                                    const int inv_nwaves) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int lds_bytes = (int)lds_bytes_for(cols);
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
   const int row_begin = wg * q + min(wg, r);
   const int wg_rows = q + (wg < r ? 1 : 0);
@@ -100,7 +99,7 @@ __device__ __forceinline__ void gemv_wave_row_body(const uint4* __restrict__ W, 
   XStage xst;
   stage_x_begin(xst, x, cols);
   open_block();
-  stage_x_finish<false>(lds, xst, x, cols, lds_bytes);        // ends with a barrier
+  stage_x_finish<false>(lds, xst, x, cols);                   // ends with a barrier
 
   while (true) {
     float yv = 0.0f;                                   // lane i: result of row blk + i

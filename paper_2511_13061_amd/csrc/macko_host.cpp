@@ -1,6 +1,7 @@
 // Host side of libmacko: the C ABI, the handle, the host encoder / decoder and
 // the storage report.  The format is that of Section 4.1 with b_val = 16 and
-// b_delta = 4; see include/macko.h for the byte layout.
+// b_delta = 4 by default (1, 2 and 8 through the _ex entry points); see
+// include/macko.h for the byte layout.
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -42,7 +43,8 @@ int device_cu_count() {
 // Storage report: eq. 2 for the measured effective density, eqs. 8-10 for the
 // best / worst / expected cases at the measured density.
 void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, int64_t pad_nnz,
-                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries) {
+                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries, int b_delta) {
+  const double max_delta = static_cast<double>(1 << b_delta);
   std::memset(rep, 0, sizeof(*rep));
   rep->rows = rows;
   rep->cols = cols;
@@ -53,12 +55,12 @@ void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, i
   rep->empty_rows = empty_rows;
   rep->max_row_entries = max_row_entries;
   rep->values_bytes = alloc_nnz * 2;
-  rep->deltas_bytes = alloc_nnz / 2;
+  rep->deltas_bytes = alloc_nnz * b_delta / 8;
   rep->rowptr_bytes = 4 * (rows + 1);
   rep->total_bytes = rep->values_bytes + rep->deltas_bytes + rep->rowptr_bytes;
   rep->dense_bytes = 2 * rows * cols;
   rep->b_val = 16;
-  rep->b_delta = kDeltaBits;
+  rep->b_delta = b_delta;
   const double cells = static_cast<double>(rows) * static_cast<double>(cols);
   const double nan = std::numeric_limits<double>::quiet_NaN();
   rep->effd = cells > 0 ? static_cast<double>(rep->total_bytes) / (2.0 * cells) : 0.0;
@@ -67,11 +69,11 @@ void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, i
     return;
   }
   const double d = static_cast<double>(nnz) / cells;
-  const double per_entry = (16.0 + kDeltaBits) / 16.0;
+  const double per_entry = (16.0 + b_delta) / 16.0;
   rep->density = d;
   rep->effd_best = d * per_entry;
-  rep->effd_worst = (d + (1.0 - d) / kMaxDelta) * per_entry;
-  const double z = std::pow(1.0 - d, static_cast<double>(kMaxDelta));
+  rep->effd_worst = (d + (1.0 - d) / max_delta) * per_entry;
+  const double z = std::pow(1.0 - d, max_delta);
   rep->effd_expected = (d > 0.0 && d < 1.0) ? d * (1.0 + z / (1.0 - z)) * per_entry : d * per_entry;
 }
 
@@ -99,12 +101,12 @@ void parallel_blocks(int64_t n, F&& body) {
 }
 
 // Stored entries of one row: a non-zero whose distance to the previously
-// stored column is g costs (g-1)/16 padding entries plus itself.
-inline void count_row(const uint16_t* row, int64_t cols, int64_t* entries, int64_t* nnz) {
+// stored column is g costs (g-1) / 2^b_delta padding entries plus itself.
+inline void count_row(const uint16_t* row, int64_t cols, int b_delta, int64_t* entries, int64_t* nnz) {
   int64_t prev = -1, e = 0, n = 0;
   for (int64_t c = 0; c < cols; ++c) {
     if (!is_nonzero(row[c])) continue;
-    e += 1 + ((c - prev - 1) >> kDeltaBits);
+    e += 1 + ((c - prev - 1) >> b_delta);
     ++n;
     prev = c;
   }
@@ -114,28 +116,29 @@ inline void count_row(const uint16_t* row, int64_t cols, int64_t* entries, int64
 
 // Write one row's entries; codes go to a byte-per-entry scratch array that is
 // packed afterwards (two rows may share a byte of the packed array).
-inline void fill_row(const uint16_t* row, int64_t cols, uint16_t* values, uint8_t* codes) {
+inline void fill_row(const uint16_t* row, int64_t cols, int b_delta, uint16_t* values, uint8_t* codes) {
+  const int64_t full = (int64_t{1} << b_delta) - 1;   // code of the largest delta
   int64_t prev = -1, k = 0;
   for (int64_t c = 0; c < cols; ++c) {
     const uint16_t w = row[c];
     if (!is_nonzero(w)) continue;
     const int64_t g1 = c - prev - 1;          // gap - 1
-    for (int64_t p = g1 >> kDeltaBits; p > 0; --p) {
+    for (int64_t p = g1 >> b_delta; p > 0; --p) {
       values[k] = 0;
-      codes[k] = kMaxDelta - 1;
+      codes[k] = static_cast<uint8_t>(full);
       ++k;
     }
     values[k] = w;
-    codes[k] = static_cast<uint8_t>(g1 & (kMaxDelta - 1));
+    codes[k] = static_cast<uint8_t>(g1 & full);
     ++k;
     prev = c;
   }
 }
 
-int encode_host(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, macko_matrix* m) {
+int encode_host(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta, macko_matrix* m) {
   std::vector<int64_t> entries(rows), nnzs(rows);
   parallel_blocks(rows, [&](int64_t lo, int64_t hi) {
-    for (int64_t r = lo; r < hi; ++r) count_row(dense + r * ld, cols, &entries[r], &nnzs[r]);
+    for (int64_t r = lo; r < hi; ++r) count_row(dense + r * ld, cols, b_delta, &entries[r], &nnzs[r]);
   });
   int64_t pad_nnz = 0, nnz = 0, empty = 0, longest = 0;
   m->h_row_ptr.assign(rows + 1, 0);
@@ -147,27 +150,34 @@ int encode_host(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, m
     if (pad_nnz >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
     m->h_row_ptr[r + 1] = static_cast<uint32_t>(pad_nnz);
   }
-  const int64_t alloc = (pad_nnz + kAllocGranule - 1) / kAllocGranule * kAllocGranule;
+  const int64_t granule = alloc_granule(b_delta);
+  const int64_t alloc = (pad_nnz + granule - 1) / granule * granule;
   if (alloc >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
   m->h_values.assign(alloc, 0);
-  m->h_deltas.assign(alloc / 2, 0);
+  m->h_deltas.assign(alloc * b_delta / 8, 0);
   std::vector<uint8_t> codes(alloc, 0);
   parallel_blocks(rows, [&](int64_t lo, int64_t hi) {
     for (int64_t r = lo; r < hi; ++r) {
       const int64_t at = m->h_row_ptr[r];
-      fill_row(dense + r * ld, cols, m->h_values.data() + at, codes.data() + at);
+      fill_row(dense + r * ld, cols, b_delta, m->h_values.data() + at, codes.data() + at);
     }
   });
-  parallel_blocks(alloc / 2, [&](int64_t lo, int64_t hi) {
-    for (int64_t b = lo; b < hi; ++b)
-      m->h_deltas[b] = static_cast<uint8_t>(codes[2 * b] | (codes[2 * b + 1] << 4));
+  // entry k occupies bits [k * b_delta, (k + 1) * b_delta) of the packed array (low bits first)
+  const int per_byte = 8 / b_delta;
+  parallel_blocks(alloc / per_byte, [&](int64_t lo, int64_t hi) {
+    for (int64_t b = lo; b < hi; ++b) {
+      unsigned byte = 0;
+      for (int j = 0; j < per_byte; ++j) byte |= static_cast<unsigned>(codes[per_byte * b + j]) << (b_delta * j);
+      m->h_deltas[b] = static_cast<uint8_t>(byte);
+    }
   });
   m->rows = rows;
   m->cols = cols;
   m->pad_nnz = pad_nnz;
   m->alloc_nnz = alloc;
+  m->b_delta = b_delta;
   m->has_host = true;
-  fill_report(&m->report, rows, cols, nnz, pad_nnz, alloc, empty, longest);
+  fill_report(&m->report, rows, cols, nnz, pad_nnz, alloc, empty, longest, b_delta);
   return MACKO_OK;
 }
 
@@ -178,16 +188,23 @@ using macko::tuning;
 
 extern "C" {
 
+static bool valid_b_delta(int b) { return b == 1 || b == 2 || b == 4 || b == 8; }
+
 int macko_encode(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                  macko_handle_t* out, macko_report_t* report) {
+  return macko_encode_ex(dense_host, rows, cols, ld, macko::kDeltaBits, out, report);
+}
+
+int macko_encode_ex(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld, int b_delta,
+                    macko_handle_t* out, macko_report_t* report) {
   if (out) *out = nullptr;
-  if (!out || rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
+  if (!out || rows < 0 || cols < 0 || ld < cols || !valid_b_delta(b_delta)) return MACKO_E_INVALID_ARG;
   if (!dense_host && rows > 0 && cols > 0) return MACKO_E_INVALID_ARG;
   if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
   macko_matrix* m = nullptr;
   try {
     m = new macko_matrix();
-    int st = macko::encode_host(dense_host, rows, cols, ld, m);
+    int st = macko::encode_host(dense_host, rows, cols, ld, b_delta, m);
     if (st != MACKO_OK) {
       delete m;
       return st;
@@ -206,8 +223,13 @@ int macko_encode(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t
 
 int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, void* stream,
                         macko_handle_t* out, macko_report_t* report) {
+  return macko_encode_device_ex(dense_dev, rows, cols, ld, macko::kDeltaBits, stream, out, report);
+}
+
+int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, int b_delta,
+                           void* stream, macko_handle_t* out, macko_report_t* report) {
   if (out) *out = nullptr;
-  if (!out || rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
+  if (!out || rows < 0 || cols < 0 || ld < cols || !valid_b_delta(b_delta)) return MACKO_E_INVALID_ARG;
   if (!dense_dev && rows > 0 && cols > 0) return MACKO_E_INVALID_ARG;
   if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
   macko_matrix* m = new (std::nothrow) macko_matrix();
@@ -216,7 +238,7 @@ int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64
   uint8_t* d = nullptr;
   uint32_t* rp = nullptr;
   int64_t nnz = 0, pad = 0, alloc = 0, empty = 0, longest = 0;
-  int st = macko::encode_on_device(static_cast<const uint16_t*>(dense_dev), rows, cols, ld,
+  int st = macko::encode_on_device(static_cast<const uint16_t*>(dense_dev), rows, cols, ld, b_delta,
                                    static_cast<hipStream_t>(stream), &v, &d, &rp, &nnz, &pad, &alloc,
                                    &empty, &longest);
   if (st != MACKO_OK) {
@@ -230,9 +252,10 @@ int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64
   m->d_values = v;
   m->d_deltas = d;
   m->d_row_ptr = rp;
+  m->b_delta = b_delta;
   m->bound = true;
   m->owns_device = true;
-  macko::fill_report(&m->report, rows, cols, nnz, pad, alloc, empty, longest);
+  macko::fill_report(&m->report, rows, cols, nnz, pad, alloc, empty, longest, b_delta);
   if (report) *report = m->report;
   *out = m;
   return MACKO_OK;
@@ -240,13 +263,20 @@ int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64
 
 int macko_wrap_device(int64_t rows, int64_t cols, int64_t pad_nnz, const void* values_dev,
                       const void* deltas_dev, const void* rowptr_dev, macko_handle_t* out) {
+  return macko_wrap_device_ex(rows, cols, pad_nnz, macko::kDeltaBits, values_dev, deltas_dev, rowptr_dev, out);
+}
+
+int macko_wrap_device_ex(int64_t rows, int64_t cols, int64_t pad_nnz, int b_delta, const void* values_dev,
+                         const void* deltas_dev, const void* rowptr_dev, macko_handle_t* out) {
   if (out) *out = nullptr;
-  if (!out || rows < 0 || cols < 0 || pad_nnz < 0 || !rowptr_dev) return MACKO_E_INVALID_ARG;
+  if (!out || rows < 0 || cols < 0 || pad_nnz < 0 || !rowptr_dev || !valid_b_delta(b_delta))
+    return MACKO_E_INVALID_ARG;
   if (pad_nnz > 0 && (!values_dev || !deltas_dev)) return MACKO_E_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(values_dev) & 15) || (reinterpret_cast<uintptr_t>(deltas_dev) & 15) ||
       (reinterpret_cast<uintptr_t>(rowptr_dev) & 3))
     return MACKO_E_INVALID_ARG;
-  const int64_t alloc = (pad_nnz + macko::kAllocGranule - 1) / macko::kAllocGranule * macko::kAllocGranule;
+  const int64_t granule = macko::alloc_granule(b_delta);
+  const int64_t alloc = (pad_nnz + granule - 1) / granule * granule;
   if (alloc >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
   if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
   macko_matrix* m = new (std::nothrow) macko_matrix();
@@ -258,8 +288,9 @@ int macko_wrap_device(int64_t rows, int64_t cols, int64_t pad_nnz, const void* v
   m->d_values = static_cast<const uint16_t*>(values_dev);
   m->d_deltas = static_cast<const uint8_t*>(deltas_dev);
   m->d_row_ptr = static_cast<const uint32_t*>(rowptr_dev);
+  m->b_delta = b_delta;
   m->bound = true;
-  macko::fill_report(&m->report, rows, cols, -1, pad_nnz, alloc, -1, -1);
+  macko::fill_report(&m->report, rows, cols, -1, pad_nnz, alloc, -1, -1, b_delta);
   *out = m;
   return MACKO_OK;
 }
@@ -274,7 +305,7 @@ int macko_device_bytes(macko_handle_t h, int64_t* values_bytes, int64_t* deltas_
                        int64_t* rowptr_bytes) {
   if (!h) return MACKO_E_INVALID_ARG;
   if (values_bytes) *values_bytes = h->alloc_nnz * 2;
-  if (deltas_bytes) *deltas_bytes = h->alloc_nnz / 2;
+  if (deltas_bytes) *deltas_bytes = h->alloc_nnz * h->b_delta / 8;
   if (rowptr_bytes) *rowptr_bytes = 4 * (h->rows + 1);
   return MACKO_OK;
 }
@@ -290,7 +321,7 @@ int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas_dev, void
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (h->alloc_nnz > 0) {
     MACKO_HIP_TRY(hipMemcpyAsync(values_dev, h->h_values.data(), h->alloc_nnz * 2, hipMemcpyHostToDevice, s));
-    MACKO_HIP_TRY(hipMemcpyAsync(deltas_dev, h->h_deltas.data(), h->alloc_nnz / 2, hipMemcpyHostToDevice, s));
+    MACKO_HIP_TRY(hipMemcpyAsync(deltas_dev, h->h_deltas.data(), h->alloc_nnz * h->b_delta / 8, hipMemcpyHostToDevice, s));
   }
   MACKO_HIP_TRY(hipMemcpyAsync(rowptr_dev, h->h_row_ptr.data(), 4 * (h->rows + 1), hipMemcpyHostToDevice, s));
   // the host vectors are pageable: make sure the copies have left them before returning
@@ -320,7 +351,7 @@ int macko_fetch_device(macko_handle_t h, uint16_t* values_host, uint8_t* deltas_
   if (h->alloc_nnz > 0) {
     if (!values_host || !deltas_host) return MACKO_E_INVALID_ARG;
     MACKO_HIP_TRY(hipMemcpy(values_host, h->d_values, h->alloc_nnz * 2, hipMemcpyDeviceToHost));
-    MACKO_HIP_TRY(hipMemcpy(deltas_host, h->d_deltas, h->alloc_nnz / 2, hipMemcpyDeviceToHost));
+    MACKO_HIP_TRY(hipMemcpy(deltas_host, h->d_deltas, h->alloc_nnz * h->b_delta / 8, hipMemcpyDeviceToHost));
   }
   MACKO_HIP_TRY(hipMemcpy(rowptr_host, h->d_row_ptr, 4 * (h->rows + 1), hipMemcpyDeviceToHost));
   return MACKO_OK;
@@ -334,8 +365,10 @@ int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld) {
     uint16_t* row = dense_host_out + r * ld;
     std::fill(row, row + h->cols, uint16_t{0});
     int64_t pos = 0;  // column + 1 of the last decoded entry
+    const int b = h->b_delta;
     for (int64_t k = h->h_row_ptr[r]; k < h->h_row_ptr[r + 1]; ++k) {
-      pos += ((h->h_deltas[k >> 1] >> (4 * (k & 1))) & 15) + 1;
+      const int64_t bit = k * b;
+      pos += ((h->h_deltas[bit >> 3] >> (bit & 7)) & ((1u << b) - 1u)) + 1;
       if (pos > h->cols) return MACKO_E_INVALID_ARG;
       row[pos - 1] = h->h_values[k];
     }
@@ -367,7 +400,7 @@ int macko_spmv_group(int n, const macko_handle_t* handles, const void* const* x_
     int st = check_vec_ptrs(x_dev[i], y_dev[i], h->cols);
     if (st != MACKO_OK) return st;
     p[m++] = macko::SpmvProblem{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
-                                x_dev[i], y_dev[i]};
+                                x_dev[i], y_dev[i], h->b_delta};
   }
   if (m == 0) return MACKO_OK;
   return macko::launch_spmv_group(m, p, static_cast<hipStream_t>(stream));
@@ -381,7 +414,9 @@ int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void
   if (ldx < h->cols || ldy < h->rows) return MACKO_E_INVALID_ARG;
   int st = check_vec_ptrs(X_dev, Y_dev, h->cols);
   if (st != MACKO_OK) return st;
-  macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz, nullptr, nullptr};
+  if (h->b_delta != macko::kDeltaBits) return MACKO_E_UNSUPPORTED;   // the batch kernel decodes 4-bit codes only
+  macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz, nullptr, nullptr,
+                       h->b_delta};
   return macko::launch_spmm(p, X_dev, ldx, Y_dev, ldy, batch, static_cast<hipStream_t>(stream));
 }
 

@@ -10,9 +10,9 @@
 
 namespace macko {
 
-constexpr int kDeltaBits = 4;           // b_delta
-constexpr int kMaxDelta = 16;           // 2^b_delta
-constexpr int kAllocGranule = 32;       // entries per 16 bytes of packed deltas
+constexpr int kDeltaBits = 4;           // default b_delta
+// entries per 16 bytes of packed codes: both arrays are padded to a multiple of this
+constexpr int64_t alloc_granule(int b_delta) { return 128 / b_delta; }
 
 struct Tuning {
   int64_t spmv_kernel = 0;
@@ -50,6 +50,7 @@ struct SpmvProblem {
   int64_t rows, cols, pad_nnz;
   const void* x;
   void* y;
+  int b_delta = kDeltaBits;
 };
 struct GemvProblem {
   const void* W;
@@ -64,19 +65,21 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream);
 int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64_t ldy, int batch,
                 hipStream_t stream);
 // GPU encoder: counting pass + fill pass.  Allocates *values, *deltas, *row_ptr with hipMalloc.
-int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, hipStream_t stream,
+int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta,
+                     hipStream_t stream,
                      uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
                      int64_t* pad_nnz, int64_t* alloc_nnz, int64_t* empty_rows,
                      int64_t* max_row_entries);
 
 void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, int64_t pad_nnz,
-                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries);
+                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries, int b_delta);
 
 }  // namespace macko
 
 struct macko_matrix {
   int64_t rows = 0, cols = 0;
   int64_t pad_nnz = 0, alloc_nnz = 0;
+  int b_delta = macko::kDeltaBits;
   macko_report_t report{};
   // host copy (empty for device-encoded and wrapped handles)
   bool has_host = false;

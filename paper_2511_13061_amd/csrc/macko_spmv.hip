@@ -19,16 +19,26 @@ namespace {
 // ---------------------------------------------------------------------------
 // Generic kernel: LANES (16, 32 or 64) lanes cooperate on a row, so a wavefront
 // works on 64/LANES rows at once.  Every entry is individually masked against
-// the row bounds.  Used for short rows and as the fallback when x does not fit
-// in LDS (XLDS = false gathers x from global memory).
+// the row bounds.  Used for short rows, for 1-bit codes, and as the fallback
+// when x does not fit in LDS (XLDS = false gathers x from global memory).
 // ---------------------------------------------------------------------------
-template <int LANES, bool XLDS>
+// The BD-bit codes of the 8 entries of chunk `chunk`, entry k in bits [BD k, BD (k+1)).
+template <int BD>
+__device__ __forceinline__ uint64_t load_chunk_codes(const uint32_t* __restrict__ deltas, uint32_t chunk) {
+  if (BD == 1) return reinterpret_cast<const uint8_t*>(deltas)[chunk];
+  if (BD == 2) return reinterpret_cast<const uint16_t*>(deltas)[chunk];
+  if (BD == 4) return deltas[chunk];
+  const uint2 v = reinterpret_cast<const uint2*>(deltas)[chunk];
+  return (uint64_t)v.x | ((uint64_t)v.y << 32);
+}
+
+template <int LANES, bool XLDS, int BD>
 __global__ void __launch_bounds__(1024)
 spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
                     const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
-                    uint16_t* __restrict__ y, int rows, int cols, int rows_per_wg, int lds_bytes) {
+                    uint16_t* __restrict__ y, int rows, int cols, int rows_per_wg) {
   extern __shared__ __align__(16) unsigned char lds[];
-  if (XLDS) stage_x_to_lds(lds, x, cols, lds_bytes);
+  if (XLDS) stage_x_to_lds(lds, x, cols);
   const uint16_t* xs = XLDS ? reinterpret_cast<const uint16_t*>(lds + kFrontPad) : x;
 
   const int groups = blockDim.x / LANES;
@@ -47,10 +57,10 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
     float acc = 0.0f;
     while (__any(cur < end)) {
       const uint32_t e0 = cur + 8u * gl;
-      uint32_t w = 0;
+      uint64_t w = 0;
       uint4 v = make_uint4(0, 0, 0, 0);
       if (e0 < end) {                  // the 8-entry chunk intersects [start, end)
-        w = deltas[e0 >> 3];
+        w = load_chunk_codes<BD>(deltas, e0 >> 3);
         v = values[e0 >> 3];
       }
       const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
@@ -59,7 +69,7 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         const bool valid = (e0 + k >= start) && (e0 + k < end);
-        d[k] = valid ? (int)((w >> (4 * k)) & 15u) + 1 : 0;
+        d[k] = valid ? (int)((w >> (BD * k)) & ((1u << BD) - 1u)) + 1 : 0;
         local += d[k];
       }
       int incl = local;                // inclusive prefix over the group (Alg. 1)
@@ -124,6 +134,120 @@ __device__ __forceinline__ float gather_x(const unsigned char* xbase, int q) {
   return f16_bits_to_f32(*reinterpret_cast<const uint16_t*>(xbase + q));
 }
 
+// ---------------------------------------------------------------------------
+// Codes of a lane's 8 consecutive entries and the positions they decode to, for
+// code widths of 2, 4 and 8 bits.  All positions are doubled (bytes of the LDS
+// copy of x) and include the +1 per entry, i.e. entry k advances by 2 code + 2.
+//   load(deltas, chunk)  the 2 / 4 / 8 bytes of chunk `chunk` (8 entries)
+//   clear()              all codes 0 (every entry one column after the other)
+//   decode()             prefix sums inside the lane
+//   total()              doubled sum of the lane's 8 deltas
+//   offset<K>()          doubled position of entry K relative to the lane's start, minus 2
+//                        (= byte offset of its column in x when the lane starts at column 0)
+//   through(k)           lane 0's doubled position after entry k (k wavefront-uniform)
+// ---------------------------------------------------------------------------
+template <int BD>
+struct LaneCodes;
+
+// 2- and 4-bit codes: the eight doubled prefixes are at most 2*15*8 = 240 and fit
+// the bytes of two words; the constant part 2K of entry K is added bytewise.
+template <int BD>
+struct LaneCodesBytes {
+  uint32_t w;           // packed codes as loaded
+  uint32_t P, E;        // byte m: doubled code prefix through entry 2m+1 / 2m
+  uint32_t P2, E2;      // the same plus the constant part: doubled position of the entry, minus 2
+  __device__ __forceinline__ void clear() { w = 0u; }
+  __device__ __forceinline__ void keep_if(bool c) { w = c ? w : 0u; }
+  __device__ __forceinline__ void decode() {
+    uint32_t lo2, hi2;                                 // doubled codes of even / odd entries, one per byte
+    if (BD == 4) {
+      lo2 = (w << 1) & 0x1E1E1E1Eu;
+      hi2 = (w >> 3) & 0x1E1E1E1Eu;
+    } else {                                           // 2-bit codes: one nibble per pair of entries
+      uint32_t t = w & 0xFFFFu;
+      t = (t | (t << 8)) & 0x00FF00FFu;
+      t = (t | (t << 4)) & 0x0F0F0F0Fu;                // byte m: codes of entries 2m (bits 0-1) and 2m+1 (bits 2-3)
+      lo2 = (t << 1) & 0x06060606u;
+      hi2 = (t >> 1) & 0x06060606u;
+    }
+    P = lo2 + hi2;                                     // pair sums
+    P = lshl_add<8>(P, P);
+    P = lshl_add<16>(P, P);
+    E = lshl_add<8>(P, lo2);
+    E2 = E + 0x0C080400u;                              // the largest byte, 240 + 14, still fits
+    P2 = P + 0x0E0A0602u;
+  }
+  __device__ __forceinline__ uint32_t total() const { return (P >> 24) + 16u; }
+  template <int K>
+  __device__ __forceinline__ int offset() const {
+    return (int)((((K & 1) ? P2 : E2) >> (8 * (K >> 1))) & 0xFFu);
+  }
+  __device__ __forceinline__ uint32_t through(int k) const {
+    const uint32_t src = __builtin_amdgcn_readfirstlane((k & 1) ? P : E);
+    return ((src >> (8 * (k >> 1))) & 0xFFu) + 2u * (uint32_t)(k + 1);
+  }
+};
+template <>
+struct LaneCodes<4> : LaneCodesBytes<4> {
+  __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) { w = deltas[chunk]; }
+};
+template <>
+struct LaneCodes<2> : LaneCodesBytes<2> {
+  __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
+    w = reinterpret_cast<const uint16_t*>(deltas)[chunk];
+  }
+};
+
+// 8-bit codes: prefixes reach 8 * 512 = 4096 and are kept as 16-bit halves of four words.
+template <>
+struct LaneCodes<8> {
+  uint32_t w0, w1;      // codes of entries 0..3 and 4..7, one per byte
+  uint32_t X[4];        // halves of X[i]: doubled position after entry 2i and after entry 2i+1
+  uint32_t tot;
+  __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
+    const uint2 v = reinterpret_cast<const uint2*>(deltas)[chunk];
+    w0 = v.x;
+    w1 = v.y;
+  }
+  __device__ __forceinline__ void clear() { w0 = w1 = 0u; }
+  __device__ __forceinline__ void keep_if(bool c) {
+    w0 = c ? w0 : 0u;
+    w1 = c ? w1 : 0u;
+  }
+  __device__ __forceinline__ void decode() {
+    // bytes (c_2i, c_2i+1) -> halves, then 2c + 2 in every half
+    uint32_t Y[4];
+    Y[0] = __builtin_amdgcn_perm(0u, w0, 0x0C010C00u);
+    Y[1] = __builtin_amdgcn_perm(0u, w0, 0x0C030C02u);
+    Y[2] = __builtin_amdgcn_perm(0u, w1, 0x0C010C00u);
+    Y[3] = __builtin_amdgcn_perm(0u, w1, 0x0C030C02u);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      Y[i] = (Y[i] << 1) + 0x00020002u;
+      Y[i] = lshl_add<16>(Y[i], Y[i]);                 // low half: entry 2i alone, high half: the pair
+    }
+    const uint32_t r1 = Y[0] >> 16;
+    const uint32_t r2 = r1 + (Y[1] >> 16);
+    const uint32_t r3 = r2 + (Y[2] >> 16);
+    tot = r3 + (Y[3] >> 16);
+    X[0] = Y[0];
+    X[1] = Y[1] + (r1 | (r1 << 16));
+    X[2] = Y[2] + (r2 | (r2 << 16));
+    X[3] = Y[3] + (r3 | (r3 << 16));
+  }
+  __device__ __forceinline__ uint32_t total() const { return tot; }
+  template <int K>
+  __device__ __forceinline__ int offset() const {
+    return (int)((K & 1) ? (X[K >> 1] >> 16) : (X[K >> 1] & 0xFFFFu)) - 2;
+  }
+  __device__ __forceinline__ uint32_t through(int k) const {
+    const int i = k >> 1;
+    const uint32_t sel = i == 0 ? X[0] : (i == 1 ? X[1] : (i == 2 ? X[2] : X[3]));
+    const uint32_t src = __builtin_amdgcn_readfirstlane(sel);
+    return (k & 1) ? (src >> 16) : (src & 0xFFFFu);
+  }
+};
+
 // One matrix of a grouped launch.  Its rows are dealt out evenly over its
 // workgroups: q rows each, one more for the first r of them.
 struct SpmvMat {
@@ -150,7 +274,7 @@ struct SpmvGroupHeader {
 
 // The work of one workgroup: workgroup number `wg` of the matrix given by the
 // pointers, whose rows are dealt out q (+1 for the first r workgroups) at a time.
-template <int RING, bool SIMPLE>
+template <int RING, bool SIMPLE, int BD>
 __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ values,
                                                    const uint32_t* __restrict__ deltas,
                                                    const uint32_t* __restrict__ row_ptr,
@@ -158,14 +282,13 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
                                                    const int rows, const int cols, const int q, const int r,
                                                    const int wg, const int inv_nwaves) {
   extern __shared__ __align__(16) unsigned char lds[];
-  const int lds_bytes = (int)lds_bytes_for(cols);
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
   const int row_begin = wg * q + min(wg, r);
   const int wg_rows = q + (wg < r ? 1 : 0);
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const unsigned char* xbase = lds + kFrontPad;       // LDS address of x[0]
+  const unsigned char* xbase = lds + front_pad_for(BD);   // LDS address of x[0]
   const uint32_t lane8 = 8u * lane;
   const int per_wave = (wg_rows * inv_nwaves) >> 16;   // wg_rows / nwaves (exact for wg_rows <= 1024)
   const int extra = wg_rows - per_wave * nwaves;         // wg_rows % nwaves
@@ -177,7 +300,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
   const int nb = wrow_end - wrow_begin;                // at most 64: the host caps rows_per_wg
   uint32_t rp_lo = 0, rp_hi = 0;
   RowCursor ld, cp;                                    // load side, compute side
-  uint32_t wq[RING];
+  LaneCodes<BD> wq[RING];
   uint4 vq[RING];
 
   auto issue = [&](int j) {
@@ -190,7 +313,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
       }
     }                  // else a padding item: every lane re-reads its previous chunk (a line it has just
                        // used; one fixed address would make every wavefront queue at the same L2 channel)
-    wq[j] = deltas[chunk];
+    wq[j].load(deltas, chunk);
     vq[j] = values[chunk];
   };
   auto fetch_row_ptrs = [&]() {                        // unconditional loads, clamped to the last row
@@ -213,7 +336,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
   fetch_row_ptrs();
   stage_x_begin(xst, x, cols);
   prime_ring();
-  stage_x_finish<SIMPLE>(lds, xst, x, cols, lds_bytes);  // ends with a barrier
+  stage_x_finish<SIMPLE>(lds, xst, x, cols, front_pad_for(BD), back_pad_for(BD));  // ends with a barrier
 
   {
     float yv = 0.0f;                                   // lane i: result of row blk + i
@@ -222,7 +345,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
     while (cp.i < nb) {
 #pragma unroll
       for (int j = 0; j < RING; ++j) {
-        uint32_t w = wq[j];
+        LaneCodes<BD> w = wq[j];
         uint4 v = vq[j];
 
         const bool live = cp.i < nb;                   // false for the padding items after the last row
@@ -231,46 +354,32 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
         const uint32_t e0 = cp.a0 + 512u * cp.step + lane8;
         if (!live || cp.step == cp.nsteps - 1) {       // clear what lies past the row end
           const uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;   // valid entries in this lane's chunk
-          w = nv != 0 ? w : 0u;
+          w.keep_if(nv != 0);
           v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
           v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
           v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
           v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
         }
-        // doubled codes of even / odd entries, one per byte
-        const uint32_t lo2 = (w << 1) & 0x1E1E1E1Eu;
-        const uint32_t hi2 = (w >> 3) & 0x1E1E1E1Eu;
-        uint32_t P = lo2 + hi2;                        // pair sums
-        P = lshl_add<8>(P, P);
-        P = lshl_add<16>(P, P);                        // byte m: doubled code prefix through entry 2m+1
-        const uint32_t E = lshl_add<8>(P, lo2);        // byte m: doubled code prefix through entry 2m
-        const uint32_t tot = (P >> 24) + 16u;          // doubled sum of this lane's 8 deltas
+        w.decode();
+        const uint32_t tot = w.total();                // doubled sum of this lane's 8 deltas
         const uint32_t incl = wave_incl_scan_u32(tot);
         if (live && cp.step == 0) {
           base2 = 0;
           const int before = (int)(cp.start - cp.a0);  // entries of the previous row in lane 0's chunk
-          if (before > 0) {
-            const int k = before - 1;
-            const uint32_t src = __builtin_amdgcn_readfirstlane((k & 1) ? P : E);
-            base2 = -(int)(((src >> (8 * (k >> 1))) & 0xFFu) + 2u * (uint32_t)(k + 1));
-          }
+          if (before > 0) base2 = -(int)w.through(before - 1);
         }
-        // byte m of E2 / P2: doubled position of entry 2m / 2m+1 relative to the lane,
-        // minus 2 (so that the largest value, 240 + 14, still fits a byte)
-        const uint32_t E2 = E + 0x0C080400u;
-        const uint32_t P2 = P + 0x0E0A0602u;
         const int lanebase = base2 + (int)(incl - tot);   // byte offset in x of the lane's chunk start
-#define MACKO_X(word, m) gather_x(xbase, lanebase + (int)(((word) >> (8 * (m))) & 0xFFu))
+#define MACKO_X(k) gather_x(xbase, lanebase + w.template offset<k>())
 #define MACKO_LO(u) f16_bits_to_f32((uint16_t)((u) & 0xFFFFu))
 #define MACKO_HI(u) f16_bits_to_f32((uint16_t)((u) >> 16))
-        acc = fmaf(MACKO_LO(v.x), MACKO_X(E2, 0), acc);
-        acc = fmaf(MACKO_HI(v.x), MACKO_X(P2, 0), acc);
-        acc = fmaf(MACKO_LO(v.y), MACKO_X(E2, 1), acc);
-        acc = fmaf(MACKO_HI(v.y), MACKO_X(P2, 1), acc);
-        acc = fmaf(MACKO_LO(v.z), MACKO_X(E2, 2), acc);
-        acc = fmaf(MACKO_HI(v.z), MACKO_X(P2, 2), acc);
-        acc = fmaf(MACKO_LO(v.w), MACKO_X(E2, 3), acc);
-        acc = fmaf(MACKO_HI(v.w), MACKO_X(P2, 3), acc);
+        acc = fmaf(MACKO_LO(v.x), MACKO_X(0), acc);
+        acc = fmaf(MACKO_HI(v.x), MACKO_X(1), acc);
+        acc = fmaf(MACKO_LO(v.y), MACKO_X(2), acc);
+        acc = fmaf(MACKO_HI(v.y), MACKO_X(3), acc);
+        acc = fmaf(MACKO_LO(v.z), MACKO_X(4), acc);
+        acc = fmaf(MACKO_HI(v.z), MACKO_X(5), acc);
+        acc = fmaf(MACKO_LO(v.w), MACKO_X(6), acc);
+        acc = fmaf(MACKO_HI(v.w), MACKO_X(7), acc);
 #undef MACKO_X
 #undef MACKO_LO
 #undef MACKO_HI
@@ -290,8 +399,8 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
   }
 }
 
-// Grouped launch: the workgroup first finds its matrix.
-template <int RING, bool SIMPLE>
+// Grouped launch (matrices of one code width): the workgroup first finds its matrix.
+template <int RING, bool SIMPLE, int BD>
 __global__ void __launch_bounds__(1024)
 spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4, const int wb5, const int wb6,
                      const int wb7, const int inv_nwaves, const SpmvGroupArgs g) {
@@ -304,20 +413,21 @@ spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4,
     mi = in ? i : mi;
     wg0 = in ? wbs[i] : wg0;
   }
-  spmv_wave_row_body<RING, SIMPLE>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
-                                   g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
-                                   inv_nwaves);
+  spmv_wave_row_body<RING, SIMPLE, BD>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
+                                       g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
+                                       inv_nwaves);
 }
 
 // One matrix: everything the workgroup needs is a scalar argument (15 registers),
 // so a starting wavefront goes straight to its row pointers without any argument load.
-template <int RING, bool SIMPLE>
+template <int RING, bool SIMPLE, int BD>
 __global__ void __launch_bounds__(1024)
 spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
                      const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
                      uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
                      const int inv_nwaves) {
-  spmv_wave_row_body<RING, SIMPLE>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x, inv_nwaves);
+  spmv_wave_row_body<RING, SIMPLE, BD>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
+                                       inv_nwaves);
 }
 
 // y = 0 for a matrix without stored entries
@@ -346,16 +456,41 @@ constexpr int64_t kWideLdsBytes = 36 * 1024;
 
 namespace {
 
-int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
-  const Tuning& t = tuning();
-  const int cus = device_cu_count();
-  const int64_t lds_bytes = lds_bytes_for(p.cols);
-  const bool lds_ok = lds_bytes <= kMaxLdsBytes;
-  const int64_t avg = p.rows > 0 ? p.pad_nnz / p.rows : 0;
+template <int LANES, int BD>
+int launch_subwave_as(const SpmvProblem& p, int block, int64_t grid, int64_t rpw, bool lds_ok, int64_t lds_bytes,
+                      hipStream_t stream) {
   const uint4* v4 = reinterpret_cast<const uint4*>(p.values);
   const uint32_t* d4 = reinterpret_cast<const uint32_t*>(p.deltas);
   const uint16_t* xp = static_cast<const uint16_t*>(p.x);
   uint16_t* yp = static_cast<uint16_t*>(p.y);
+  if (lds_ok) {
+    auto kfn = spmv_subwave_kernel<LANES, true, BD>;
+    int st = set_lds_limit(kfn, lds_bytes);
+    if (st != MACKO_OK) return st;
+    hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds_bytes, stream, v4, d4, p.row_ptr, xp,
+                       yp, (int)p.rows, (int)p.cols, (int)rpw);
+  } else {
+    hipLaunchKernelGGL((spmv_subwave_kernel<LANES, false, BD>), dim3((unsigned)grid), dim3(block), 0, stream, v4,
+                       d4, p.row_ptr, xp, yp, (int)p.rows, (int)p.cols, (int)rpw);
+  }
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
+
+template <int BD>
+int launch_subwave_bd(const SpmvProblem& p, int lanes, int block, int64_t grid, int64_t rpw, bool lds_ok,
+                      int64_t lds_bytes, hipStream_t stream) {
+  if (lanes == 64) return launch_subwave_as<64, BD>(p, block, grid, rpw, lds_ok, lds_bytes, stream);
+  if (lanes == 32) return launch_subwave_as<32, BD>(p, block, grid, rpw, lds_ok, lds_bytes, stream);
+  return launch_subwave_as<16, BD>(p, block, grid, rpw, lds_ok, lds_bytes, stream);
+}
+
+int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
+  const Tuning& t = tuning();
+  const int cus = device_cu_count();
+  const int64_t lds_bytes = lds_bytes_for(p.cols);    // every entry is masked: the plain guards do
+  const bool lds_ok = lds_bytes <= kMaxLdsBytes;
+  const int64_t avg = p.rows > 0 ? p.pad_nnz / p.rows : 0;
   int lanes = kernel_lanes;
   if (lanes == 0) lanes = avg >= 384 ? 64 : (avg >= 192 ? 32 : 16);
   const int block = t.spmv_block ? (int)t.spmv_block : 256;
@@ -367,71 +502,60 @@ int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
     rpw = (std::max<int64_t>(rpw, groups) + groups - 1) / groups * groups;
   }
   const int64_t grid = (p.rows + rpw - 1) / rpw;
-  const size_t shm = lds_ok ? (size_t)lds_bytes : 0;
-#define MACKO_LAUNCH_SUB(L)                                                                          \
-  do {                                                                                               \
-    if (lds_ok) {                                                                                    \
-      auto kfn = spmv_subwave_kernel<L, true>;                                                       \
-      int st = set_lds_limit(kfn, lds_bytes);                                                        \
-      if (st != MACKO_OK) return st;                                                                 \
-      hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), shm, stream, v4, d4, p.row_ptr, xp, \
-                         yp, (int)p.rows, (int)p.cols, (int)rpw, (int)lds_bytes);                    \
-    } else {                                                                                         \
-      hipLaunchKernelGGL((spmv_subwave_kernel<L, false>), dim3((unsigned)grid), dim3(block), 0,      \
-                         stream, v4, d4, p.row_ptr, xp, yp, (int)p.rows, (int)p.cols, (int)rpw, 0);  \
-    }                                                                                                \
-  } while (0)
-  if (lanes == 64) MACKO_LAUNCH_SUB(64);
-  else if (lanes == 32) MACKO_LAUNCH_SUB(32);
-  else MACKO_LAUNCH_SUB(16);
-#undef MACKO_LAUNCH_SUB
+  switch (p.b_delta) {
+    case 1: return launch_subwave_bd<1>(p, lanes, block, grid, rpw, lds_ok, lds_bytes, stream);
+    case 2: return launch_subwave_bd<2>(p, lanes, block, grid, rpw, lds_ok, lds_bytes, stream);
+    case 4: return launch_subwave_bd<4>(p, lanes, block, grid, rpw, lds_ok, lds_bytes, stream);
+    case 8: return launch_subwave_bd<8>(p, lanes, block, grid, rpw, lds_ok, lds_bytes, stream);
+    default: return MACKO_E_UNSUPPORTED;
+  }
+}
+
+// The wave-per-row launch of a planned group whose matrices share the code width BD.
+template <int BD>
+int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, int nwr, const Plan& plan,
+                       int64_t max_lds, bool simple, bool ring4, hipStream_t stream) {
+  const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
+  if (nwr == 1) {
+    using K1 = void (*)(const uint4*, const uint32_t*, const uint32_t*, const uint16_t*, uint16_t*, int, int, int,
+                        int, int);
+    K1 kfn = simple ? (K1)spmv_wave_row_kernel<2, true, BD> : (K1)spmv_wave_row_kernel<2, false, BD>;
+    if (BD == 4 && ring4)
+      kfn = simple ? (K1)spmv_wave_row_kernel<4, true, 4> : (K1)spmv_wave_row_kernel<4, false, 4>;
+    int st = set_lds_limit(kfn, max_lds);
+    if (st != MACKO_OK) return st;
+    const SpmvMat& m = args.m[0];
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.values, m.deltas, m.row_ptr, m.x, m.y,
+                       m.rows, m.cols, m.q, m.r, head.inv_nwaves);
+  } else {
+    using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
+    KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD> : (KG)spmv_wave_row_kernel<2, false, BD>;
+    if (BD == 4 && ring4)
+      kfn = simple ? (KG)spmv_wave_row_kernel<4, true, 4> : (KG)spmv_wave_row_kernel<4, false, 4>;
+    int st = set_lds_limit(kfn, max_lds);
+    if (st != MACKO_OK) return st;
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
+                       head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
+                       head.inv_nwaves, args);
+  }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
 }
 
-}  // namespace
-
-int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
-  if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;
+// One grouped wave-per-row launch for the matrices wr[0..nwr) (same code width).
+int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hipStream_t stream) {
   const Tuning& t = tuning();
   const int cus = device_cu_count();
-  auto wants_wave_row = [&](const SpmvProblem& p) {
-    if (p.rows == 0 || p.pad_nnz == 0) return false;
-    if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
-    return p.pad_nnz / p.rows >= 384 && lds_bytes_for(p.cols) <= kMaxLdsBytes;
-  };
-
-  // matrices that do not go into the grouped wave-per-row launch
-  const SpmvProblem* wr[kMaxGroup];
   PlanInput in[kMaxGroup];
-  int nwr = 0;
   int64_t max_lds = 0, total_steps = 0;
-  for (int i = 0; i < n; ++i) {
-    const SpmvProblem& p = problems[i];
-    if (p.rows == 0) continue;
-    if (p.pad_nnz == 0) {                               // nothing stored: y = 0
-      hipLaunchKernelGGL(zero_y_kernel, dim3((unsigned)((p.rows + 255) / 256)), dim3(256), 0, stream,
-                         static_cast<uint16_t*>(p.y), (int)p.rows);
-      hipError_t e0 = hipGetLastError();
-      if (e0 != hipSuccess) return hip_fail(e0);
-      continue;
-    }
-    if (!wants_wave_row(p)) {                           // short rows or x larger than LDS: own launch
-      int st = launch_subwave(p, (int)t.spmv_lanes, stream);
-      if (st != MACKO_OK) return st;
-      continue;
-    }
-    const int64_t lds_bytes = lds_bytes_for(p.cols);
-    if (lds_bytes > kMaxLdsBytes) return MACKO_E_UNSUPPORTED;
-    wr[nwr] = &p;
-    in[nwr].rows = p.rows;
-    in[nwr].steps_per_row = std::max<int64_t>(1, (p.pad_nnz / p.rows + 511) / 512);
-    in[nwr].lds_bytes = lds_bytes;
-    total_steps += in[nwr].rows * in[nwr].steps_per_row;
-    max_lds = std::max(max_lds, lds_bytes);
-    ++nwr;
+  for (int i = 0; i < nwr; ++i) {
+    const SpmvProblem& p = *wr[i];
+    in[i].rows = p.rows;
+    in[i].steps_per_row = std::max<int64_t>(1, (p.pad_nnz / p.rows + 511) / 512);
+    in[i].lds_bytes = lds_bytes_for(p.cols, b_delta);
+    total_steps += in[i].rows * in[i].steps_per_row;
+    max_lds = std::max(max_lds, in[i].lds_bytes);
   }
-  if (nwr == 0) return MACKO_OK;
 
   Plan plan;
   bool planned = false;
@@ -495,31 +619,53 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   }
   // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
   // compute unit, and the smaller loop body matters when a wavefront runs it only
-  // a few times (instruction fetch is cold at every launch).
+  // a few times.
   const bool ring4 = t.spmv_ring == 4;
-  const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
-  if (nwr == 1) {
-    using K1 = void (*)(const uint4*, const uint32_t*, const uint32_t*, const uint16_t*, uint16_t*, int, int, int,
-                        int, int);
-    K1 kfn = ring4 ? (simple ? (K1)spmv_wave_row_kernel<4, true> : (K1)spmv_wave_row_kernel<4, false>)
-                   : (simple ? (K1)spmv_wave_row_kernel<2, true> : (K1)spmv_wave_row_kernel<2, false>);
-    int st = set_lds_limit(kfn, max_lds);
-    if (st != MACKO_OK) return st;
-    const SpmvMat& m = args.m[0];
-    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.values, m.deltas, m.row_ptr, m.x, m.y,
-                       m.rows, m.cols, m.q, m.r, head.inv_nwaves);
-  } else {
-    using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
-    KG kfn = ring4 ? (simple ? (KG)spmv_wave_row_kernel<4, true> : (KG)spmv_wave_row_kernel<4, false>)
-                   : (simple ? (KG)spmv_wave_row_kernel<2, true> : (KG)spmv_wave_row_kernel<2, false>);
-    int st = set_lds_limit(kfn, max_lds);
-    if (st != MACKO_OK) return st;
-    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
-                       head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
-                       head.inv_nwaves, args);
+  switch (b_delta) {
+    case 2: return launch_wave_row_bd<2>(args, head, nwr, plan, max_lds, simple, ring4, stream);
+    case 4: return launch_wave_row_bd<4>(args, head, nwr, plan, max_lds, simple, ring4, stream);
+    case 8: return launch_wave_row_bd<8>(args, head, nwr, plan, max_lds, simple, ring4, stream);
+    default: return MACKO_E_UNSUPPORTED;
   }
-  hipError_t e = hipGetLastError();
-  return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
+
+}  // namespace
+
+int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
+  if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;
+  const Tuning& t = tuning();
+  auto wants_wave_row = [&](const SpmvProblem& p) {
+    if (p.rows == 0 || p.pad_nnz == 0) return false;
+    if (p.b_delta == 1) return false;                   // 1-bit codes: the generic kernel only
+    if (lds_bytes_for(p.cols, p.b_delta) > kMaxLdsBytes) return false;
+    if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
+    return p.pad_nnz / p.rows >= 384;
+  };
+  // matrices that do not go into a grouped wave-per-row launch
+  for (int i = 0; i < n; ++i) {
+    const SpmvProblem& p = problems[i];
+    if (p.rows == 0) continue;
+    if (p.pad_nnz == 0) {                               // nothing stored: y = 0
+      hipLaunchKernelGGL(zero_y_kernel, dim3((unsigned)((p.rows + 255) / 256)), dim3(256), 0, stream,
+                         static_cast<uint16_t*>(p.y), (int)p.rows);
+      hipError_t e0 = hipGetLastError();
+      if (e0 != hipSuccess) return hip_fail(e0);
+    } else if (!wants_wave_row(p)) {                    // short rows or x larger than LDS: own launch
+      int st = launch_subwave(p, (int)t.spmv_lanes, stream);
+      if (st != MACKO_OK) return st;
+    }
+  }
+  // one grouped launch per code width
+  for (int bd : {4, 2, 8}) {
+    const SpmvProblem* wr[kMaxGroup];
+    int nwr = 0;
+    for (int i = 0; i < n; ++i)
+      if (problems[i].b_delta == bd && wants_wave_row(problems[i])) wr[nwr++] = &problems[i];
+    if (nwr == 0) continue;
+    int st = launch_wave_row_group(nwr, wr, bd, stream);
+    if (st != MACKO_OK) return st;
+  }
+  return MACKO_OK;
 }
 
 }  // namespace macko

@@ -48,11 +48,11 @@ def check_y(y_dev, W, x, what=""):
     return float(np.max(err / bound))
 
 
-def spmv_case(W, x, **knobs):
+def spmv_case(W, x, b_delta=4, **knobs):
     for k, v in knobs.items():
         M.set_tuning(k, v)
     try:
-        m = M.encode(W).to_device()
+        m = M.encode(W, b_delta).to_device()
         y = m.spmv(to_dev(x))
         torch.cuda.synchronize()
     finally:
@@ -263,6 +263,64 @@ def test_wrap_device_reuses_an_existing_encoding():
     torch.cuda.synchronize()
     check_y(y, W, x, "wrapped")
     assert torch.equal(y, m.spmv(to_dev(x)))
+
+
+# ------------------------------------------------------------------ other code widths
+
+WIDTH_CASES = {
+    "half_1200x3000": lambda: (wl.bernoulli(1200, 3000, 0.5, 0.02, 51, 1), wl.x_vector(3000, 51, 1)),
+    "dense_300x1031": lambda: (wl.bernoulli(300, 1031, 1.0, 0.02, 51, 2), wl.x_vector(1031, 51, 2)),
+    "sparse97_600x9000": lambda: (wl.bernoulli(600, 9000, 0.03, 1.0, 51, 3), wl.x_vector(9000, 51, 3)),
+    "ragged_301x777": lambda: (wl.bernoulli(301, 777, 0.7, 0.02, 51, 4), wl.x_vector(777, 51, 4)),
+    "c4_512x4096": lambda: (wl.config4(rows=512, cols=4096).W, wl.config4(rows=512, cols=4096).x),
+    "one_row_20000": lambda: (wl.bernoulli(1, 20000, 0.3, 0.02, 51, 5), wl.x_vector(20000, 51, 5)),
+}
+
+
+@pytest.mark.parametrize("variant", ["auto", "sub32", "wave_row", "wave_row_b64_r200"])
+@pytest.mark.parametrize("b_delta", [1, 2, 8])
+@pytest.mark.parametrize("case", list(WIDTH_CASES))
+def test_spmv_other_code_widths(case, b_delta, variant):
+    """1-, 2- and 8-bit codes: same product, same tolerance (1-bit codes always take the generic kernel)."""
+    W, x = WIDTH_CASES[case]()
+    y = spmv_case(W, x, b_delta, **VARIANTS[variant])
+    check_y(y, W, x, f"{case}/b{b_delta}/{variant}")
+
+
+@pytest.mark.parametrize("b_delta", [1, 2, 8])
+def test_other_code_widths_gpu_encoder_wrap_and_groups(b_delta):
+    W = wl.bernoulli(700, 2500, 0.35, 0.02, 52, b_delta)
+    W[13] = 0
+    x = wl.x_vector(2500, 52, 1)
+    enc = oracle.encode(W, b_delta)
+    g = M.encode_device(to_dev(W), b_delta=b_delta)
+    assert_same_encoding(g.fetch_device(), enc)
+    rep = g.get_report()
+    assert (rep.nnz, rep.pad_nnz, rep.alloc_nnz, rep.b_delta) == (enc.nnz, enc.pad_nnz, enc.alloc_nnz, b_delta)
+    check_y(g.spmv(to_dev(x)), W, x, f"device-encoded b{b_delta}")
+    # adopt the same device arrays through the wrap call
+    bufs = [torch.from_numpy(a.copy()).cuda() for a in g.fetch_device()]
+    w = M.wrap_device(700, 2500, enc.pad_nnz, *bufs, b_delta=b_delta)
+    assert torch.equal(w.spmv(to_dev(x)), g.spmv(to_dev(x)))
+    # a group that mixes code widths: one launch per width, same results
+    others = [M.encode(W, b).to_device() for b in (4, 2, 8)]
+    ys = M.spmv_group([g] + others, [to_dev(x)] * 4)
+    torch.cuda.synchronize()
+    for i, yi in enumerate(ys):
+        check_y(yi, W, x, f"mixed group member {i}")
+    # the batch product has no kernel for these widths
+    with pytest.raises(M.MackoError) as e:
+        g.spmm(torch.zeros(2, 2500, dtype=torch.float16, device="cuda"))
+    assert e.value.status == -3
+
+
+def test_code_widths_full_size_llama_shape():
+    """4096 x 11008 at 50 % (2-bit codes) and at 97 % (8-bit codes), in the launch shape bench.py times."""
+    for b_delta, density, stream in ((2, 0.5, 61), (8, 0.03, 62), (2, 0.75, 63)):
+        W = wl.bernoulli(4096, 11008, density, 0.02, 53, stream)
+        x = wl.x_vector(11008, 53, stream)
+        m = M.encode(W, b_delta).to_device()
+        check_y(m.spmv(to_dev(x)), W, x, f"b{b_delta} d{density}")
 
 
 # ------------------------------------------------------------------ grouped launches

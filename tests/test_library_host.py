@@ -25,7 +25,7 @@ def same_encoding(m, enc):
     assert np.array_equal(r, enc.row_ptr)
 
 
-def same_report(rep, enc, W):
+def same_report(rep, enc, W, b_delta=4):
     assert (rep.rows, rep.cols) == W.shape
     assert rep.nnz == enc.nnz and rep.pad_nnz == enc.pad_nnz and rep.alloc_nnz == enc.alloc_nnz
     assert rep.padding_entries == enc.padding_entries
@@ -35,15 +35,15 @@ def same_report(rep, enc, W):
     ent = np.diff(enc.row_ptr.astype(np.int64))
     assert rep.empty_rows == int((ent == 0).sum())
     assert rep.max_row_entries == (int(ent.max()) if ent.size else 0)
-    assert rep.b_val == 16 and rep.b_delta == 4
+    assert rep.b_val == 16 and rep.b_delta == b_delta
     if W.size:
         d = enc.nnz / W.size
         cf = oracle.closed_forms
         assert rep.density == pytest.approx(d, abs=1e-15)
         assert rep.effd == pytest.approx(enc.effd, rel=1e-14)
-        assert rep.effd_best == pytest.approx(cf.effd_macko_best(d), rel=1e-13)
-        assert rep.effd_worst == pytest.approx(cf.effd_macko_worst(d), rel=1e-13)
-        assert rep.effd_expected == pytest.approx(cf.effd_macko_expected(d), rel=1e-12)
+        assert rep.effd_best == pytest.approx(cf.effd_macko_best(d, b_delta=b_delta), rel=1e-13)
+        assert rep.effd_worst == pytest.approx(cf.effd_macko_worst(d, b_delta=b_delta), rel=1e-13)
+        assert rep.effd_expected == pytest.approx(cf.effd_macko_expected(d, b_delta=b_delta), rel=1e-12)
 
 
 def test_library_exports_every_declared_symbol():
@@ -76,6 +76,49 @@ def test_host_encoder_is_bit_exact_against_the_oracle(name, make):
     same_report(rep_holder.report, enc, W)
     assert np.array_equal(rep_holder.decode(), oracle.decode(enc))
     rep_holder.destroy()
+
+
+@pytest.mark.parametrize("b_delta", [1, 2, 8])
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+def test_host_encoder_other_code_widths_bit_exact_against_the_oracle(name, make, b_delta):
+    """macko_encode_ex: 1-, 2- and 8-bit codes (Section 4.1 allows exactly 1, 2, 4, 8)."""
+    W = make()
+    enc = oracle.encode(W, b_delta)
+    m = M.encode(W, b_delta)
+    same_encoding(m, enc)
+    same_report(m.report, enc, W, b_delta)
+    assert np.array_equal(m.decode(), oracle.decode(enc))
+    vb, db, rb = m.device_bytes()
+    assert (vb, db, rb) == (enc.values_bytes, enc.deltas_bytes, enc.rowptr_bytes)
+    m.destroy()
+
+
+def test_worked_example_of_section_4_1_through_the_library():
+    """The paper's row (values 1..4 at 1-based columns 2, 5, 12, 13) with 2-bit codes stores
+    values [1, 2, 0, 3, 4] with deltas [2, 3, 4, 3, 1]."""
+    one = np.float16([1, 2, 3, 4]).view(np.uint16)
+    W = np.zeros((1, 16), dtype=np.uint16)
+    W[0, [1, 4, 11, 12]] = one
+    m = M.encode(W, 2)
+    v, d, r = m.host_buffers()
+    assert r.tolist() == [0, 5]
+    assert v[:5].tolist() == [one[0], one[1], 0, one[2], one[3]]
+    codes = [(int(d[k // 4]) >> (2 * (k % 4))) & 3 for k in range(5)]
+    assert [c + 1 for c in codes] == [2, 3, 4, 3, 1]
+    assert m.report.padding_entries == 1 and m.report.alloc_nnz == 64
+
+
+def test_code_width_argument_is_validated():
+    lib = M.load_library()
+    W = np.ones((2, 2), dtype=np.uint16)
+    h = ctypes.c_void_p(5)
+    for bad in (0, 3, 5, 16, -4):
+        assert lib.macko_encode_ex(W.ctypes.data, 2, 2, 2, bad, ctypes.byref(h), None) == -1
+        assert h.value is None
+        assert lib.macko_wrap_device_ex(2, 2, 4, bad, 256, 256, 256, ctypes.byref(h)) == -1
+    # the batch product decodes 4-bit codes only; refused before any device work
+    m = M.encode(W, 2)
+    assert lib.macko_spmm(m._h, 2, 16, 2, 16, 2, None) == -5    # not bound comes first
 
 
 def test_special_bit_patterns_and_strided_input():
