@@ -494,7 +494,7 @@ int macko_set_tuning(const char* name, int64_t value) {
   const std::string n(name);
   if (n == "spmv_kernel" && value > 2) return MACKO_E_INVALID_ARG;
   if (n == "gemv_ring" && value != 0 && value != 2 && value != 4 && value != 8) return MACKO_E_INVALID_ARG;
-  if (n == "spmv_ring" && value != 0 && value != 2 && value != 4) return MACKO_E_INVALID_ARG;
+  if (n == "spmv_ring" && value != 0 && (value < 2 || value > 4)) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_resident" || n == "gemv_resident") && value > 2) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_wgs_per_cu" || n == "gemv_wgs_per_cu") && value > 4) return MACKO_E_INVALID_ARG;
   if (n == "spmv_lanes" && value != 0 && value != 16 && value != 32 && value != 64) return MACKO_E_INVALID_ARG;

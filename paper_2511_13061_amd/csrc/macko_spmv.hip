@@ -514,14 +514,16 @@ int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
 // The wave-per-row launch of a planned group whose matrices share the code width BD.
 template <int BD>
 int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, int nwr, const Plan& plan,
-                       int64_t max_lds, bool simple, bool ring4, hipStream_t stream) {
+                       int64_t max_lds, bool simple, int ring, hipStream_t stream) {
   const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
   if (nwr == 1) {
     using K1 = void (*)(const uint4*, const uint32_t*, const uint32_t*, const uint16_t*, uint16_t*, int, int, int,
                         int, int);
     K1 kfn = simple ? (K1)spmv_wave_row_kernel<2, true, BD> : (K1)spmv_wave_row_kernel<2, false, BD>;
-    if (BD == 4 && ring4)
+    if (BD == 4 && ring == 4)
       kfn = simple ? (K1)spmv_wave_row_kernel<4, true, 4> : (K1)spmv_wave_row_kernel<4, false, 4>;
+    if (BD == 4 && ring == 3)
+      kfn = simple ? (K1)spmv_wave_row_kernel<3, true, 4> : (K1)spmv_wave_row_kernel<3, false, 4>;
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     const SpmvMat& m = args.m[0];
@@ -530,8 +532,10 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
   } else {
     using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
     KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD> : (KG)spmv_wave_row_kernel<2, false, BD>;
-    if (BD == 4 && ring4)
+    if (BD == 4 && ring == 4)
       kfn = simple ? (KG)spmv_wave_row_kernel<4, true, 4> : (KG)spmv_wave_row_kernel<4, false, 4>;
+    if (BD == 4 && ring == 3)
+      kfn = simple ? (KG)spmv_wave_row_kernel<3, true, 4> : (KG)spmv_wave_row_kernel<3, false, 4>;
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
@@ -620,11 +624,11 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
   // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
   // compute unit, and the smaller loop body matters when a wavefront runs it only
   // a few times.
-  const bool ring4 = t.spmv_ring == 4;
+  const int ring = (int)t.spmv_ring;
   switch (b_delta) {
-    case 2: return launch_wave_row_bd<2>(args, head, nwr, plan, max_lds, simple, ring4, stream);
-    case 4: return launch_wave_row_bd<4>(args, head, nwr, plan, max_lds, simple, ring4, stream);
-    case 8: return launch_wave_row_bd<8>(args, head, nwr, plan, max_lds, simple, ring4, stream);
+    case 2: return launch_wave_row_bd<2>(args, head, nwr, plan, max_lds, simple, ring, stream);
+    case 4: return launch_wave_row_bd<4>(args, head, nwr, plan, max_lds, simple, ring, stream);
+    case 8: return launch_wave_row_bd<8>(args, head, nwr, plan, max_lds, simple, ring, stream);
     default: return MACKO_E_UNSUPPORTED;
   }
 }

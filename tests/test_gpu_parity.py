@@ -522,7 +522,23 @@ def test_dense_gemv_with_leading_dimension_and_on_sparse_input():
 
 # ------------------------------------------------------------------ full-size configurations
 
+def grouped_like_the_bench(handles, xs, singles):
+    """The launches bench.py times: {q,k,v}, {o}, {gate,up}, {down}, and all seven at once.  Every product
+    must come out exactly as from its own launch (the arithmetic per row does not depend on the launch shape)."""
+    sq, gu, dn = handles
+    xq, xg, xd = xs
+    yq, yg, yd = singles
+    for group, xv, want in (([sq] * 3, [xq] * 3, [yq] * 3), ([sq], [xq], [yq]), ([gu] * 2, [xg] * 2, [yg] * 2),
+                            ([dn], [xd], [yd]),
+                            ([sq] * 4 + [gu] * 2 + [dn], [xq] * 4 + [xg] * 2 + [xd], [yq] * 4 + [yg] * 2 + [yd])):
+        got = M.spmv_group(group, xv)
+        torch.cuda.synchronize()
+        for g, w in zip(got, want):
+            assert torch.equal(g, w)
+
+
 def test_config2_llama2_7b_shapes_full_size():
+    handles, xs, singles = [], [], []
     for case in wl.config2():
         enc = oracle.encode(case.W)
         m = M.encode(case.W)
@@ -531,11 +547,13 @@ def test_config2_llama2_7b_shapes_full_size():
         y = m.spmv(to_dev(case.x))
         torch.cuda.synchronize()
         check_y(y, case.W, case.x, case.name)
+        handles.append(m); xs.append(to_dev(case.x)); singles.append(y)
         yd = M.dense_gemv(to_dev(case.W), to_dev(case.x))
         torch.cuda.synchronize()
         check_y(yd, case.W, case.x, case.name + " dense")
         g = M.encode_device(to_dev(case.W))
         assert_same_encoding(g.fetch_device(), enc)
+    grouped_like_the_bench(handles, xs, singles)
 
 
 @pytest.mark.parametrize("sparsity", [0, 50, 90])
@@ -568,8 +586,11 @@ def test_config4_adversarial_full_size():
 
 
 def test_config5_llama2_13b_layer_shapes_full_size():
+    handles, xs, singles = [], [], []
     for case in wl.config5_layer():
         m = M.encode(case.W).to_device()
         y = m.spmv(to_dev(case.x))
         torch.cuda.synchronize()
         check_y(y, case.W, case.x, case.name)
+        handles.append(m); xs.append(to_dev(case.x)); singles.append(y)
+    grouped_like_the_bench(handles, xs, singles)
