@@ -119,6 +119,18 @@ def cpu_baseline(oracle, cases, min_cpu_seconds=10.0):
     """The oracle's SpMV (fp64, from the format buffers) timed on the host."""
     encs = [(oracle.encode(c.W), c.x) for c in cases]
     threads = oracle.max_threads()
+    # one thread, smallest matrix only (a bounded sample: about a second)
+    e0, x0 = min(encs, key=lambda ex: ex[0].total_bytes)
+    oracle.set_threads(1)
+    oracle.spmv(e0, x0)
+    t1 = float("inf")
+    for _ in range(3):
+        ta = time.perf_counter()
+        oracle.spmv(e0, x0)
+        t1 = min(t1, time.perf_counter() - ta)
+    oracle.set_threads(threads)
+    one_thread = {"GBps": round((e0.total_bytes + 2 * e0.cols + 2 * e0.rows) / t1 / 1e9, 3),
+                  "us": round(t1 * 1e6, 1), "matrix": f"{e0.rows}x{e0.cols}"}
     nbytes = sum(e.total_bytes + 2 * e.cols + 2 * e.rows for e, _ in encs)
     for e, x in encs:          # warm-up
         oracle.spmv(e, x)
@@ -137,6 +149,7 @@ def cpu_baseline(oracle, cases, min_cpu_seconds=10.0):
         "sample": f"one pass over the {len(encs)} distinct layer matrices "
                   f"({nbytes / 1e6:.1f} MB of format+x+y), best of {passes} passes, OpenMP over rows",
         "us_per_pass": best * 1e6,
+        "one_thread": one_thread,
     }
 
 
@@ -312,8 +325,12 @@ def main():
         so, do = sparse_ops[tag], dense_ops[tag]
         ts = time_single_op(torch, so, stream_ptr, max(10, args.warmup // 2), n_single)
         td = time_single_op(torch, do, stream_ptr, max(10, args.warmup // 2), n_single)
+        # the same launch on ONE copy over and over: the matrix stays in the 256 MB last-level cache
+        tsw = time_region(torch, lambda i: so.launch(0, stream_ptr), 10, n_single) / n_single
+        tdw = time_region(torch, lambda i: do.launch(0, stream_ptr), 10, n_single) / n_single
         per_shape[f"{so.rows}x{so.cols}"] = {
             "macko_us": round(ts * 1e6, 2), "dense_us": round(td * 1e6, 2),
+            "warm_cache_macko_us": round(tsw * 1e6, 2), "warm_cache_dense_us": round(tdw * 1e6, 2),
             "macko_GBps": round(so.bytes / ts / 1e9, 1), "dense_GBps": round(do.bytes / td / 1e9, 1),
             "speedup_vs_dense": round(td / ts, 3),
             "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
