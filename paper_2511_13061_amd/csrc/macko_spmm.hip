@@ -242,6 +242,7 @@ int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y,
 // (and matrices with short rows) go through the matrix-vector path.
 int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64_t ldy, int batch,
                 hipStream_t stream) {
+  if (p.pad_nnz > (int64_t{1} << 32) - 4096) return MACKO_E_UNSUPPORTED;   // 32-bit entry indices in the kernel
   const uint16_t* Xp = static_cast<const uint16_t*>(X);
   uint16_t* Yp = static_cast<uint16_t*>(Y);
   if (p.rows == 0 || batch == 0) return MACKO_OK;

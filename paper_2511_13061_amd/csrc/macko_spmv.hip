@@ -202,7 +202,9 @@ struct LaneCodes<2> : LaneCodesBytes<2> {
 template <>
 struct LaneCodes<8> {
   uint32_t w0, w1;      // codes of entries 0..3 and 4..7, one per byte
-  uint32_t X[4];        // halves of X[i]: doubled position after entry 2i and after entry 2i+1
+  // halves of Xi: doubled position after entry 2i and after entry 2i+1 (four named
+  // registers: an array indexed by a run-time value would be put in scratch memory)
+  uint32_t X0, X1, X2, X3;
   uint32_t tot;
   __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
     const uint2 v = reinterpret_cast<const uint2*>(deltas)[chunk];
@@ -214,36 +216,35 @@ struct LaneCodes<8> {
     w0 = c ? w0 : 0u;
     w1 = c ? w1 : 0u;
   }
+  // bytes (c_a, c_b) of w -> halves holding 2c + 2, then low half: the first entry alone, high half: the pair
+  static __device__ __forceinline__ uint32_t pair(uint32_t w, uint32_t sel) {
+    const uint32_t y = (__builtin_amdgcn_perm(0u, w, sel) << 1) + 0x00020002u;
+    return lshl_add<16>(y, y);
+  }
   __device__ __forceinline__ void decode() {
-    // bytes (c_2i, c_2i+1) -> halves, then 2c + 2 in every half
-    uint32_t Y[4];
-    Y[0] = __builtin_amdgcn_perm(0u, w0, 0x0C010C00u);
-    Y[1] = __builtin_amdgcn_perm(0u, w0, 0x0C030C02u);
-    Y[2] = __builtin_amdgcn_perm(0u, w1, 0x0C010C00u);
-    Y[3] = __builtin_amdgcn_perm(0u, w1, 0x0C030C02u);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      Y[i] = (Y[i] << 1) + 0x00020002u;
-      Y[i] = lshl_add<16>(Y[i], Y[i]);                 // low half: entry 2i alone, high half: the pair
-    }
-    const uint32_t r1 = Y[0] >> 16;
-    const uint32_t r2 = r1 + (Y[1] >> 16);
-    const uint32_t r3 = r2 + (Y[2] >> 16);
-    tot = r3 + (Y[3] >> 16);
-    X[0] = Y[0];
-    X[1] = Y[1] + (r1 | (r1 << 16));
-    X[2] = Y[2] + (r2 | (r2 << 16));
-    X[3] = Y[3] + (r3 | (r3 << 16));
+    const uint32_t Y0 = pair(w0, 0x0C010C00u), Y1 = pair(w0, 0x0C030C02u);
+    const uint32_t Y2 = pair(w1, 0x0C010C00u), Y3 = pair(w1, 0x0C030C02u);
+    const uint32_t r1 = Y0 >> 16;
+    const uint32_t r2 = r1 + (Y1 >> 16);
+    const uint32_t r3 = r2 + (Y2 >> 16);
+    tot = r3 + (Y3 >> 16);
+    X0 = Y0;
+    X1 = Y1 + (r1 | (r1 << 16));
+    X2 = Y2 + (r2 | (r2 << 16));
+    X3 = Y3 + (r3 | (r3 << 16));
   }
   __device__ __forceinline__ uint32_t total() const { return tot; }
   template <int K>
   __device__ __forceinline__ int offset() const {
-    return (int)((K & 1) ? (X[K >> 1] >> 16) : (X[K >> 1] & 0xFFFFu)) - 2;
+    const uint32_t x = (K >> 1) == 0 ? X0 : ((K >> 1) == 1 ? X1 : ((K >> 1) == 2 ? X2 : X3));
+    return (int)((K & 1) ? (x >> 16) : (x & 0xFFFFu)) - 2;
   }
   __device__ __forceinline__ uint32_t through(int k) const {
+    // lane 0's four words as scalars, then a scalar choice
+    const uint32_t s0 = __builtin_amdgcn_readfirstlane(X0), s1 = __builtin_amdgcn_readfirstlane(X1);
+    const uint32_t s2 = __builtin_amdgcn_readfirstlane(X2), s3 = __builtin_amdgcn_readfirstlane(X3);
     const int i = k >> 1;
-    const uint32_t sel = i == 0 ? X[0] : (i == 1 ? X[1] : (i == 2 ? X[2] : X[3]));
-    const uint32_t src = __builtin_amdgcn_readfirstlane(sel);
+    const uint32_t src = i == 0 ? s0 : (i == 1 ? s1 : (i == 2 ? s2 : s3));
     return (k & 1) ? (src >> 16) : (src & 0xFFFFu);
   }
 };
@@ -512,6 +513,10 @@ int set_lds_limit(K kernel, int64_t bytes) {
 constexpr int64_t kMaxLdsBytes = 160 * 1024 - 64;   // 160 KB per CU minus the static row counter
 // launches with at most this many wavefront steps per compute unit run as one resident round
 constexpr int64_t kResidentStepsPerCu = 768;
+// rows of at least this many stored entries on average take the wave-per-row kernel (a step
+// covers 512 entries; below about 40 % use of a step the sub-wave kernel wins: measured
+// crossover between 133 and 247 entries per row on 36864 x 12288 at 98-99 % sparsity)
+constexpr int64_t kWaveRowMinEntries = 192;
 // x copies of at least this many bytes make a matrix "wide" for the launch planner
 constexpr int64_t kWideLdsBytes = 36 * 1024;
 
@@ -555,7 +560,7 @@ int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
   const bool lds_ok = lds_bytes <= kMaxLdsBytes;
   const int64_t avg = p.rows > 0 ? p.pad_nnz / p.rows : 0;
   int lanes = kernel_lanes;
-  if (lanes == 0) lanes = avg >= 384 ? 64 : (avg >= 192 ? 32 : 16);
+  if (lanes == 0) lanes = avg >= 256 ? 32 : 16;        // 64 lanes per row measured slower at every length
   const int block = t.spmv_block ? (int)t.spmv_block : 256;
   const int groups = block / lanes;
   int64_t rpw = t.spmv_rows_per_wg;
@@ -718,12 +723,14 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
     if (p.b_delta == 1) return false;                   // 1-bit codes: the generic kernel only
     if (lds_bytes_for(p.cols, p.b_delta) > kMaxLdsBytes) return false;
     if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
-    return p.pad_nnz / p.rows >= 384;
+    return p.pad_nnz / p.rows >= kWaveRowMinEntries;
   };
   // matrices that do not go into a grouped wave-per-row launch
   for (int i = 0; i < n; ++i) {
     const SpmvProblem& p = problems[i];
     if (p.rows == 0) continue;
+    // the kernels index entries with 32 bits and look up to two steps past a row's end
+    if (p.pad_nnz > (int64_t{1} << 32) - 4096) return MACKO_E_UNSUPPORTED;
     if (p.pad_nnz == 0) {                               // nothing stored: y = 0
       hipLaunchKernelGGL(zero_y_kernel, dim3((unsigned)((p.rows + 255) / 256)), dim3(256), 0, stream,
                          static_cast<uint16_t*>(p.y), (int)p.rows);
