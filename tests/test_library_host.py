@@ -173,3 +173,25 @@ def test_padding_bound_reported_for_llama_like_rows():
     assert r.nnz == 64 * 2048 and r.density == 0.5
     assert r.effd_best <= r.effd <= r.effd_worst
     assert r.padding_entries <= 64 * 4096 * 0.5 / 16
+
+
+def test_kernels_use_no_scratch_memory(tmp_path):
+    """No kernel may spill registers or keep a run-time-indexed array in scratch memory: a scratch
+    store per step costs more HBM bandwidth than the format saves (this happened to the 8-bit decode)."""
+    import shutil
+    import subprocess
+    from paper_2511_13061_amd import build as B
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("no hipcc")
+    flags = [f for f in B.HIPCC_FLAGS if f not in ("-fPIC",)]
+    for src in (s for s in B.SOURCES if s.endswith(".hip")):
+        out = tmp_path / (src + ".s")
+        subprocess.check_call([hipcc, *flags, "-I", os.path.join(ROOT, "include"), "-I", B.CSRC, "-x", "hip",
+                               "--cuda-device-only", "-S", "-o", str(out), os.path.join(B.CSRC, src)],
+                              stderr=subprocess.DEVNULL)
+        text = out.read_text()
+        assert ".amdhsa_kernel" in text, src
+        assert not re.search(r"^\s*scratch_(load|store)", text, re.M), f"{src}: scratch memory access"
+        assert not re.search(r"\.private_segment_fixed_size:\s*[1-9]", text), f"{src}: private segment in use"
+        assert not re.search(r"\.(vgpr|sgpr)_spill_count:\s*[1-9]", text), f"{src}: register spills"
