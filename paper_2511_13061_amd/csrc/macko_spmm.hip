@@ -12,6 +12,7 @@
 // behind the columns play the same role as in the matrix-vector kernel.
 #include "macko_device.h"
 #include "macko_internal.h"
+#include "macko_plan.h"
 
 namespace macko {
 namespace {
@@ -84,20 +85,24 @@ template <int BT>
 __global__ void __launch_bounds__(1024)
 spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
                      const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ X, int64_t ldx,
-                     uint16_t* __restrict__ Y, int64_t ldy, int batch, int rows, int cols, int rows_per_wg) {
+                     uint16_t* __restrict__ Y, int64_t ldy, int batch, int rows, int cols, int q, int r_extra,
+                     int inv_nwaves) {
   constexpr int RING = 2;
   using XV = typename XVec<BT>::type;
   extern __shared__ __align__(16) unsigned char lds[];
-  const int row_begin = (int)blockIdx.x * rows_per_wg;
-  const int row_end = min(rows, row_begin + rows_per_wg);
+  // rows dealt out evenly: q per workgroup, one more for the first r_extra; the same over the wavefronts
+  const int wg = (int)blockIdx.x;
+  const int row_begin = wg * q + min(wg, r_extra);
+  const int wg_rows = q + (wg < r_extra ? 1 : 0);
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const unsigned char* xbase = lds + kFrontPad * BT;   // LDS address of column 0
   const uint32_t lane8 = 8u * lane;
-  const int per_wave = (row_end - row_begin + nwaves - 1) / nwaves;
-  const int blk = min(row_end, row_begin + wave * per_wave);
-  const int nb = min(row_end, blk + per_wave) - blk;   // at most 64: the host caps rows_per_wg
+  const int per_wave = (wg_rows * inv_nwaves) >> 16;     // wg_rows / nwaves (exact for wg_rows <= 1024)
+  const int extra = wg_rows - per_wave * nwaves;
+  const int blk = row_begin + wave * per_wave + min(wave, extra);
+  const int nb = per_wave + (wave < extra ? 1 : 0);      // at most 64: the host sees to that
 
   uint32_t chunk = 0;
   RowCursor ld, cp;
@@ -214,14 +219,25 @@ int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y,
               hipStream_t stream) {
   const int cus = device_cu_count();
   const int64_t lds = (int64_t)BT * lds_bytes_for(p.cols);
-  const int block = lds > 48 * 1024 ? 1024 : 512;
-  const int nwaves = block / 64;
   const int64_t avg = p.pad_nnz / p.rows;
-  const int64_t steps_per_row = std::max<int64_t>(1, (avg + 511) / 512);
-  const int64_t want = (16 + steps_per_row - 1) / steps_per_row;
-  const int64_t cap = std::max<int64_t>(1, p.rows / ((int64_t)cus * 16));
-  const int64_t rpw = std::min<int64_t>(std::min(want, cap) * nwaves, 64 * nwaves);
-  const int64_t grid = (p.rows + rpw - 1) / rpw;
+  PlanInput in{p.rows, std::max<int64_t>(1, (avg + 511) / 512), lds};
+  // The interleaved copy of X is BT times the size of x, so a workgroup is expensive to start:
+  // one resident round (a single 16-wavefront workgroup per compute unit once the copy passes
+  // 36 KB) unless the matrix is large, as for the matrix-vector kernel.
+  Plan plan;
+  bool planned = false;
+  if (in.rows * in.steps_per_row <= (int64_t)cus * 800 || lds >= 36 * 1024)
+    planned = plan_resident(plan, 1, &in, cus, 0, lds >= 36 * 1024 ? 1 : 0);
+  if (!planned) {
+    const int block = lds > 48 * 1024 ? 1024 : 512;
+    const int64_t want = (16 + in.steps_per_row - 1) / in.steps_per_row;
+    const int64_t cap = std::max<int64_t>(1, p.rows / ((int64_t)cus * 16));
+    const int64_t rpw = std::min(want, cap) * (block / 64);
+    plan_by_rows_per_wg(plan, 1, &in, block, &rpw);
+  }
+  const int block = plan.block;
+  const int64_t grid = plan.total_wgs;
+  if (grid >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
   auto kfn = spmm_wave_row_kernel<BT>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -230,7 +246,8 @@ int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y,
   }
   hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds, stream,
                      reinterpret_cast<const uint4*>(p.values), reinterpret_cast<const uint32_t*>(p.deltas),
-                     p.row_ptr, X, ldx, Y, ldy, batch, (int)p.rows, (int)p.cols, (int)rpw);
+                     p.row_ptr, X, ldx, Y, ldy, batch, (int)p.rows, (int)p.cols, plan.m[0].q, plan.m[0].r,
+                     65536 / (block / 64) + 1);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
 }
