@@ -328,9 +328,13 @@ def main():
         # the same launch on ONE copy over and over: the matrix stays in the 256 MB last-level cache
         tsw = time_region(torch, lambda i: so.launch(0, stream_ptr), 10, n_single) / n_single
         tdw = time_region(torch, lambda i: do.launch(0, stream_ptr), 10, n_single) / n_single
+        # context for the baseline: the vendor library's GEMV on the same dense matrices (torch.mv)
+        ncop = len(do.W)
+        tlib = time_region(torch, lambda i: torch.mv(do.W[i % ncop], do.x, out=do.y), 10, n_single) / n_single
         per_shape[f"{so.rows}x{so.cols}"] = {
             "macko_us": round(ts * 1e6, 2), "dense_us": round(td * 1e6, 2),
             "warm_cache_macko_us": round(tsw * 1e6, 2), "warm_cache_dense_us": round(tdw * 1e6, 2),
+            "library_gemv_us": round(tlib * 1e6, 2),
             "macko_GBps": round(so.bytes / ts / 1e9, 1), "dense_GBps": round(do.bytes / td / 1e9, 1),
             "speedup_vs_dense": round(td / ts, 3),
             "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
