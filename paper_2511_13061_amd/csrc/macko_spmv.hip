@@ -694,7 +694,15 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
   // Two steps of loads in flight per wavefront are enough at 16+ wavefronts per
   // compute unit, and the smaller loop body matters when a wavefront runs it only
   // a few times.
-  const int ring = (int)t.spmv_ring;
+  // Ring depth: two steps in flight per wavefront, except in a resident round of at most 16
+  // wavefronts per compute unit working on long rows (4096 x 11008: one row of 11 steps per
+  // wavefront), where two steps leave the memory system short of requests: four there (6 %).
+  int ring = (int)t.spmv_ring;
+  if (ring == 0 && planned && plan.total_wgs * nwaves <= (int64_t)cus * 16) {
+    int64_t min_steps = in[0].steps_per_row;
+    for (int i = 1; i < nwr; ++i) min_steps = std::min(min_steps, in[i].steps_per_row);
+    if (min_steps >= 8) ring = 4;
+  }
   // Rows claimed one at a time instead of fixed shares: in a resident round, when every
   // workgroup has at most 63 rows (the claim bookkeeping lives in one register) and at least
   // two per wavefront (with one row each there is nothing to rebalance).  Measured gain:
