@@ -512,7 +512,7 @@ int set_lds_limit(K kernel, int64_t bytes) {
 
 constexpr int64_t kMaxLdsBytes = 160 * 1024 - 64;   // 160 KB per CU minus the static row counter
 // launches with at most this many wavefront steps per compute unit run as one resident round
-constexpr int64_t kResidentStepsPerCu = 800;
+constexpr int64_t kResidentStepsPerCu = 768;
 // rows of at least this many stored entries on average take the wave-per-row kernel (a step
 // covers 512 entries; below about 40 % use of a step the sub-wave kernel wins: measured
 // crossover between 133 and 247 entries per row on 36864 x 12288 at 98-99 % sparsity)
