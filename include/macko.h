@@ -207,8 +207,6 @@ MACKO_API int macko_last_hip_error(void);
  *   "spmv_resident"     0 auto, 1 never, 2 always: launch exactly one resident round of
  *                       workgroups (a multiple of the compute-unit count) shaped to the row counts
  *   "spmv_wgs_per_cu"   workgroups per compute unit of such a round (1..4), 0 auto
- *   "spmv_dynamic"      0 auto, 1 never, 2 whenever possible: the wavefronts of a workgroup claim its
- *                       rows one by one instead of owning fixed shares (at most 63 rows per workgroup)
  *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8), "gemv_resident",
  *   "gemv_wgs_per_cu"   the same for the dense GEMV
  * Settings are process wide and not thread safe. */

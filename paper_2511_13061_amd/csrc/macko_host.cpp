@@ -480,7 +480,6 @@ static int64_t* tuning_slot(const char* name) {
   if (n == "spmv_ring") return &t.spmv_ring;
   if (n == "spmv_resident") return &t.spmv_resident;
   if (n == "spmv_wgs_per_cu") return &t.spmv_wgs_per_cu;
-  if (n == "spmv_dynamic") return &t.spmv_dynamic;
   if (n == "gemv_resident") return &t.gemv_resident;
   if (n == "gemv_wgs_per_cu") return &t.gemv_wgs_per_cu;
   if (n == "gemv_block") return &t.gemv_block;
@@ -496,7 +495,7 @@ int macko_set_tuning(const char* name, int64_t value) {
   if (n == "spmv_kernel" && value > 2) return MACKO_E_INVALID_ARG;
   if (n == "gemv_ring" && value != 0 && value != 2 && value != 4 && value != 8) return MACKO_E_INVALID_ARG;
   if (n == "spmv_ring" && value != 0 && (value < 2 || value > 4)) return MACKO_E_INVALID_ARG;
-  if ((n == "spmv_resident" || n == "gemv_resident" || n == "spmv_dynamic") && value > 2) return MACKO_E_INVALID_ARG;
+  if ((n == "spmv_resident" || n == "gemv_resident") && value > 2) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_wgs_per_cu" || n == "gemv_wgs_per_cu") && value > 4) return MACKO_E_INVALID_ARG;
   if (n == "spmv_lanes" && value != 0 && value != 16 && value != 32 && value != 64) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_block" || n == "gemv_block") && value != 0 && (value % 64 != 0 || value > 1024))

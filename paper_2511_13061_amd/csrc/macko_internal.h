@@ -22,7 +22,6 @@ struct Tuning {
   int64_t spmv_ring = 0;
   int64_t spmv_resident = 0;      // 0 auto, 1 never, 2 always one resident round of workgroups
   int64_t spmv_wgs_per_cu = 0;    // resident round: workgroups per compute unit (0 = planner's choice)
-  int64_t spmv_dynamic = 0;       // rows claimed from a counter: 0 auto, 1 never, 2 whenever possible
   int64_t gemv_block = 0;
   int64_t gemv_rows_per_wg = 0;
   int64_t gemv_ring = 0;

@@ -275,16 +275,7 @@ struct SpmvGroupHeader {
 
 // The work of one workgroup: workgroup number `wg` of the matrix given by the
 // pointers, whose rows are dealt out q (+1 for the first r workgroups) at a time.
-//
-// DYN: the wavefronts of a workgroup do not own fixed shares of its rows but
-// take the next unclaimed row from a counter in LDS whenever they finish one.
-// The compute unit serves its wavefronts unevenly (in a resident launch the
-// first wavefront of a workgroup can finish in half the time of the last), and
-// with fixed shares the launch lasts as long as the slowest share; with claims
-// the wavefronts end within one row of each other.  Needs at most 63 rows per
-// workgroup (every wavefront holds all the workgroup's row pointers, lane i row
-// i's, and the order of its claims in another register).
-template <int RING, bool SIMPLE, int BD, bool DYN>
+template <int RING, bool SIMPLE, int BD>
 __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ values,
                                                    const uint32_t* __restrict__ deltas,
                                                    const uint32_t* __restrict__ row_ptr,
@@ -292,7 +283,6 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
                                                    const int rows, const int cols, const int q, const int r,
                                                    const int wg, const int inv_nwaves) {
   extern __shared__ __align__(16) unsigned char lds[];
-  __shared__ uint32_t next_row;                        // DYN: first unclaimed row of the workgroup
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
   const int row_begin = wg * q + min(wg, r);
   const int wg_rows = q + (wg < r ? 1 : 0);
@@ -307,68 +297,21 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
   const int wrow_end = wrow_begin + per_wave + (wave < extra ? 1 : 0);
 
   uint32_t chunk = 0;      // 8-entry chunk index this lane loads next (chunk 0 exists: pad_nnz > 0)
-  // the rows this wavefront can work on: its own share, or (DYN) all of the workgroup's
-  const int blk = DYN ? row_begin : wrow_begin;
-  const int nb = DYN ? wg_rows : wrow_end - wrow_begin;   // at most 64: the host sees to that
+  const int blk = wrow_begin;
+  const int nb = wrow_end - wrow_begin;                // at most 64: the host sees to that
   uint32_t rp_lo = 0, rp_hi = 0;
   RowCursor ld, cp;                                    // load side, compute side
   LaneCodes<BD> wq[RING];
   uint4 vq[RING];
-  // DYN: lane k of `claims` holds the k-th row this wavefront claimed (nb = none left);
-  // the load side appends, the compute side follows behind; `mine` marks the rows to store
-  uint32_t claims = 0;
-  int n_claimed = 0, n_consumed = 0;
-  uint64_t mine = 0;
-
-  // move a cursor to its next non-empty row
-  auto ld_next = [&]() {
-    if (!DYN) {
-      ++ld.i;
-      seek_nonempty(ld, nb, rp_lo, rp_hi);
-      return;
-    }
-    ld.start = ld.end = 0;
-    while (true) {
-      uint32_t ticket = 0;
-      if (lane == 0) ticket = atomicAdd(&next_row, 1u);
-      ld.i = min((int)__builtin_amdgcn_readfirstlane(ticket), nb);
-      claims = lane == n_claimed ? (uint32_t)ld.i : claims;
-      ++n_claimed;
-      if (ld.i >= nb) break;
-      ld.start = (uint32_t)__builtin_amdgcn_readlane((int)rp_lo, ld.i);
-      ld.end = (uint32_t)__builtin_amdgcn_readlane((int)rp_hi, ld.i);
-      if (ld.end > ld.start) break;
-    }
-    ld.a0 = ld.start & ~7u;
-    ld.nsteps = (int)((ld.end - ld.a0 + 511u) >> 9);
-    ld.step = 0;
-  };
-  auto cp_next = [&]() {
-    if (!DYN) {
-      ++cp.i;
-      seek_nonempty(cp, nb, rp_lo, rp_hi);
-      return;
-    }
-    cp.start = cp.end = 0;
-    while (true) {
-      cp.i = __builtin_amdgcn_readlane((int)claims, n_consumed);
-      ++n_consumed;
-      if (cp.i >= nb) break;
-      mine |= uint64_t{1} << cp.i;                     // empty rows too: their result is the 0 in yv
-      cp.start = (uint32_t)__builtin_amdgcn_readlane((int)rp_lo, cp.i);
-      cp.end = (uint32_t)__builtin_amdgcn_readlane((int)rp_hi, cp.i);
-      if (cp.end > cp.start) break;
-    }
-    cp.a0 = cp.start & ~7u;
-    cp.nsteps = (int)((cp.end - cp.a0 + 511u) >> 9);
-    cp.step = 0;
-  };
 
   auto issue = [&](int j) {
     if (ld.i < nb) {
       const uint32_t e0 = ld.a0 + 512u * ld.step + lane8;
       chunk = min(e0, ld.end - 1u) >> 3;
-      if (++ld.step == ld.nsteps) ld_next();
+      if (++ld.step == ld.nsteps) {
+        ++ld.i;
+        seek_nonempty(ld, nb, rp_lo, rp_hi);
+      }
     }                  // else a padding item: every lane re-reads its previous chunk (a line it has just
                        // used; one fixed address would make every wavefront queue at the same L2 channel)
     wq[j].load(deltas, chunk);
@@ -380,14 +323,9 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
     rp_hi = row_ptr[r + 1];
   };
   auto prime_ring = [&]() {
-    if (DYN) {
-      ld_next();
-      cp_next();                                       // follows the same claims
-    } else {
-      ld.i = 0;
-      seek_nonempty(ld, nb, rp_lo, rp_hi);
-      cp = ld;
-    }
+    ld.i = 0;
+    seek_nonempty(ld, nb, rp_lo, rp_hi);
+    cp = ld;
 #pragma unroll
     for (int j = 0; j < RING; ++j) issue(j);
   };
@@ -396,10 +334,8 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
   // are in registers the first streaming loads go out, and only then is x
   // written to LDS, so the stream is already in flight behind the barrier.
   XStage xst;
-  if (DYN && threadIdx.x == 0) next_row = 0;
   fetch_row_ptrs();
   stage_x_begin(xst, x, cols);
-  if (DYN) __syncthreads();                            // the counter is set; the loads above are in flight
   prime_ring();
   stage_x_finish<SIMPLE>(lds, xst, x, cols, front_pad_for(BD), back_pad_for(BD));  // ends with a barrier
 
@@ -455,16 +391,17 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
           const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), 63);
           yv = lane == cp.i ? __builtin_bit_cast(float, tbits) : yv;
           acc = 0.0f;
-          cp_next();
+          ++cp.i;
+          seek_nonempty(cp, nb, rp_lo, rp_hi);
         }
       }
     }
-    if (DYN ? ((mine >> lane) & 1) != 0 : lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
+    if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
   }
 }
 
 // Grouped launch (matrices of one code width): the workgroup first finds its matrix.
-template <int RING, bool SIMPLE, int BD, bool DYN>
+template <int RING, bool SIMPLE, int BD>
 __global__ void __launch_bounds__(1024)
 spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4, const int wb5, const int wb6,
                      const int wb7, const int inv_nwaves, const SpmvGroupArgs g) {
@@ -477,20 +414,20 @@ spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4,
     mi = in ? i : mi;
     wg0 = in ? wbs[i] : wg0;
   }
-  spmv_wave_row_body<RING, SIMPLE, BD, DYN>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
+  spmv_wave_row_body<RING, SIMPLE, BD>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
                                        g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
                                        inv_nwaves);
 }
 
 // One matrix: everything the workgroup needs is a scalar argument (15 registers),
 // so a starting wavefront goes straight to its row pointers without any argument load.
-template <int RING, bool SIMPLE, int BD, bool DYN>
+template <int RING, bool SIMPLE, int BD>
 __global__ void __launch_bounds__(1024)
 spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
                      const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
                      uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
                      const int inv_nwaves) {
-  spmv_wave_row_body<RING, SIMPLE, BD, DYN>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
+  spmv_wave_row_body<RING, SIMPLE, BD>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
                                        inv_nwaves);
 }
 
@@ -582,17 +519,16 @@ int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
 // The wave-per-row launch of a planned group whose matrices share the code width BD.
 template <int BD>
 int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, int nwr, const Plan& plan,
-                       int64_t max_lds, bool simple, int ring, bool dyn, hipStream_t stream) {
+                       int64_t max_lds, bool simple, int ring, hipStream_t stream) {
   const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
   if (nwr == 1) {
     using K1 = void (*)(const uint4*, const uint32_t*, const uint32_t*, const uint16_t*, uint16_t*, int, int, int,
                         int, int);
-    K1 kfn = simple ? (K1)spmv_wave_row_kernel<2, true, BD, false> : (K1)spmv_wave_row_kernel<2, false, BD, false>;
-    if (dyn) kfn = simple ? (K1)spmv_wave_row_kernel<2, true, BD, true> : (K1)spmv_wave_row_kernel<2, false, BD, true>;
+    K1 kfn = simple ? (K1)spmv_wave_row_kernel<2, true, BD> : (K1)spmv_wave_row_kernel<2, false, BD>;
     if (BD == 4 && ring == 4)
-      kfn = simple ? (K1)spmv_wave_row_kernel<4, true, 4, false> : (K1)spmv_wave_row_kernel<4, false, 4, false>;
+      kfn = simple ? (K1)spmv_wave_row_kernel<4, true, 4> : (K1)spmv_wave_row_kernel<4, false, 4>;
     if (BD == 4 && ring == 3)
-      kfn = simple ? (K1)spmv_wave_row_kernel<3, true, 4, false> : (K1)spmv_wave_row_kernel<3, false, 4, false>;
+      kfn = simple ? (K1)spmv_wave_row_kernel<3, true, 4> : (K1)spmv_wave_row_kernel<3, false, 4>;
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     const SpmvMat& m = args.m[0];
@@ -600,12 +536,11 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
                        m.rows, m.cols, m.q, m.r, head.inv_nwaves);
   } else {
     using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
-    KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD, false> : (KG)spmv_wave_row_kernel<2, false, BD, false>;
-    if (dyn) kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD, true> : (KG)spmv_wave_row_kernel<2, false, BD, true>;
+    KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD> : (KG)spmv_wave_row_kernel<2, false, BD>;
     if (BD == 4 && ring == 4)
-      kfn = simple ? (KG)spmv_wave_row_kernel<4, true, 4, false> : (KG)spmv_wave_row_kernel<4, false, 4, false>;
+      kfn = simple ? (KG)spmv_wave_row_kernel<4, true, 4> : (KG)spmv_wave_row_kernel<4, false, 4>;
     if (BD == 4 && ring == 3)
-      kfn = simple ? (KG)spmv_wave_row_kernel<3, true, 4, false> : (KG)spmv_wave_row_kernel<3, false, 4, false>;
+      kfn = simple ? (KG)spmv_wave_row_kernel<3, true, 4> : (KG)spmv_wave_row_kernel<3, false, 4>;
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
@@ -703,20 +638,10 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
     for (int i = 1; i < nwr; ++i) min_steps = std::min(min_steps, in[i].steps_per_row);
     if (min_steps >= 8) ring = 4;
   }
-  // Rows claimed one at a time instead of fixed shares: in a resident round, when every
-  // workgroup has at most 63 rows (the claim bookkeeping lives in one register) and at least
-  // two per wavefront (with one row each there is nothing to rebalance).  Measured gain:
-  // 1-2 % on the decoder-layer launches; with many small workgroups the dispatcher already
-  // balances the load and the claims only cost.  Only the default ring depth has the variant.
-  bool dyn = (ring == 0 || ring == 2) && t.spmv_dynamic != 1 && (planned || t.spmv_dynamic == 2);
-  for (int i = 0; i < nwr; ++i) {
-    const int wg_rows = plan.m[i].q + (plan.m[i].r ? 1 : 0);
-    dyn = dyn && wg_rows <= 63 && (t.spmv_dynamic == 2 || plan.m[i].q >= 2 * nwaves);
-  }
   switch (b_delta) {
-    case 2: return launch_wave_row_bd<2>(args, head, nwr, plan, max_lds, simple, ring, dyn, stream);
-    case 4: return launch_wave_row_bd<4>(args, head, nwr, plan, max_lds, simple, ring, dyn, stream);
-    case 8: return launch_wave_row_bd<8>(args, head, nwr, plan, max_lds, simple, ring, dyn, stream);
+    case 2: return launch_wave_row_bd<2>(args, head, nwr, plan, max_lds, simple, ring, stream);
+    case 4: return launch_wave_row_bd<4>(args, head, nwr, plan, max_lds, simple, ring, stream);
+    case 8: return launch_wave_row_bd<8>(args, head, nwr, plan, max_lds, simple, ring, stream);
     default: return MACKO_E_UNSUPPORTED;
   }
 }

@@ -25,7 +25,7 @@ def _need_gpu_and_library():
     M.load_library()          # raises if libmacko.so is missing: no fallback
     yield
     for knob in ("spmv_kernel", "spmv_lanes", "spmv_block", "spmv_rows_per_wg", "spmv_ring", "spmv_resident",
-                 "spmv_wgs_per_cu", "spmv_dynamic", "gemv_block", "gemv_rows_per_wg", "gemv_ring", "gemv_resident",
+                 "spmv_wgs_per_cu", "gemv_block", "gemv_rows_per_wg", "gemv_ring", "gemv_resident",
                  "gemv_wgs_per_cu"):
         M.set_tuning(knob, 0)
 
@@ -91,8 +91,8 @@ VARIANTS = {
     "wave_row_b256_r5": {"spmv_kernel": 2, "spmv_block": 256, "spmv_rows_per_wg": 5},
     "wave_row_b1024_r700": {"spmv_kernel": 2, "spmv_block": 1024, "spmv_rows_per_wg": 700},
     "wave_row_b64_r200": {"spmv_kernel": 2, "spmv_block": 64, "spmv_rows_per_wg": 200},
-    "wave_row_dyn_b256_r37": {"spmv_kernel": 2, "spmv_block": 256, "spmv_rows_per_wg": 37, "spmv_dynamic": 2},
-    "wave_row_dyn_b128_r63": {"spmv_kernel": 2, "spmv_block": 128, "spmv_rows_per_wg": 63, "spmv_dynamic": 2},
+    "wave_row_b256_r37": {"spmv_kernel": 2, "spmv_block": 256, "spmv_rows_per_wg": 37},
+    "wave_row_b128_r63": {"spmv_kernel": 2, "spmv_block": 128, "spmv_rows_per_wg": 63},
 }
 
 
@@ -117,7 +117,7 @@ def test_spmv_empty_rows_mixed_with_full_rows_and_row_boundaries_inside_chunks()
         cols = rng.choice(C, size=(r - 39) % 10 + 1, replace=False)
         W[r, cols] = wl.normal_f16(cols.size, 1.0, 11, r, nonzero=True)
     x = wl.x_vector(C, 11, 1)
-    for variant in ("auto", "wave_row", "sub16", "wave_row_b64_r200", "wave_row_dyn_b256_r37", "wave_row_dyn_b128_r63"):
+    for variant in ("auto", "wave_row", "sub16", "wave_row_b64_r200", "wave_row_b256_r37", "wave_row_b128_r63"):
         y = spmv_case(W, x, **VARIANTS[variant])
         check_y(y, W, x, variant)
         assert (y[10:30] == 0).all() and (y[395:] == 0).all()
@@ -132,13 +132,8 @@ RESIDENT_VARIANTS = {
     "k4": {"spmv_resident": 2, "spmv_wgs_per_cu": 4},
     "k1_b1024": {"spmv_resident": 2, "spmv_wgs_per_cu": 1, "spmv_block": 1024},
     "k2_b704": {"spmv_resident": 2, "spmv_wgs_per_cu": 2, "spmv_block": 704},
-    # rows claimed one by one by the wavefronts of a workgroup instead of fixed shares
-    "dyn_k1_b256": {"spmv_resident": 2, "spmv_wgs_per_cu": 1, "spmv_block": 256, "spmv_dynamic": 2},
-    "dyn_k2": {"spmv_resident": 2, "spmv_wgs_per_cu": 2, "spmv_dynamic": 2},
-    "dyn_k1_b1024": {"spmv_resident": 2, "spmv_wgs_per_cu": 1, "spmv_block": 1024, "spmv_dynamic": 2},
-    "dyn_many_wgs_r40_b256": {"spmv_resident": 1, "spmv_rows_per_wg": 40, "spmv_block": 256, "spmv_dynamic": 2},
-    "dyn_many_wgs_r63_b64": {"spmv_resident": 1, "spmv_rows_per_wg": 63, "spmv_block": 64, "spmv_dynamic": 2},
-    "dyn_off": {"spmv_resident": 2, "spmv_dynamic": 1},
+    "many_wgs_r40_b256": {"spmv_resident": 1, "spmv_rows_per_wg": 40, "spmv_block": 256},
+    "many_wgs_r63_b64": {"spmv_resident": 1, "spmv_rows_per_wg": 63, "spmv_block": 64},
 }
 
 
@@ -286,7 +281,7 @@ WIDTH_CASES = {
 }
 
 
-@pytest.mark.parametrize("variant", ["auto", "sub32", "wave_row", "wave_row_b64_r200", "wave_row_dyn_b256_r37"])
+@pytest.mark.parametrize("variant", ["auto", "sub32", "wave_row", "wave_row_b64_r200", "wave_row_b256_r37"])
 @pytest.mark.parametrize("b_delta", [1, 2, 8])
 @pytest.mark.parametrize("case", list(WIDTH_CASES))
 def test_spmv_other_code_widths(case, b_delta, variant):
