@@ -165,6 +165,8 @@ def main():
     ap.add_argument("--shapes", action="store_true",
                     help="also time every shape of the paper's Appendix D at 50 %% sparsity")
     ap.add_argument("--spmm", action="store_true", help="also time the small-batch product macko_spmm")
+    ap.add_argument("--adversarial", action="store_true",
+                    help="also time the two 8192x8192 padding stress matrices (configs[3])")
     ap.add_argument("--widths", action="store_true",
                     help="also time 2-, 4- and 8-bit codes on the 36864x12288 matrix (Appendix C of the paper)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -411,6 +413,28 @@ def main():
             del so, case
             torch.cuda.empty_cache()
         extra["sweep_36864x12288"] = sweep
+
+    # ---- optional: padding stress (configs[3]) ------------------------------------
+    if args.adversarial:
+        table = {}
+        for case in (wl.config4(), wl.config4b()):
+            so = SparseOp(M, torch, case, copies=12)
+            do = DenseOp(M, torch, case, copies=8)
+            ts = time_single_op(torch, so, stream_ptr, 10, 100)
+            td = time_single_op(torch, do, stream_ptr, 10, 100)
+            rep = so.report
+            table[case.name] = {
+                "macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
+                "macko_GBps": round(so.bytes / ts / 1e9), "speedup_vs_dense": round(td / ts, 3),
+                "sparsity": round(1.0 - rep.density, 4), "effd": round(rep.effd, 4),
+                "effd_worst_case_eq9": round(rep.effd_worst, 4),
+                "padding_per_nnz": round(rep.padding_entries / max(rep.nnz, 1), 4),
+                "max_row_entries": rep.max_row_entries, "empty_rows": rep.empty_rows,
+            }
+            log(f"  adversarial {case.name}: {table[case.name]}")
+            del so, do
+            torch.cuda.empty_cache()
+        extra["adversarial_8192x8192"] = table
 
     # ---- optional: other code widths (Appendix C) on the sweep matrix ---------------
     if args.widths:
