@@ -380,9 +380,16 @@ def main():
             M.encode_device(Wd).destroy()
         torch.cuda.synchronize()
         t_gpu = (time.perf_counter() - t_g0) / 5
+        # bytes the GPU encoder moves: the dense matrix twice (count, fill), values + one code byte
+        # per entry written, the code bytes read again and packed, counts and row pointers
+        rep_e = sparse_ops[tag].report
+        n_e = rep_e.alloc_nnz
+        enc_bytes = 2 * case.W.nbytes + 3 * n_e + n_e + n_e // 2 + 16 * case.rows
         enc[f"{case.rows}x{case.cols}"] = {
             "host_ms": round(t_host * 1e3, 2), "gpu_ms": round(t_gpu * 1e3, 3),
             "gpu_dense_input_GBps": round(case.W.nbytes / t_gpu / 1e9, 1),
+            "gpu_traffic_GBps": round(enc_bytes / t_gpu / 1e9, 1),
+            "gpu_frac_of_hbm_peak": round(enc_bytes / t_gpu / 1e9 / HBM_PEAK_GBPS, 4),
         }
     extra["encode"] = enc
     log(f"encode: {enc}")
@@ -610,7 +617,8 @@ def main():
                    "macko_bytes_per_step": layer_macko_bytes, "dense_bytes_per_step": layer_dense_bytes},
         "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
         "us_per_spmv": round(ms_per_step * 1e3 / 7, 3),
-        "dense_gemv": {"ms_per_step": round(t_dense / args.steps * 1e3, 5), "GBps": round(dense_gbps, 1)},
+        "dense_gemv": {"ms_per_step": round(t_dense / args.steps * 1e3, 5), "GBps": round(dense_gbps, 1),
+                       "frac_of_hbm_peak": round(dense_gbps / HBM_PEAK_GBPS, 4)},
         "speedup_vs_dense_gemv": round(t_dense / t_sparse, 3),
         "memory_reduction_vs_dense": round(layer_dense_bytes / layer_macko_bytes, 3),
         "per_shape": per_shape,
