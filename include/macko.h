@@ -88,10 +88,12 @@ MACKO_API int macko_encode(const uint16_t* dense_host, int64_t rows, int64_t col
                            macko_handle_t* out, macko_report_t* report);
 
 /* Encode a dense fp16 matrix held in device memory, on the GPU.  The library
- * allocates the device buffers (hipMalloc) and the handle owns them; the handle
+ * allocates the device arrays (one hipMalloc) and the handle owns them; the handle
  * is bound on return and keeps no host copy.  Synchronises `stream` (the sizes
  * of the outputs are only known after a counting pass).  The result is
- * bit-identical to macko_encode on the same input. */
+ * bit-identical to macko_encode on the same input.  The encoder keeps one scratch
+ * buffer per device (about a quarter of the largest dense matrix seen so far, in
+ * bytes) until the process ends, and runs one call at a time per process. */
 MACKO_API int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld,
                                   void* stream, macko_handle_t* out, macko_report_t* report);
 

@@ -1,7 +1,7 @@
 // Dense fp16 -> MACKO conversion on the GPU (format of Section 4.1, tail
-// padding of Section 4.5).  Three passes: count the stored entries of every
-// row, prefix-sum the counts into row_ptr, then write values and codes.  The
-// output is bit-identical to the host encoder's.
+// padding of Section 4.5).  Passes: count the stored entries of every row,
+// prefix-sum the counts into row_ptr, write values and one code byte per entry,
+// pack the code bytes.  The output is bit-identical to the host encoder's.
 //
 // One wavefront works on one row; per step a lane looks at 8 consecutive
 // columns (one 16-byte load, issued one step ahead).  The position of the
@@ -11,6 +11,8 @@
 // entries plus itself.  Per-row counts go to arrays that the scan kernel totals (no atomics).
 #include "macko_device.h"
 #include "macko_internal.h"
+
+#include <mutex>
 
 namespace macko {
 namespace {
@@ -126,82 +128,159 @@ encode_count_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int6
   }
 }
 
-// row_ptr[r] = sum of row_entries[0..r); one workgroup.  Also totals the
-// statistics of the storage report.  The entry total is kept as a 64-bit number
-// so that the host can detect overflow of the 32-bit row pointers before
-// anything is written through them.
-__global__ void __launch_bounds__(1024)
-encode_scan_kernel(const uint32_t* __restrict__ row_entries, const uint32_t* __restrict__ row_nnz,
-                   int rows, uint32_t* __restrict__ row_ptr, EncodeStats* __restrict__ stats) {
-  __shared__ unsigned long long wave_sum[16];
-  __shared__ unsigned long long wave_nnz[16];
-  __shared__ unsigned int wave_empty[16];
-  __shared__ unsigned int wave_max[16];
-  const int t = threadIdx.x;
-  const int lane = t & 63, wave = t >> 6;
-  const int seg = (rows + 1023) / 1024;
-  const int lo = min(rows, t * seg), hi = min(rows, lo + seg);
-  unsigned long long s = 0, n = 0;
-  unsigned int empty = 0, longest = 0;
-  for (int r = lo; r < hi; ++r) {
-    const uint32_t e = row_entries[r];
-    s += e;
-    n += row_nnz[r];
-    empty += e == 0;
-    longest = max(longest, e);
-  }
-  // inclusive scan of the segment sums over the wavefront, totals of the rest
-  unsigned long long incl = s;
+// Row pointers from the per-row counts in three small launches: every block of
+// 1024 rows totals its counts, one workgroup turns the block totals into block
+// offsets (and totals the statistics of the storage report), every block then
+// prefix-sums its own rows.  The entry total is kept as a 64-bit number so that
+// the host can detect overflow of the 32-bit row pointers before anything is
+// written through them.
+struct BlockSums {
+  unsigned long long entries;
+  unsigned long long nnz;
+  unsigned int empty;
+  unsigned int longest;
+};
+
+__device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long v, int lane) {
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
-    const unsigned long long up = __shfl_up(incl, off);
-    if (lane >= off) incl += up;
+    const unsigned long long up = __shfl_up(v, off);
+    if (lane >= off) v += up;
   }
+  return v;
+}
+
+__global__ void __launch_bounds__(1024)
+encode_block_sums_kernel(const uint32_t* __restrict__ row_entries, const uint32_t* __restrict__ row_nnz, int rows,
+                         BlockSums* __restrict__ sums) {
+  __shared__ BlockSums part[16];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int r = blockIdx.x * 1024 + t;
+  const uint32_t e = r < rows ? row_entries[r] : 0u;
+  unsigned long long se = e, sn = r < rows ? row_nnz[r] : 0u;
+  unsigned int empty = (r < rows && e == 0) ? 1u : 0u, longest = e;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
-    n += __shfl_xor(n, off);
+    se += __shfl_xor(se, off);
+    sn += __shfl_xor(sn, off);
     empty += __shfl_xor(empty, off);
     longest = max(longest, __shfl_xor(longest, off));
   }
-  if (lane == 63) {
-    wave_sum[wave] = incl;
-    wave_nnz[wave] = n;
-    wave_empty[wave] = empty;
-    wave_max[wave] = longest;
-  }
+  if (lane == 0) part[wave] = BlockSums{se, sn, empty, longest};
   __syncthreads();
-  unsigned long long before = 0;                       // entries of the wavefronts in front of this one
-  for (int i = 0; i < wave; ++i) before += wave_sum[i];
-  if (t == 1023) {
-    unsigned long long nn = 0;
-    unsigned int em = 0, mx = 0;
-    for (int i = 0; i < 16; ++i) {
-      nn += wave_nnz[i];
-      em += wave_empty[i];
-      mx = max(mx, wave_max[i]);
+  if (t == 0) {
+    BlockSums b = part[0];
+    for (int i = 1; i < 16; ++i) {
+      b.entries += part[i].entries;
+      b.nnz += part[i].nnz;
+      b.empty += part[i].empty;
+      b.longest = max(b.longest, part[i].longest);
     }
-    const unsigned long long total = before + incl;
-    stats->pad_nnz = total;
-    stats->nnz = nn;
-    stats->empty_rows = em;
-    stats->max_row_entries = mx;
-    row_ptr[rows] = (uint32_t)total;
-  }
-  unsigned long long run = before + incl - s;
-  for (int r = lo; r < hi; ++r) {
-    row_ptr[r] = (uint32_t)run;
-    run += row_entries[r];
+    sums[blockIdx.x] = b;
   }
 }
 
-__global__ void __launch_bounds__(256)
+// one workgroup: block_off[b] = entries of the blocks in front of b; totals to *stats
+__global__ void __launch_bounds__(1024)
+encode_block_offsets_kernel(const BlockSums* __restrict__ sums, int nblocks, unsigned long long* __restrict__ block_off,
+                            uint32_t* __restrict__ row_ptr_last, EncodeStats* __restrict__ stats) {
+  __shared__ unsigned long long wave_tot[16];
+  __shared__ unsigned long long carry_s;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  unsigned long long nnz = 0;
+  unsigned int empty = 0, longest = 0;
+  if (t == 0) carry_s = 0;
+  __syncthreads();
+  for (int base = 0; base < nblocks; base += 1024) {
+    const int b = base + t;
+    const BlockSums v = b < nblocks ? sums[b] : BlockSums{0, 0, 0, 0};
+    nnz += v.nnz;
+    empty += v.empty;
+    longest = max(longest, v.longest);
+    const unsigned long long incl = wave_incl_scan_u64(v.entries, lane);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    unsigned long long before = carry_s;
+    for (int i = 0; i < wave; ++i) before += wave_tot[i];
+    if (b < nblocks) block_off[b] = before + incl - v.entries;
+    __syncthreads();
+    if (t == 1023) carry_s = before + incl;
+    __syncthreads();
+  }
+  // totals of the statistics over the workgroup
+  __shared__ unsigned long long s_nnz[16];
+  __shared__ unsigned int s_empty[16], s_long[16];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    nnz += __shfl_xor(nnz, off);
+    empty += __shfl_xor(empty, off);
+    longest = max(longest, __shfl_xor(longest, off));
+  }
+  if (lane == 0) {
+    s_nnz[wave] = nnz;
+    s_empty[wave] = empty;
+    s_long[wave] = longest;
+  }
+  __syncthreads();
+  if (t == 0) {
+    unsigned long long nn = 0;
+    unsigned int em = 0, mx = 0;
+    for (int i = 0; i < 16; ++i) {
+      nn += s_nnz[i];
+      em += s_empty[i];
+      mx = max(mx, s_long[i]);
+    }
+    stats->pad_nnz = carry_s;
+    stats->nnz = nn;
+    stats->empty_rows = em;
+    stats->max_row_entries = mx;
+    *row_ptr_last = (uint32_t)carry_s;
+  }
+}
+
+__global__ void __launch_bounds__(1024)
+encode_row_ptr_kernel(const uint32_t* __restrict__ row_entries, int rows, const unsigned long long* __restrict__ block_off,
+                      uint32_t* __restrict__ row_ptr, uint32_t total) {
+  __shared__ unsigned long long wave_tot[16];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int r = blockIdx.x * 1024 + t;
+  const unsigned long long e = r < rows ? row_entries[r] : 0u;
+  const unsigned long long incl = wave_incl_scan_u64(e, lane);
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  unsigned long long before = block_off[blockIdx.x];
+  for (int i = 0; i < wave; ++i) before += wave_tot[i];
+  if (r < rows) row_ptr[r] = (uint32_t)(before + incl - e);
+  if (r == rows - 1) row_ptr[rows] = total;
+}
+
+// Second pass: values and one code byte per entry.  A wavefront's entries of one step are
+// contiguous in the output (from `cursor` on), but every lane holds a different number of them;
+// they are first put in order in LDS (index = position in the output modulo 16, so that aligned
+// 16-byte pieces of LDS are aligned 16-byte pieces of the arrays) and then written out with
+// 16-byte stores, the ragged first and last piece element by element.  A step with more than
+// kStage entries (long runs of padding) writes straight to memory instead.
+constexpr int kStage = 1024;
+constexpr int kFillWaves = 4;
+
+__global__ void __launch_bounds__(64 * kFillWaves)
 encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok, int b_delta,
                    const uint32_t* __restrict__ row_ptr, uint16_t* __restrict__ values,
-                   uint8_t* __restrict__ codes8) {
+                   uint8_t* __restrict__ codes8, uint32_t pad_nnz, uint32_t alloc_nnz) {
+  // the zero tail of both arrays (fewer than 128 entries): the first workgroup writes it
+  if (blockIdx.x == 0)
+    for (uint32_t k = pad_nnz + threadIdx.x; k < alloc_nnz; k += blockDim.x) {
+      values[k] = 0;
+      codes8[k] = 0;
+    }
+  __shared__ __align__(16) uint16_t stage_v[kFillWaves][kStage + 16];
+  __shared__ __align__(16) uint8_t stage_c[kFillWaves][kStage + 16];
   const int full = (1 << b_delta) - 1;             // code of the largest delta
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nwaves = blockDim.x >> 6;
+  uint16_t* sv = stage_v[wave];
+  uint8_t* sc = stage_c[wave];
   for (int row = blockIdx.x * nwaves + wave; row < rows; row += gridDim.x * nwaves) {
     const uint16_t* src = dense + (int64_t)row * ld;
     uint32_t carry = 0;
@@ -213,8 +292,35 @@ encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64
       nxt = load_raw(src, col0 + 512, cols, vec_ok);                 // next step's columns, in flight
       const LaneView v = view_chunk(c.mask, col0, lane, b_delta, &carry);
       const uint32_t incl = wave_incl_scan_u32(v.entries);
-      size_t o = (size_t)cursor + (incl - v.entries);
-      if (c.mask) {
+      const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      const bool staged = total <= (uint32_t)kStage;                 // wavefront-uniform
+      const uint32_t align = cursor & 15u;
+      // where this lane's first entry goes: LDS index (staged) or output index (direct)
+      size_t o = staged ? (size_t)(align + (incl - v.entries)) : (size_t)cursor + (incl - v.entries);
+      if (c.mask && staged && b_delta >= 3) {
+        // Common case.  Only the chunk's first non-zero can have padding in front of it; the
+        // eight columns are then visited in a fixed order, so that no register is picked with a
+        // run-time index and every lane runs the same eight predicated stores.
+        for (int pads = v.lead >> b_delta; pads > 0; --pads) {       // padding entries, greedy
+          sv[o] = 0;
+          sc[o] = (uint8_t)full;
+          ++o;
+        }
+        int g1 = v.lead & full;                  // code of the next stored non-zero
+        bool seen = false;                       // zeros in front of the first non-zero are part of v.lead
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          if ((c.mask >> k) & 1u) {
+            sv[o] = c.h[k];
+            sc[o] = (uint8_t)g1;
+            ++o;
+            g1 = 0;                              // the next non-zero is g1 + 1 columns further
+            seen = true;
+          } else if (seen) {
+            ++g1;
+          }
+        }
+      } else if (c.mask) {
         unsigned m = c.mask;
         int g1 = v.lead;                         // (gap - 1) in front of the next stored non-zero
         int prevk = -1;
@@ -223,17 +329,53 @@ encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64
           m &= m - 1;
           if (prevk >= 0) g1 = k - prevk - 1;
           for (int pads = g1 >> b_delta; pads > 0; --pads) {        // padding entries, greedy
-            values[o] = 0;
-            codes8[o] = (uint8_t)full;
+            if (staged) {
+              sv[o] = 0;
+              sc[o] = (uint8_t)full;
+            } else {
+              values[o] = 0;
+              codes8[o] = (uint8_t)full;
+            }
             ++o;
           }
-          values[o] = c.h[k];
-          codes8[o] = (uint8_t)(g1 & full);
+          if (staged) {
+            sv[o] = c.h[k];
+            sc[o] = (uint8_t)(g1 & full);
+          } else {
+            values[o] = c.h[k];
+            codes8[o] = (uint8_t)(g1 & full);
+          }
           ++o;
           prevk = k;
         }
       }
-      cursor += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      if (staged && total > 0) {
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t first = align, last = align + total;         // staged entries [first, last)
+        const size_t out0 = (size_t)cursor - align;                  // output index of staged index 0 (multiple of 16)
+        // values: pieces of 8 entries
+        for (uint32_t p = lane; 8u * p < last; p += 64) {
+          const uint32_t lo = 8u * p, hi = lo + 8u;
+          if (hi <= first) continue;
+          if (lo >= first && hi <= last) {
+            *reinterpret_cast<uint4*>(values + out0 + lo) = *reinterpret_cast<const uint4*>(sv + lo);
+          } else {
+            for (uint32_t k = max(lo, first); k < min(hi, last); ++k) values[out0 + k] = sv[k];
+          }
+        }
+        // code bytes: pieces of 16 entries
+        for (uint32_t p = lane; 16u * p < last; p += 64) {
+          const uint32_t lo = 16u * p, hi = lo + 16u;
+          if (hi <= first) continue;
+          if (lo >= first && hi <= last) {
+            *reinterpret_cast<uint4*>(codes8 + out0 + lo) = *reinterpret_cast<const uint4*>(sc + lo);
+          } else {
+            for (uint32_t k = max(lo, first); k < min(hi, last); ++k) codes8[out0 + k] = sc[k];
+          }
+        }
+        __builtin_amdgcn_wave_barrier();
+      }
+      cursor += total;
     }
   }
 }
@@ -269,65 +411,140 @@ struct DeviceBuf {
   }
 };
 
+// Scratch memory of the encoder (per-row counts, block sums, the code bytes), kept per
+// device and reused from call to call; it only grows.  One encoder call at a time uses it.
+struct Workspace {
+  void* p = nullptr;
+  size_t cap = 0;
+  EncodeStats* pinned_stats = nullptr;   // host, pinned: the counting pass reports through it
+};
+std::mutex g_ws_mutex;
+Workspace g_ws[64];
+
+hipError_t workspace_reserve(Workspace& ws, size_t bytes) {
+  if (bytes <= ws.cap) return hipSuccess;
+  if (ws.p) (void)hipFree(ws.p);
+  ws.p = nullptr;
+  ws.cap = 0;
+  const size_t want = bytes + bytes / 4;             // some slack so that similar sizes do not reallocate
+  hipError_t e = hipMalloc(&ws.p, want);
+  if (e == hipSuccess) ws.cap = want;
+  return e;
+}
+
+constexpr size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
 }  // namespace
 
+// The handle's three arrays live in ONE allocation (*block, to be released with hipFree):
+// values first, then deltas, then row_ptr, each at a multiple of 256 bytes.
 int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta,
-                     hipStream_t stream,
+                     hipStream_t stream, void** block,
                      uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
                      int64_t* pad_nnz, int64_t* alloc_nnz, int64_t* empty_rows,
                      int64_t* max_row_entries) {
   const int cus = device_cu_count();
   const bool vec_ok = (ld % 8 == 0) && (reinterpret_cast<uintptr_t>(dense) & 15) == 0;
-  DeviceBuf counts, nnzs, stats_d, rp, vals, dels, codes;
-  if (counts.alloc(4 * (size_t)rows) != hipSuccess || nnzs.alloc(4 * (size_t)rows) != hipSuccess || stats_d.alloc(sizeof(EncodeStats)) != hipSuccess ||
-      rp.alloc(4 * (size_t)(rows + 1)) != hipSuccess) {
+  int dev = 0;
+  MACKO_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return MACKO_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_ws_mutex);
+  Workspace& ws = g_ws[dev];
+  if (!ws.pinned_stats) {
+    void* h = nullptr;
+    if (hipHostMalloc(&h, sizeof(EncodeStats), hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      return MACKO_E_OUT_OF_MEMORY;
+    }
+    ws.pinned_stats = static_cast<EncodeStats*>(h);
+  }
+  // scratch layout of the counting pass
+  const int64_t nblocks = (rows + 1023) / 1024;
+  const size_t o_counts = 0;
+  const size_t o_nnz = align_up(o_counts + 4 * (size_t)rows, 256);
+  const size_t o_rowptr = align_up(o_nnz + 4 * (size_t)rows, 256);
+  const size_t o_sums = align_up(o_rowptr + 256, 256);
+  const size_t o_boff = align_up(o_sums + sizeof(BlockSums) * (size_t)std::max<int64_t>(nblocks, 1), 256);
+  const size_t o_stats = align_up(o_boff + 8 * (size_t)std::max<int64_t>(nblocks, 1), 256);
+  const size_t o_codes = align_up(o_stats + sizeof(EncodeStats), 256);
+  // room for the code bytes is reserved for the expected case right away (half the cells), so
+  // that the common call does not have to grow the scratch after the counting pass
+  if (workspace_reserve(ws, o_codes + (size_t)rows * (size_t)cols / 2 + 4096) != hipSuccess) {
     (void)hipGetLastError();
     return MACKO_E_OUT_OF_MEMORY;
   }
+  auto at = [&](size_t off) { return static_cast<unsigned char*>(ws.p) + off; };
+  uint32_t* counts = reinterpret_cast<uint32_t*>(at(o_counts));
+  uint32_t* nnzs = reinterpret_cast<uint32_t*>(at(o_nnz));
+  uint32_t* rp_last = reinterpret_cast<uint32_t*>(at(o_rowptr));   // scratch word for the 32-bit total
+  BlockSums* sums = reinterpret_cast<BlockSums*>(at(o_sums));
+  unsigned long long* boff = reinterpret_cast<unsigned long long*>(at(o_boff));
+  EncodeStats* stats_d = reinterpret_cast<EncodeStats*>(at(o_stats));
+
   const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((rows + 3) / 4, (int64_t)cus * 16));
   if (rows > 0) {
     hipLaunchKernelGGL(encode_count_kernel, dim3(grid), dim3(256), 0, stream, dense, (int)rows,
-                       (int)cols, ld, vec_ok, b_delta, static_cast<uint32_t*>(counts.p),
-                       static_cast<uint32_t*>(nnzs.p));
+                       (int)cols, ld, vec_ok, b_delta, counts, nnzs);
+    hipLaunchKernelGGL(encode_block_sums_kernel, dim3((unsigned)nblocks), dim3(1024), 0, stream, counts, nnzs,
+                       (int)rows, sums);
   }
-  hipLaunchKernelGGL(encode_scan_kernel, dim3(1), dim3(1024), 0, stream,
-                     static_cast<const uint32_t*>(counts.p), static_cast<const uint32_t*>(nnzs.p),
-                     (int)rows, static_cast<uint32_t*>(rp.p),
-                     static_cast<EncodeStats*>(stats_d.p));
+  hipLaunchKernelGGL(encode_block_offsets_kernel, dim3(1), dim3(1024), 0, stream, sums, (int)nblocks, boff,
+                     rp_last, stats_d);
   MACKO_HIP_TRY(hipGetLastError());
-  EncodeStats st{};
-  MACKO_HIP_TRY(hipMemcpyAsync(&st, stats_d.p, sizeof(st), hipMemcpyDeviceToHost, stream));
+  MACKO_HIP_TRY(hipMemcpyAsync(ws.pinned_stats, stats_d, sizeof(EncodeStats), hipMemcpyDeviceToHost, stream));
   MACKO_HIP_TRY(hipStreamSynchronize(stream));
+  const EncodeStats st = *ws.pinned_stats;
   if (st.pad_nnz >= (1ull << 32)) return MACKO_E_OVERFLOW;
   const int64_t pad = (int64_t)st.pad_nnz;
   const int64_t granule = alloc_granule(b_delta);
   const int64_t alloc = (pad + granule - 1) / granule * granule;
   if (alloc >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
-  if (vals.alloc((size_t)alloc * 2) != hipSuccess || dels.alloc((size_t)alloc * b_delta / 8) != hipSuccess ||
-      codes.alloc((size_t)alloc) != hipSuccess) {
+
+  // the output block; the code bytes get more scratch if the guess above was too small
+  // (nothing in the old scratch but the per-row counts is needed any more, so they are
+  // turned into row pointers before the scratch moves)
+  const size_t b_values = 0;
+  const size_t b_deltas = align_up(b_values + (size_t)alloc * 2, 256);
+  const size_t b_rowptr = align_up(b_deltas + (size_t)alloc * b_delta / 8, 256);
+  const size_t b_total = b_rowptr + 4 * (size_t)(rows + 1);
+  DeviceBuf out;
+  if (out.alloc(b_total) != hipSuccess) {
     (void)hipGetLastError();
     return MACKO_E_OUT_OF_MEMORY;
   }
-  if (alloc > pad) {  // zero tail of both arrays
-    MACKO_HIP_TRY(hipMemsetAsync(static_cast<uint16_t*>(vals.p) + pad, 0, (size_t)(alloc - pad) * 2, stream));
-    MACKO_HIP_TRY(hipMemsetAsync(static_cast<uint8_t*>(codes.p) + pad, 0, (size_t)(alloc - pad), stream));
+  unsigned char* ob = static_cast<unsigned char*>(out.p);
+  uint16_t* vals = reinterpret_cast<uint16_t*>(ob + b_values);
+  uint32_t* dels = reinterpret_cast<uint32_t*>(ob + b_deltas);
+  uint32_t* rp = reinterpret_cast<uint32_t*>(ob + b_rowptr);
+  if (rows > 0)
+    hipLaunchKernelGGL(encode_row_ptr_kernel, dim3((unsigned)nblocks), dim3(1024), 0, stream, counts, (int)rows,
+                       boff, rp, (uint32_t)pad);
+  else
+    MACKO_HIP_TRY(hipMemsetAsync(rp, 0, 4, stream));
+  if (o_codes + (size_t)alloc + 256 > ws.cap) {
+    MACKO_HIP_TRY(hipStreamSynchronize(stream));       // the launch above reads the old scratch
+    if (workspace_reserve(ws, o_codes + (size_t)alloc + 256) != hipSuccess) {
+      (void)hipGetLastError();
+      return MACKO_E_OUT_OF_MEMORY;
+    }
   }
-  if (rows > 0 && pad > 0) {
-    hipLaunchKernelGGL(encode_fill_kernel, dim3(grid), dim3(256), 0, stream, dense, (int)rows, (int)cols,
-                       ld, vec_ok, b_delta, static_cast<const uint32_t*>(rp.p), static_cast<uint16_t*>(vals.p),
-                       static_cast<uint8_t*>(codes.p));
-  }
-  if (alloc > 0) {
+  uint8_t* codes = static_cast<unsigned char*>(ws.p) + o_codes;
+
+  if (rows > 0 && alloc > 0) {
+    hipLaunchKernelGGL(encode_fill_kernel, dim3(grid), dim3(64 * kFillWaves), 0, stream, dense, (int)rows,
+                       (int)cols, ld, vec_ok, b_delta, static_cast<const uint32_t*>(rp), vals, codes,
+                       (uint32_t)pad, (uint32_t)alloc);
     const int64_t words = alloc * b_delta / 32;
     const unsigned pgrid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((words + 255) / 256, (int64_t)cus * 16));
-    hipLaunchKernelGGL(encode_pack_kernel, dim3(pgrid), dim3(256), 0, stream,
-                       static_cast<const uint8_t*>(codes.p), words, b_delta, static_cast<uint32_t*>(dels.p));
+    hipLaunchKernelGGL(encode_pack_kernel, dim3(pgrid), dim3(256), 0, stream, static_cast<const uint8_t*>(codes),
+                       words, b_delta, dels);
   }
   MACKO_HIP_TRY(hipGetLastError());
   MACKO_HIP_TRY(hipStreamSynchronize(stream));
-  *values = static_cast<uint16_t*>(vals.release());
-  *deltas = static_cast<uint8_t*>(dels.release());
-  *row_ptr = static_cast<uint32_t*>(rp.release());
+  *block = out.release();
+  *values = vals;
+  *deltas = reinterpret_cast<uint8_t*>(dels);
+  *row_ptr = rp;
   *nnz = (int64_t)st.nnz;
   *pad_nnz = pad;
   *alloc_nnz = alloc;

@@ -238,8 +238,9 @@ int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, in
   uint8_t* d = nullptr;
   uint32_t* rp = nullptr;
   int64_t nnz = 0, pad = 0, alloc = 0, empty = 0, longest = 0;
+  void* block = nullptr;
   int st = macko::encode_on_device(static_cast<const uint16_t*>(dense_dev), rows, cols, ld, b_delta,
-                                   static_cast<hipStream_t>(stream), &v, &d, &rp, &nnz, &pad, &alloc,
+                                   static_cast<hipStream_t>(stream), &block, &v, &d, &rp, &nnz, &pad, &alloc,
                                    &empty, &longest);
   if (st != MACKO_OK) {
     delete m;
@@ -255,6 +256,7 @@ int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, in
   m->b_delta = b_delta;
   m->bound = true;
   m->owns_device = true;
+  m->d_block = block;
   macko::fill_report(&m->report, rows, cols, nnz, pad, alloc, empty, longest, b_delta);
   if (report) *report = m->report;
   *out = m;
@@ -446,11 +448,7 @@ int macko_dense_gemv_group(int n, const void* const* W_dev, const int64_t* rows,
 
 void macko_destroy(macko_handle_t h) {
   if (!h) return;
-  if (h->owns_device) {
-    (void)hipFree(const_cast<uint16_t*>(h->d_values));
-    (void)hipFree(const_cast<uint8_t*>(h->d_deltas));
-    (void)hipFree(const_cast<uint32_t*>(h->d_row_ptr));
-  }
+  if (h->owns_device && h->d_block) (void)hipFree(h->d_block);   // the three arrays are parts of it
   delete h;
 }
 

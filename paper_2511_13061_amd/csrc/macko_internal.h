@@ -64,9 +64,9 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream);
 // batch products with one matrix: Y[b] = W X[b], vectors ldx / ldy elements apart (p.x, p.y unused)
 int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64_t ldy, int batch,
                 hipStream_t stream);
-// GPU encoder: counting pass + fill pass.  Allocates *values, *deltas, *row_ptr with hipMalloc.
+// GPU encoder: counting pass + fill pass.  The three arrays are parts of one hipMalloc'd *block.
 int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta,
-                     hipStream_t stream,
+                     hipStream_t stream, void** block,
                      uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
                      int64_t* pad_nnz, int64_t* alloc_nnz, int64_t* empty_rows,
                      int64_t* max_row_entries);
@@ -92,4 +92,5 @@ struct macko_matrix {
   const uint32_t* d_row_ptr = nullptr;
   bool bound = false;
   bool owns_device = false;
+  void* d_block = nullptr;   // owns_device: the one allocation that holds the three arrays
 };
