@@ -108,9 +108,8 @@ MACKO_API int macko_wrap_device(int64_t rows, int64_t cols, int64_t pad_nnz, con
 /* The same three calls for another code width b_delta in {1, 2, 4, 8} (Section
  * 4.1 allows exactly these; Appendix C: 2 bits store less below ~45 % sparsity,
  * 8 bits above ~95 %).  Everything else -- handles, binding, decode, the report,
- * macko_spmv and macko_spmv_group -- works for every width; macko_spmm takes
- * 4-bit handles only (MACKO_E_UNSUPPORTED otherwise).  Any other b_delta is
- * MACKO_E_INVALID_ARG. */
+ * macko_spmv, macko_spmv_group and macko_spmm -- works for every width.  Any
+ * other b_delta is MACKO_E_INVALID_ARG. */
 MACKO_API int macko_encode_ex(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                               int b_delta, macko_handle_t* out, macko_report_t* report);
 MACKO_API int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld,

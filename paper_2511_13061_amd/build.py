@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmacko.so")
 SOURCES = ["macko_host.cpp", "macko_spmv.hip", "macko_gemv.hip", "macko_encode_gpu.hip", "macko_spmm.hip"]
-HEADERS = ["macko_internal.h", "macko_device.h", "macko_plan.h"]
+HEADERS = ["macko_internal.h", "macko_device.h", "macko_plan.h", "macko_decode.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

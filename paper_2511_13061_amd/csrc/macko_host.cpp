@@ -416,7 +416,6 @@ int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void
   if (ldx < h->cols || ldy < h->rows) return MACKO_E_INVALID_ARG;
   int st = check_vec_ptrs(X_dev, Y_dev, h->cols);
   if (st != MACKO_OK) return st;
-  if (h->b_delta != macko::kDeltaBits) return MACKO_E_UNSUPPORTED;   // the batch kernel decodes 4-bit codes only
   macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz, nullptr, nullptr,
                        h->b_delta};
   return macko::launch_spmm(p, X_dev, ldx, Y_dev, ldy, batch, static_cast<hipStream_t>(stream));

@@ -10,6 +10,7 @@
 // are adjacent (2*BT bytes), so one gather address per entry fetches all of
 // them with a single ds_read_b32 / b64 / b128.  Guards of zeros in front of and
 // behind the columns play the same role as in the matrix-vector kernel.
+#include "macko_decode.h"
 #include "macko_device.h"
 #include "macko_internal.h"
 #include "macko_plan.h"
@@ -43,19 +44,19 @@ __device__ __forceinline__ void unpack_x<8>(const uint4& v, float* out) {
 }
 
 // Copy X (batch vectors of `cols` fp16, vector b at X + b*ldx) into LDS, interleaved
-// by column, between zero guards of kFrontPad*BT and kBackPad*BT bytes.  Vectors
+// by column, between zero guards of front_pad*BT and back_pad*BT bytes.  Vectors
 // b >= batch are filled with zeros.  Ends with a barrier.
 template <int BT>
 __device__ __forceinline__ void stage_X_interleaved(unsigned char* lds, const uint16_t* __restrict__ X,
-                                                    int64_t ldx, int batch, int cols) {
+                                                    int64_t ldx, int batch, int cols, int front_pad, int back_pad) {
   const int tid = threadIdx.x, nt = blockDim.x;
   const int chunks = (cols + 7) >> 3;
   const bool vec_ok = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && (ldx & 7) == 0;
   uint4* lds16 = reinterpret_cast<uint4*>(lds);
   const uint4 zero = make_uint4(0, 0, 0, 0);
-  const int front16 = kFrontPad * BT / 16, back16 = kBackPad * BT / 16, body16 = chunks * BT;   // 16-byte units
+  const int front16 = front_pad * BT / 16, back16 = back_pad * BT / 16, body16 = chunks * BT;   // 16-byte units
   for (int i = tid; i < front16 + back16; i += nt) lds16[i < front16 ? i : i + body16] = zero;
-  uint16_t* xs = reinterpret_cast<uint16_t*>(lds + kFrontPad * BT);
+  uint16_t* xs = reinterpret_cast<uint16_t*>(lds + front_pad * BT);
   for (int t = tid; t < chunks; t += nt) {
     uint16_t h[BT][8];
 #pragma unroll
@@ -81,7 +82,7 @@ __device__ __forceinline__ void stage_X_interleaved(unsigned char* lds, const ui
   __syncthreads();
 }
 
-template <int BT>
+template <int BT, int BD>
 __global__ void __launch_bounds__(1024)
 spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
                      const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ X, int64_t ldx,
@@ -97,7 +98,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const unsigned char* xbase = lds + kFrontPad * BT;   // LDS address of column 0
+  const unsigned char* xbase = lds + front_pad_for(BD) * BT;   // LDS address of column 0
   const uint32_t lane8 = 8u * lane;
   const int per_wave = (wg_rows * inv_nwaves) >> 16;     // wg_rows / nwaves (exact for wg_rows <= 1024)
   const int extra = wg_rows - per_wave * nwaves;
@@ -106,7 +107,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
 
   uint32_t chunk = 0;
   RowCursor ld, cp;
-  uint32_t wq[RING];
+  LaneCodes<BD> wq[RING];
   uint4 vq[RING];
   const int r = min(blk + lane, rows - 1);             // unconditional loads, clamped to the last row
   const uint32_t rp_lo = row_ptr[r];
@@ -123,7 +124,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
     } else {
       chunk = 0;
     }
-    wq[j] = deltas[chunk];
+    wq[j].load(deltas, chunk);
     vq[j] = values[chunk];
   };
   ld.i = 0;
@@ -131,7 +132,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
   cp = ld;
 #pragma unroll
   for (int j = 0; j < RING; ++j) issue(j);
-  stage_X_interleaved<BT>(lds, X, ldx, batch, cols);    // ends with a barrier
+  stage_X_interleaved<BT>(lds, X, ldx, batch, cols, front_pad_for(BD), back_pad_for(BD));    // ends with a barrier
 
   float yv[BT], acc[BT];
 #pragma unroll
@@ -140,7 +141,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
   while (cp.i < nb) {
 #pragma unroll
     for (int j = 0; j < RING; ++j) {
-      uint32_t w = wq[j];
+      LaneCodes<BD> w = wq[j];
       uint4 v = vq[j];
       const bool live = cp.i < nb;
       if (!live) base2 = 0;
@@ -148,37 +149,28 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
       const uint32_t e0 = cp.a0 + 512u * cp.step + lane8;
       if (!live || cp.step == cp.nsteps - 1) {
         const uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;
-        w = nv != 0 ? w : 0u;
+        w.keep_if(nv != 0);
         v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
         v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
         v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
         v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
       }
-      const uint32_t lo2 = (w << 1) & 0x1E1E1E1Eu;
-      const uint32_t hi2 = (w >> 3) & 0x1E1E1E1Eu;
-      uint32_t P = lo2 + hi2;
-      P = lshl_add<8>(P, P);
-      P = lshl_add<16>(P, P);
-      const uint32_t E = lshl_add<8>(P, lo2);
-      const uint32_t tot = (P >> 24) + 16u;
+      w.decode();
+      const uint32_t tot = w.total();
       const uint32_t incl = wave_incl_scan_u32(tot);
       if (live && cp.step == 0) {
         base2 = 0;
         const int before = (int)(cp.start - cp.a0);
-        if (before > 0) {
-          const int k = before - 1;
-          const uint32_t src = __builtin_amdgcn_readfirstlane((k & 1) ? P : E);
-          base2 = -(int)(((src >> (8 * (k >> 1))) & 0xFFu) + 2u * (uint32_t)(k + 1));
-        }
+        if (before > 0) base2 = -(int)w.through(before - 1);
       }
-      const uint32_t E2 = E + 0x0C080400u;
-      const uint32_t P2 = P + 0x0E0A0602u;
       const int lanebase = base2 + (int)(incl - tot);
+      const int off[8] = {w.template offset<0>(), w.template offset<1>(), w.template offset<2>(),
+                          w.template offset<3>(), w.template offset<4>(), w.template offset<5>(),
+                          w.template offset<6>(), w.template offset<7>()};
       const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const uint32_t word = (k & 1) ? P2 : E2;
-        const int q = lanebase + (int)((word >> (8 * (k >> 1))) & 0xFFu);   // byte offset for one vector
+        const int q = lanebase + off[k];                                    // byte offset for one vector
         const XV xraw = *reinterpret_cast<const XV*>(xbase + q * BT);
         float xf[BT];
         unpack_x<BT>(xraw, xf);
@@ -214,11 +206,11 @@ __global__ void __launch_bounds__(256) zero_Y_kernel(uint16_t* __restrict__ Y, i
     for (int b = 0; b < batch; ++b) Y[(int64_t)b * ldy + i] = 0;
 }
 
-template <int BT>
-int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y, int64_t ldy, int batch,
-              hipStream_t stream) {
+template <int BT, int BD>
+int launch_bt_bd(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y, int64_t ldy, int batch,
+                 hipStream_t stream) {
   const int cus = device_cu_count();
-  const int64_t lds = (int64_t)BT * lds_bytes_for(p.cols);
+  const int64_t lds = (int64_t)BT * lds_bytes_for(p.cols, BD);
   const int64_t avg = p.pad_nnz / p.rows;
   PlanInput in{p.rows, std::max<int64_t>(1, (avg + 511) / 512), lds};
   // The interleaved copy of X is BT times the size of x, so a workgroup is expensive to start:
@@ -238,7 +230,7 @@ int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y,
   const int block = plan.block;
   const int64_t grid = plan.total_wgs;
   if (grid >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
-  auto kfn = spmm_wave_row_kernel<BT>;
+  auto kfn = spmm_wave_row_kernel<BT, BD>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -250,6 +242,17 @@ int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y,
                      65536 / (block / 64) + 1);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
+
+template <int BT>
+int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y, int64_t ldy, int batch,
+              hipStream_t stream) {
+  switch (p.b_delta) {
+    case 2: return launch_bt_bd<BT, 2>(p, X, ldx, Y, ldy, batch, stream);
+    case 4: return launch_bt_bd<BT, 4>(p, X, ldx, Y, ldy, batch, stream);
+    case 8: return launch_bt_bd<BT, 8>(p, X, ldx, Y, ldy, batch, stream);
+    default: return MACKO_E_UNSUPPORTED;
+  }
 }
 
 }  // namespace
@@ -269,9 +272,10 @@ int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? MACKO_OK : hip_fail(e);
   }
-  const int64_t one = lds_bytes_for(p.cols);
+  const int64_t one = lds_bytes_for(p.cols, p.b_delta);
   const int64_t limit = 160 * 1024 - 64;
-  const bool long_rows = p.pad_nnz / p.rows >= 384;
+  // 1-bit codes have no batch kernel: they go through the matrix-vector path one vector at a time
+  const bool long_rows = p.pad_nnz / p.rows >= 384 && p.b_delta != 1;
   int done = 0;
   while (done < batch) {
     const int left = batch - done;

@@ -312,10 +312,12 @@ def test_other_code_widths_gpu_encoder_wrap_and_groups(b_delta):
     torch.cuda.synchronize()
     for i, yi in enumerate(ys):
         check_y(yi, W, x, f"mixed group member {i}")
-    # the batch product has no kernel for these widths
-    with pytest.raises(M.MackoError) as e:
-        g.spmm(torch.zeros(2, 2500, dtype=torch.float16, device="cuda"))
-    assert e.value.status == -3
+    # the small-batch product decodes the same widths (1-bit codes: one vector at a time)
+    X = torch.stack([to_dev(wl.x_vector(2500, 52, 10 + b)) for b in range(7)])
+    Y = g.spmm(X)
+    torch.cuda.synchronize()
+    for b in range(7):
+        check_y(Y[b], W, wl.x_vector(2500, 52, 10 + b), f"spmm b{b_delta} column {b}")
 
 
 def test_code_widths_full_size_llama_shape():

@@ -116,9 +116,8 @@ def test_code_width_argument_is_validated():
         assert lib.macko_encode_ex(W.ctypes.data, 2, 2, 2, bad, ctypes.byref(h), None) == -1
         assert h.value is None
         assert lib.macko_wrap_device_ex(2, 2, 4, bad, 256, 256, 256, ctypes.byref(h)) == -1
-    # the batch product decodes 4-bit codes only; refused before any device work
     m = M.encode(W, 2)
-    assert lib.macko_spmm(m._h, 2, 16, 2, 16, 2, None) == -5    # not bound comes first
+    assert lib.macko_spmm(m._h, 2, 16, 2, 16, 2, None) == -5    # not bound: refused before any device work
 
 
 def test_special_bit_patterns_and_strided_input():
