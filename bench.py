@@ -51,15 +51,15 @@ def dense_bytes(rows, cols) -> int:
 class SparseOp:
     """One matrix bound to the device `copies` times at distinct addresses."""
 
-    def __init__(self, M, torch, case, copies):
+    def __init__(self, M, torch, case, copies, b_delta=4):
         self.name, self.rows, self.cols = case.name, case.rows, case.cols
-        first = M.encode(case.W).to_device()              # host encoder, torch-owned device memory
+        first = M.encode(case.W, b_delta).to_device()     # host encoder, torch-owned device memory
         self.report = first.report
         self.handles = [first]
         if copies > 1:                                   # further copies: GPU encoder (bit-identical output)
             Wd = torch.from_numpy(case.W.view(np.float16)).cuda()
             for _ in range(copies - 1):
-                self.handles.append(M.encode_device(Wd))
+                self.handles.append(M.encode_device(Wd, b_delta=b_delta))
             del Wd
         self.x = torch.from_numpy(case.x.view(np.float16)).cuda()
         self.y = torch.empty(case.rows, dtype=torch.float16, device="cuda")
@@ -231,11 +231,11 @@ def main():
 
     # ---- the same layer with grouped launches in dependency order --------------
     # {q,k,v} -> {o} -> {gate,up} -> {down}: products that do not depend on each other share a launch
-    def grouped_steps(kind):
+    def grouped_steps(kind, ops=None):
         steps = []
         for layer in range(n_layers):
             def pick(tag, ks):
-                op = (sparse_ops if kind == "sparse" else dense_ops)[tag]
+                op = (ops if ops is not None else sparse_ops if kind == "sparse" else dense_ops)[tag]
                 mult = dict(layer_plan)[tag]
                 if kind == "sparse":
                     return [op.handles[layer * mult + k] for k in ks], [op.x] * len(ks), \
@@ -321,6 +321,25 @@ def main():
     }
     log(f"layer, all 7 products in 1 launch (ignores the decoder's dependences): {one_launch}")
     del g1s, g1d
+
+    # the same four grouped launches with 2-bit codes (Appendix C: the smaller encoding up to
+    # about 50 % sparsity); `value` stays on the paper's default of 4 bits
+    sparse2 = {tag: SparseOp(M, torch, case, copies=mult * n_layers, b_delta=2)
+               for case, (tag, mult) in zip(cases, layer_plan)}
+    gs2 = grouped_steps("sparse", sparse2)
+    t2 = time_region(torch, make_grouped_step(gs2), args.warmup, args.steps)
+    bytes2 = sum(mult * sparse2[tag].bytes for tag, mult in layer_plan)
+    two_bit = {
+        "ms_per_step": round(t2 / args.steps * 1e3, 5), "bytes_per_step": bytes2,
+        "GBps": round(bytes2 / (t2 / args.steps) / 1e9, 1),
+        "frac_of_hbm_peak": round(bytes2 / (t2 / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
+        "speedup_vs_dense_gemv": round(t_dense / t2, 3),
+        "memory_reduction_vs_dense": round(layer_dense_bytes / bytes2, 3),
+        "padding_per_nnz": round(sparse2["qkvo"].report.padding_entries / sparse2["qkvo"].report.nnz, 4),
+    }
+    log(f"layer, 4 grouped launches, 2-bit codes: {two_bit}")
+    del gs2, sparse2
+    torch.cuda.empty_cache()
 
     # ---- per-shape numbers (cold rotation over the same copies) ---------------
     per_shape = {}
@@ -624,6 +643,7 @@ def main():
         "per_shape": per_shape,
         "separate_launches": single,
         "one_launch_independent_products": one_launch,
+        "two_bit_codes": two_bit,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
