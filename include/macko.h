@@ -208,6 +208,9 @@ MACKO_API int macko_last_hip_error(void);
  *   "spmv_resident"     0 auto, 1 never, 2 always: launch exactly one resident round of
  *                       workgroups (a multiple of the compute-unit count) shaped to the row counts
  *   "spmv_wgs_per_cu"   workgroups per compute unit of such a round (1..4), 0 auto
+ *   "spmv_resident_steps"  largest launch, in wavefront steps (512 entries) per compute unit,
+ *                       that "spmv_resident" = 0 runs as one resident round, 0 default
+ *   "spmv_steps_per_wave"  larger launches: steps of work per wavefront, 0 default
  *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8), "gemv_resident",
  *   "gemv_wgs_per_cu"   the same for the dense GEMV
  * Settings are process wide and not thread safe. */

@@ -335,7 +335,11 @@ int set_lds_limit(K kernel, int64_t bytes) {
 
 constexpr int64_t kMaxLdsBytes = 160 * 1024 - 64;   // 160 KB per CU minus the static row counter
 // launches with at most this many wavefront steps per compute unit run as one resident round
-constexpr int64_t kResidentStepsPerCu = 768;
+// (the resident round won by 3-7 % up to ~340 steps and lost by 3-10 % from ~500 steps on,
+// measured on 31 matrix shapes and the grouped launches of two decoder-layer shapes)
+constexpr int64_t kResidentStepsPerCu = 448;
+// many-workgroup regime: steps of work per wavefront (whole rows; at least one row)
+constexpr int64_t kStepsPerWave = 8;
 // rows of at least this many stored entries on average take the wave-per-row kernel (a step
 // covers 512 entries; below about 40 % use of a step the sub-wave kernel wins: measured
 // crossover between 133 and 247 entries per row on 36864 x 12288 at 98-99 % sparsity)
@@ -459,16 +463,20 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
   // resident round of a single large workgroup per compute unit whatever their
   // size: every workgroup stages its own copy of x, and the fewer copies are made
   // the better (4-8 % measured on the 18944 .. 49152 column shapes).
-  const bool small = total_steps <= (int64_t)cus * kResidentStepsPerCu;
+  const int64_t resident_steps = t.spmv_resident_steps ? t.spmv_resident_steps : kResidentStepsPerCu;
+  const bool small = total_steps <= (int64_t)cus * resident_steps;
   const bool wide = max_lds >= kWideLdsBytes;
   if (t.spmv_rows_per_wg == 0 && (t.spmv_resident == 2 || (t.spmv_resident == 0 && (small || wide)))) {
     const int k = t.spmv_wgs_per_cu ? (int)t.spmv_wgs_per_cu : (wide ? 1 : 0);
     planned = plan_resident(plan, nwr, in, cus, (int)t.spmv_block, k);
   }
   if (!planned) {
-    // Plenty of work: many workgroups, about 16 steps per wavefront (short rows:
+    // Plenty of work: many workgroups, about 8 steps per wavefront (short rows:
     // several rows per wavefront), but never so few workgroups that the launch
-    // has under ~16 wavefronts per compute unit.  Every workgroup holds its own
+    // has under ~16 wavefronts per compute unit.  Workgroups go to the eight XCDs in
+    // turn whatever their load, and what a compute unit is still working on when the
+    // others have finished is lost: 16 steps per wavefront measured 3-9 % slower on
+    // launches of 30-70 us, fewer than 6 slower again on short rows.  Every workgroup holds its own
     // copy of x in LDS; when that copy is large (more than ~24 K columns) only
     // one to three fit a compute unit, so each brings 16 wavefronts instead of 8.
     const int block = t.spmv_block ? (int)t.spmv_block : (max_lds > 48 * 1024 ? 1024 : 512);
@@ -479,7 +487,8 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
     for (int i = 0; i < nwr; ++i) {
       rpw[i] = t.spmv_rows_per_wg;
       if (rpw[i] == 0) {
-        const int64_t want = (16 + in[i].steps_per_row - 1) / in[i].steps_per_row;
+        const int64_t target = t.spmv_steps_per_wave ? t.spmv_steps_per_wave : kStepsPerWave;
+        const int64_t want = std::max<int64_t>(1, (2 * target + in[i].steps_per_row) / (2 * in[i].steps_per_row));  // nearest
         const int64_t cap = std::max<int64_t>(1, group_rows / ((int64_t)cus * 16));
         rpw[i] = std::min(want, cap) * nwaves;
       }

@@ -25,7 +25,7 @@ def _need_gpu_and_library():
     M.load_library()          # raises if libmacko.so is missing: no fallback
     yield
     for knob in ("spmv_kernel", "spmv_lanes", "spmv_block", "spmv_rows_per_wg", "spmv_ring", "spmv_resident",
-                 "spmv_wgs_per_cu", "gemv_block", "gemv_rows_per_wg", "gemv_ring", "gemv_resident",
+                 "spmv_wgs_per_cu", "spmv_resident_steps", "spmv_steps_per_wave", "gemv_block", "gemv_rows_per_wg", "gemv_ring", "gemv_resident",
                  "gemv_wgs_per_cu"):
         M.set_tuning(knob, 0)
 
@@ -134,6 +134,8 @@ RESIDENT_VARIANTS = {
     "k2_b704": {"spmv_resident": 2, "spmv_wgs_per_cu": 2, "spmv_block": 704},
     "many_wgs_r40_b256": {"spmv_resident": 1, "spmv_rows_per_wg": 40, "spmv_block": 256},
     "many_wgs_r63_b64": {"spmv_resident": 1, "spmv_rows_per_wg": 63, "spmv_block": 64},
+    "many_wgs_steps3": {"spmv_resident_steps": 1, "spmv_steps_per_wave": 3},
+    "many_wgs_steps40": {"spmv_resident_steps": 1, "spmv_steps_per_wave": 40, "spmv_block": 192},
 }
 
 
