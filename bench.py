@@ -163,7 +163,9 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="also time the 36864x12288 sparsity sweep")
     ap.add_argument("--stack", action="store_true", help="also time the Llama2-13B-shaped 32-layer stack")
     ap.add_argument("--shapes", action="store_true",
-                    help="also time every shape of the paper's Appendix D at 50 %% sparsity")
+                    help="also time every shape of the paper's Appendix D (see --shapes-sparsity)")
+    ap.add_argument("--shapes-sparsity", default="50", metavar="LIST",
+                    help="sparsity levels in per cent for --shapes, comma separated (default 50)")
     ap.add_argument("--spmm", action="store_true", help="also time the small-batch product macko_spmm")
     ap.add_argument("--adversarial", action="store_true",
                     help="also time the two 8192x8192 padding stress matrices (configs[3])")
@@ -521,26 +523,29 @@ def main():
             del Wd
         extra["spmm_small_batch"] = table
 
-    # ---- optional: every shape of Appendix D at 50 % --------------------------
+    # ---- optional: every shape of Appendix D, at 50 % and at the other levels asked for ----
     if args.shapes:
-        table = {}
-        for (r, c) in wl.APPENDIX_D_SHAPES:
-            case = wl.appendix_d_case(r, c, 50)
-            nb = int(2.5 * r * c * 0.5)
-            so = SparseOp(M, torch, case, copies=copies_for(nb, 1 << 30))
-            do = DenseOp(M, torch, case, copies=copies_for(2 * r * c, 1 << 30))
-            n = 200 if nb < (100 << 20) else 40
-            ts = time_single_op(torch, so, stream_ptr, 10, n)
-            td = time_single_op(torch, do, stream_ptr, 10, n)
-            table[f"{r}x{c}"] = {"macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
-                                 "macko_GBps": round(so.bytes / ts / 1e9), "dense_GBps": round(do.bytes / td / 1e9),
-                                 "speedup_vs_dense": round(td / ts, 3)}
-            log(f"  appendix D {r}x{c}: {table[f'{r}x{c}']}")
-            del so, do, case
-            torch.cuda.empty_cache()
-        sp = sorted(v["speedup_vs_dense"] for v in table.values())
-        extra["appendix_d_shapes_s50"] = {"shapes": table, "speedup_min": sp[0], "speedup_median": sp[len(sp) // 2],
-                                          "speedup_max": sp[-1]}
+        levels = sorted({int(v) for v in args.shapes_sparsity.split(",") if v.strip()})
+        for pct in levels:
+            table = {}
+            for (r, c) in wl.APPENDIX_D_SHAPES:
+                case = wl.appendix_d_case(r, c, pct)
+                nb = int(2.5 * r * c * (1 - pct / 100.0))
+                so = SparseOp(M, torch, case, copies=copies_for(nb, 1 << 30))
+                do = DenseOp(M, torch, case, copies=copies_for(2 * r * c, 1 << 30))
+                n = 200 if nb < (100 << 20) else 40
+                ts = time_single_op(torch, so, stream_ptr, 10, n)
+                td = time_single_op(torch, do, stream_ptr, 10, n)
+                table[f"{r}x{c}"] = {"macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
+                                     "macko_GBps": round(so.bytes / ts / 1e9), "dense_GBps": round(do.bytes / td / 1e9),
+                                     "speedup_vs_dense": round(td / ts, 3)}
+                log(f"  appendix D {r}x{c} @ {pct} %: {table[f'{r}x{c}']}")
+                del so, do, case
+                torch.cuda.empty_cache()
+            sp = sorted(v["speedup_vs_dense"] for v in table.values())
+            extra[f"appendix_d_shapes_s{pct}"] = {"shapes": table, "speedup_min": sp[0],
+                                                   "speedup_median": sp[len(sp) // 2], "speedup_max": sp[-1]}
+            log(f"  appendix D @ {pct} %: speedup min {sp[0]} median {sp[len(sp) // 2]} max {sp[-1]}")
 
     # ---- optional: Llama2-13B-shaped 32-layer stack ---------------------------
     if args.stack:
