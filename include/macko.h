@@ -149,6 +149,27 @@ MACKO_API int macko_fetch_device(macko_handle_t h, uint16_t* values_host, uint8_
  * lossless; -0 inputs come back as +0). */
 MACKO_API int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld);
 
+/* ---- expanding the format on the device ----------------------------------- */
+
+/* Column index of every stored entry, computed on the device as the product
+ * computes it (Section 4.4: the running sum of a row's deltas, formed per lane
+ * and across the wavefront as in Algorithm 1).  Together with the values
+ * array and the row pointers this is the matrix in CSR form, padding entries
+ * included as explicit zeros at the column where they sit.
+ * cols_dev: int32[alloc_nnz] on the device, 4-byte aligned, caller owned;
+ * entries [0, pad_nnz) are written, the tail is left untouched.  The handle
+ * must be bound.  Only enqueues on `stream`. */
+MACKO_API int macko_columns_device(macko_handle_t h, int32_t* cols_dev, void* stream);
+
+/* The dense rows x cols fp16 matrix back from the bound device arrays (the
+ * format is lossless, Section 5.2; -0 inputs come back as +0).
+ * dense_dev: fp16 [rows x ld] on the device, ld >= cols elements, 2-byte
+ * aligned (16-byte aligned with ld and cols multiples of 8 for the fast zero
+ * fill), caller owned, must not overlap the format arrays.  Cells [r][0, cols)
+ * are overwritten, cells between cols and ld are left untouched.  Enqueues two
+ * kernels on `stream` and does not synchronise. */
+MACKO_API int macko_decode_device(macko_handle_t h, void* dense_dev, int64_t ld, void* stream);
+
 /* ---- the product (Section 4.4; Y = M V of Appendix A) --------------------- */
 
 /* y[r] = sum_k values[k] * x[column(k)] over row r's entries, fp32

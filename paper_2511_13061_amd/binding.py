@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
     "macko_wrap_device_ex", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -97,6 +97,8 @@ def load_library():
     lib.macko_host_buffers.argtypes = [vp, hp, hp, hp]
     lib.macko_fetch_device.argtypes = [vp, vp, vp, vp]
     lib.macko_decode.argtypes = [vp, vp, i64]
+    lib.macko_columns_device.argtypes = [vp, vp, vp]
+    lib.macko_decode_device.argtypes = [vp, vp, i64, vp]
     lib.macko_spmv.argtypes = [vp, vp, vp, vp]
     lib.macko_dense_gemv.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     vpp = ctypes.POINTER(vp)
@@ -250,6 +252,28 @@ class MackoMatrix:
         out = np.empty((rep.rows, rep.cols), dtype=np.uint16)
         _check(load_library().macko_decode(self._h, out.ctypes.data, rep.cols), "macko_decode")
         return out
+
+    def columns_device(self, cols_dev=None, stream=None):
+        """macko_columns_device: int32 column index of every stored entry (torch CUDA tensor [alloc_nnz])."""
+        import torch
+        rep = self.get_report()
+        if cols_dev is None:
+            cols_dev = torch.full((max(int(rep.alloc_nnz), 1),), -1, dtype=torch.int32, device="cuda")
+        _check(load_library().macko_columns_device(self._h, _dev_ptr(cols_dev), _stream_ptr(stream)),
+               "macko_columns_device")
+        return cols_dev
+
+    def decode_device(self, dense_dev=None, stream=None):
+        """macko_decode_device: the dense fp16 matrix back, as a torch CUDA tensor [rows, cols]."""
+        import torch
+        if dense_dev is None:
+            dense_dev = torch.empty((self.rows, self.cols), dtype=torch.float16, device="cuda")
+        if dense_dev.dim() != 2 or (dense_dev.shape[1] > 1 and dense_dev.stride(1) != 1):
+            raise ValueError("dense_dev must be a row-major [rows, >= cols] tensor")
+        ld = dense_dev.stride(0) if dense_dev.shape[0] > 1 else max(dense_dev.shape[1], 1)
+        _check(load_library().macko_decode_device(self._h, _dev_ptr(dense_dev), ld, _stream_ptr(stream)),
+               "macko_decode_device")
+        return dense_dev
 
     def spmv(self, x_dev, y_dev=None, stream=None):
         """y = W x.  x_dev: torch float16 CUDA tensor [cols]; returns y_dev [rows]."""

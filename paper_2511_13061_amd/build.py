@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmacko.so")
-SOURCES = ["macko_host.cpp", "macko_spmv.hip", "macko_gemv.hip", "macko_encode_gpu.hip", "macko_spmm.hip"]
+SOURCES = ["macko_host.cpp", "macko_spmv.hip", "macko_gemv.hip", "macko_encode_gpu.hip", "macko_spmm.hip", "macko_decode_gpu.hip"]
 HEADERS = ["macko_internal.h", "macko_device.h", "macko_plan.h", "macko_decode.h"]
 
 HIPCC_FLAGS = [

@@ -8,7 +8,7 @@ namespace macko {
 
 // ---------------------------------------------------------------------------
 // Codes of a lane's 8 consecutive entries and the positions they decode to, for
-// code widths of 2, 4 and 8 bits.  All positions are doubled (bytes of the LDS
+// code widths of 1, 2, 4 and 8 bits (the product kernels use 2, 4 and 8).  All positions are doubled (bytes of the LDS
 // copy of x) and include the +1 per entry, i.e. entry k advances by 2 code + 2.
 //   load(deltas, chunk)  the 2 / 4 / 8 bytes of chunk `chunk` (8 entries)
 //   clear()              all codes 0 (every entry one column after the other)
@@ -67,6 +67,27 @@ template <>
 struct LaneCodes<2> : LaneCodesBytes<2> {
   __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
     w = reinterpret_cast<const uint16_t*>(deltas)[chunk];
+  }
+};
+
+// 1-bit codes: a prefix is a population count of the low bits.
+template <>
+struct LaneCodes<1> {
+  uint32_t w;           // the 8 codes, entry k in bit k
+  __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
+    w = reinterpret_cast<const uint8_t*>(deltas)[chunk];
+  }
+  __device__ __forceinline__ void clear() { w = 0u; }
+  __device__ __forceinline__ void keep_if(bool c) { w = c ? w : 0u; }
+  __device__ __forceinline__ void decode() {}
+  __device__ __forceinline__ uint32_t total() const { return 2u * (uint32_t)__builtin_popcount(w) + 16u; }
+  template <int K>
+  __device__ __forceinline__ int offset() const {
+    return 2 * __builtin_popcount(w & ((2u << K) - 1u)) + 2 * K;
+  }
+  __device__ __forceinline__ uint32_t through(int k) const {
+    const uint32_t s = __builtin_amdgcn_readfirstlane(w);
+    return 2u * (uint32_t)__builtin_popcount(s & ((2u << k) - 1u)) + 2u * (uint32_t)(k + 1);
   }
 };
 

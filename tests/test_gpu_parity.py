@@ -602,3 +602,97 @@ def test_config5_llama2_13b_layer_shapes_full_size():
         check_y(y, case.W, case.x, case.name)
         handles.append(m); xs.append(to_dev(case.x)); singles.append(y)
     grouped_like_the_bench(handles, xs, singles)
+
+
+# ------------------------------------------------------------------ expanding the format on the device
+
+EXPAND_CASES = dict(WIDTH_CASES)
+EXPAND_CASES["empty_rows_257x1500"] = lambda: (_with_empty_rows(wl.bernoulli(257, 1500, 0.4, 0.02, 61, 1)),
+                                                wl.x_vector(1500, 61, 1))
+EXPAND_CASES["first_nonzero_late_64x5000"] = lambda: (_late_start(wl.bernoulli(64, 5000, 0.6, 0.02, 61, 2)),
+                                                       wl.x_vector(5000, 61, 2))
+
+
+def _with_empty_rows(W):
+    W[0] = 0
+    W[100:131] = 0
+    W[-1] = 0
+    return W
+
+
+def _late_start(W):
+    W[:, :3000] = 0            # every row starts with padding entries only
+    W[5, :] = 0
+    W[5, 4999] = 0x3C00        # a row whose only non-zero is in the last column
+    return W
+
+
+@pytest.mark.parametrize("b_delta", [1, 2, 4, 8])
+@pytest.mark.parametrize("case", list(EXPAND_CASES))
+def test_columns_on_the_device_equal_the_oracles(case, b_delta):
+    """Index reconstruction (Section 4.4, Alg. 1) in isolation: the column index of every stored
+    entry, formed with the decode and the wavefront prefix sum the product uses, bit for bit."""
+    W, _ = EXPAND_CASES[case]()
+    enc = oracle.encode(W, b_delta)
+    _, want = oracle.unpack(enc)
+    m = M.encode(W, b_delta).to_device()
+    got = m.columns_device()
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert got.shape[0] == max(enc.alloc_nnz, 1)
+    assert np.array_equal(got[: enc.pad_nnz], want)
+    assert (got[enc.pad_nnz:] == -1).all()                 # the tail is not touched
+
+
+@pytest.mark.parametrize("b_delta", [1, 2, 4, 8])
+@pytest.mark.parametrize("case", list(EXPAND_CASES))
+def test_decode_on_the_device_round_trips_exactly(case, b_delta):
+    W, _ = EXPAND_CASES[case]()
+    want = oracle.decode(oracle.encode(W, b_delta))
+    m = M.encode_device(to_dev(W), b_delta=b_delta)       # device encoder -> device decoder
+    back = m.decode_device()
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy().view(np.uint16), want)
+    # into a wider, unaligned buffer: cells beyond cols keep their contents
+    rows, cols = W.shape
+    buf = torch.full((rows, cols + 5), 7.0, dtype=torch.float16, device="cuda")
+    view = buf[:, 1: 1 + cols]
+    rc = M.load_library().macko_decode_device(m._h, view.data_ptr(), buf.stride(0), 0)
+    assert rc == 0
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy().view(np.uint16)
+    assert np.array_equal(host[:, 1: 1 + cols], want)
+    assert (host[:, 0] == 0x4700).all() and (host[:, 1 + cols:] == 0x4700).all()
+
+
+def test_expand_special_values_errors_and_full_size():
+    W = wl.bernoulli(130, 900, 0.5, 0.02, 62, 1)
+    W[3, 10:20] = [0x7C00, 0xFC00, 0x7E00, 0x0001, 0x8001, 0x8000, 0x0000, 0x7BFF, 0xFBFF, 0x03FF]
+    m = M.encode(W).to_device()
+    back = m.decode_device()
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy().view(np.uint16), oracle.decode(oracle.encode(W)))
+    lib = M.load_library()
+    unbound = M.encode(W)
+    rc = lib.macko_decode_device(unbound._h, back.data_ptr(), 900, 0)
+    assert rc < 0 and "no device buffers" in M.status_string(rc)
+    assert lib.macko_decode_device(m._h, back.data_ptr(), 899, 0) < 0          # ld < cols
+    assert lib.macko_decode_device(m._h, 0, 900, 0) < 0
+    assert lib.macko_columns_device(m._h, 0, 0) < 0
+    assert lib.macko_columns_device(unbound._h, back.data_ptr(), 0) < 0
+    # all-zero and zero-sized matrices
+    z = M.encode(np.zeros((5, 64), dtype=np.uint16)).to_device()
+    out = torch.full((5, 64), 3.0, dtype=torch.float16, device="cuda")
+    z.decode_device(out)
+    torch.cuda.synchronize()
+    assert (out == 0).all()
+    assert (z.columns_device().cpu().numpy() == -1).all()
+    # one decoder-layer shape at full size, both ways
+    case = list(wl.config2())[1]
+    enc = oracle.encode(case.W)
+    g = M.encode_device(to_dev(case.W))
+    cols = g.columns_device()
+    dense = g.decode_device()
+    torch.cuda.synchronize()
+    assert np.array_equal(cols.cpu().numpy()[: enc.pad_nnz], oracle.unpack(enc)[1])
+    assert np.array_equal(dense.cpu().numpy().view(np.uint16), oracle.decode(enc))
