@@ -20,7 +20,7 @@ namespace {
 // ---------------------------------------------------------------------------
 // Generic kernel: LANES (16, 32 or 64) lanes cooperate on a row, so a wavefront
 // works on 64/LANES rows at once.  Every entry is individually masked against
-// the row bounds.  Used for short rows, for 1-bit codes, and as the fallback
+// the row bounds.  Used for short rows and as the fallback
 // when x does not fit in LDS (XLDS = false gathers x from global memory).
 // ---------------------------------------------------------------------------
 // The BD-bit codes of the 8 entries of chunk `chunk`, entry k in bits [BD k, BD (k+1)).
@@ -534,6 +534,7 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
     if (min_steps >= 8) ring = 4;
   }
   switch (b_delta) {
+    case 1: return launch_wave_row_bd<1>(args, head, nwr, plan, max_lds, simple, ring, stream);
     case 2: return launch_wave_row_bd<2>(args, head, nwr, plan, max_lds, simple, ring, stream);
     case 4: return launch_wave_row_bd<4>(args, head, nwr, plan, max_lds, simple, ring, stream);
     case 8: return launch_wave_row_bd<8>(args, head, nwr, plan, max_lds, simple, ring, stream);
@@ -548,7 +549,6 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   const Tuning& t = tuning();
   auto wants_wave_row = [&](const SpmvProblem& p) {
     if (p.rows == 0 || p.pad_nnz == 0) return false;
-    if (p.b_delta == 1) return false;                   // 1-bit codes: the generic kernel only
     if (lds_bytes_for(p.cols, p.b_delta) > kMaxLdsBytes) return false;
     if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
     return p.pad_nnz / p.rows >= kWaveRowMinEntries;
@@ -570,7 +570,7 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
     }
   }
   // one grouped launch per code width
-  for (int bd : {4, 2, 8}) {
+  for (int bd : {4, 2, 8, 1}) {
     const SpmvProblem* wr[kMaxGroup];
     int nwr = 0;
     for (int i = 0; i < n; ++i)

@@ -287,7 +287,7 @@ WIDTH_CASES = {
 @pytest.mark.parametrize("b_delta", [1, 2, 8])
 @pytest.mark.parametrize("case", list(WIDTH_CASES))
 def test_spmv_other_code_widths(case, b_delta, variant):
-    """1-, 2- and 8-bit codes: same product, same tolerance (1-bit codes always take the generic kernel)."""
+    """1-, 2- and 8-bit codes: same product, same tolerance, on both kernels."""
     W, x = WIDTH_CASES[case]()
     y = spmv_case(W, x, b_delta, **VARIANTS[variant])
     check_y(y, W, x, f"{case}/b{b_delta}/{variant}")
