@@ -45,42 +45,85 @@ __device__ __forceinline__ void unpack_x<8>(const uint4& v, float* out) {
 
 // Copy X (batch vectors of `cols` fp16, vector b at X + b*ldx) into LDS, interleaved
 // by column, between zero guards of front_pad*BT and back_pad*BT bytes.  Vectors
-// b >= batch are filled with zeros.  Ends with a barrier.
+// b >= batch are filled with zeros.  In two parts, so that the kernel can send its
+// first streaming loads between them: begin() only issues the global loads of the
+// thread's first 8 columns into registers; finish() writes them to LDS, copies the
+// rest, clears the guards and ends with a barrier.  Both are called by every thread.
 template <int BT>
-__device__ __forceinline__ void stage_X_interleaved(unsigned char* lds, const uint16_t* __restrict__ X,
-                                                    int64_t ldx, int batch, int cols, int front_pad, int back_pad) {
-  const int tid = threadIdx.x, nt = blockDim.x;
-  const int chunks = (cols + 7) >> 3;
-  const bool vec_ok = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && (ldx & 7) == 0;
-  uint4* lds16 = reinterpret_cast<uint4*>(lds);
-  const uint4 zero = make_uint4(0, 0, 0, 0);
-  const int front16 = front_pad * BT / 16, back16 = back_pad * BT / 16, body16 = chunks * BT;   // 16-byte units
-  for (int i = tid; i < front16 + back16; i += nt) lds16[i < front16 ? i : i + body16] = zero;
-  uint16_t* xs = reinterpret_cast<uint16_t*>(lds + front_pad * BT);
-  for (int t = tid; t < chunks; t += nt) {
-    uint16_t h[BT][8];
+struct XStageBatch {
+  uint32_t u[BT][4];      // vector b, the thread's first 8 columns, two per word
+
+  // 16-byte loads, all issued together (a vector past the batch re-reads vector 0 and is cleared)
+  static __device__ __forceinline__ void load_fast(uint32_t (&u)[BT][4], const uint16_t* __restrict__ X, int64_t ldx,
+                                                   int batch, int t) {
+#pragma unroll
+    for (int b = 0; b < BT; ++b) {
+      const uint4 q = *reinterpret_cast<const uint4*>(X + (int64_t)(b < batch ? b : 0) * ldx + 8 * t);
+      u[b][0] = q.x; u[b][1] = q.y; u[b][2] = q.z; u[b][3] = q.w;
+    }
+#pragma unroll
+    for (int b = 0; b < BT; ++b)
+      if (b >= batch) u[b][0] = u[b][1] = u[b][2] = u[b][3] = 0u;
+  }
+  static __device__ __forceinline__ void load_slow(uint32_t (&u)[BT][4], const uint16_t* __restrict__ X, int64_t ldx,
+                                                   int batch, int cols, int t) {
 #pragma unroll
     for (int b = 0; b < BT; ++b) {
       const uint16_t* src = X + (int64_t)b * ldx + 8 * t;
-      if (b < batch && vec_ok && 8 * t + 8 <= cols) {
-        const uint4 q = *reinterpret_cast<const uint4*>(src);
-        const uint32_t u[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-        for (int k = 0; k < 8; ++k) h[b][k] = (uint16_t)(u[k >> 1] >> (16 * (k & 1)));
-      } else {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) h[b][k] = (b < batch && 8 * t + k < cols) ? src[k] : (uint16_t)0;
+      for (int k = 0; k < 8; k += 2) {
+        const uint32_t lo = (b < batch && 8 * t + k < cols) ? src[k] : 0u;
+        const uint32_t hi = (b < batch && 8 * t + k + 1 < cols) ? src[k + 1] : 0u;
+        u[b][k >> 1] = lo | (hi << 16);
       }
     }
+  }
+  // column 8t+k of vectors b, b+1 -> one word; the BT values of a column are adjacent in LDS
+  static __device__ __forceinline__ void store(const uint32_t (&u)[BT][4], uint16_t* xs, int t) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      uint32_t* dst = reinterpret_cast<uint32_t*>(xs + (size_t)(8 * t + k) * BT);
+      uint32_t out[BT / 2];
 #pragma unroll
-      for (int b = 0; b < BT; b += 2) dst[b >> 1] = (uint32_t)h[b][k] | ((uint32_t)h[b + 1][k] << 16);
+      for (int b = 0; b < BT; b += 2) {
+        const uint32_t lo = u[b][k >> 1], hi = u[b + 1][k >> 1];
+        out[b >> 1] = (k & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+      }
+      unsigned char* dst = reinterpret_cast<unsigned char*>(xs + (size_t)(8 * t + k) * BT);
+      if (BT == 8) *reinterpret_cast<uint4*>(dst) = make_uint4(out[0], out[1], out[2 % (BT / 2)], out[3 % (BT / 2)]);
+      else if (BT == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(out[0], out[1 % (BT / 2)]);
+      else *reinterpret_cast<uint32_t*>(dst) = out[0];
     }
   }
-  __syncthreads();
-}
+
+  __device__ __forceinline__ void begin(const uint16_t* __restrict__ X, int64_t ldx, int batch, int cols) {
+    const int t = threadIdx.x;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && (ldx & 7) == 0;
+    if (vec_ok && 8 * t + 8 <= cols) load_fast(u, X, ldx, batch, t);
+  }
+
+  __device__ __forceinline__ void finish(unsigned char* lds, const uint16_t* __restrict__ X, int64_t ldx, int batch,
+                                         int cols, int front_pad, int back_pad) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int chunks = (cols + 7) >> 3;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(X) & 15) == 0 && (ldx & 7) == 0;
+    uint4* lds16 = reinterpret_cast<uint4*>(lds);
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const int front16 = front_pad * BT / 16, back16 = back_pad * BT / 16, body16 = chunks * BT;   // 16-byte units
+    for (int i = tid; i < front16 + back16; i += nt) lds16[i < front16 ? i : i + body16] = zero;
+    uint16_t* xs = reinterpret_cast<uint16_t*>(lds + front_pad * BT);
+    if (tid < chunks) {
+      if (!(vec_ok && 8 * tid + 8 <= cols)) load_slow(u, X, ldx, batch, cols, tid);   // else begin() loaded it
+      store(u, xs, tid);
+    }
+    for (int t = tid + nt; t < chunks; t += nt) {
+      uint32_t v[BT][4];
+      if (vec_ok && 8 * t + 8 <= cols) load_fast(v, X, ldx, batch, t);
+      else load_slow(v, X, ldx, batch, cols, t);
+      store(v, xs, t);
+    }
+    __syncthreads();
+  }
+};
 
 template <int BT, int BD>
 __global__ void __launch_bounds__(1024)
@@ -112,6 +155,10 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
   const int r = min(blk + lane, rows - 1);             // unconditional loads, clamped to the last row
   const uint32_t rp_lo = row_ptr[r];
   const uint32_t rp_hi = row_ptr[r + 1];
+  // start-up order as in the matrix-vector kernel: row pointers and activations are requested
+  // together, the first streaming loads follow, and only then are the activations written to LDS
+  XStageBatch<BT> xst;
+  xst.begin(X, ldx, batch, cols);
 
   auto issue = [&](int j) {
     if (ld.i < nb) {
@@ -132,7 +179,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
   cp = ld;
 #pragma unroll
   for (int j = 0; j < RING; ++j) issue(j);
-  stage_X_interleaved<BT>(lds, X, ldx, batch, cols, front_pad_for(BD), back_pad_for(BD));    // ends with a barrier
+  xst.finish(lds, X, ldx, batch, cols, front_pad_for(BD), back_pad_for(BD));    // ends with a barrier
 
   float yv[BT], acc[BT];
 #pragma unroll
@@ -181,10 +228,10 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
       issue(j);
       base2 += (int)__builtin_amdgcn_readlane((int)incl, 63);
       if (live && ++cp.step == cp.nsteps) {
+        wave_sum_to_last_lane_n<BT>(acc);                // the BT sums side by side
 #pragma unroll
         for (int b = 0; b < BT; ++b) {
-          const float total = wave_sum_to_last_lane(acc[b]);
-          const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), 63);
+          const int tbits = __builtin_amdgcn_readlane(__builtin_bit_cast(int, acc[b]), 63);
           yv[b] = lane == cp.i ? __builtin_bit_cast(float, tbits) : yv[b];
           acc[b] = 0.0f;
         }
