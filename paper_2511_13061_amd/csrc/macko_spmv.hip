@@ -527,8 +527,10 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
   // Ring depth: two steps in flight per wavefront, except in a resident round of at most 16
   // wavefronts per compute unit working on long rows (4096 x 11008: one row of 11 steps per
   // wavefront), where two steps leave the memory system short of requests: four there (6 %).
+  // Not for the wide matrices (one 16-wavefront workgroup per compute unit, rows of 20-48
+  // steps): measured 3-7 % slower with four on the seven shapes of 18944 columns and more.
   int ring = (int)t.spmv_ring;
-  if (ring == 0 && planned && plan.total_wgs * nwaves <= (int64_t)cus * 16) {
+  if (ring == 0 && planned && !wide && plan.total_wgs * nwaves <= (int64_t)cus * 16) {
     int64_t min_steps = in[0].steps_per_row;
     for (int i = 1; i < nwr; ++i) min_steps = std::min(min_steps, in[i].steps_per_row);
     if (min_steps >= 8) ring = 4;
