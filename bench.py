@@ -196,11 +196,16 @@ def main():
 
     if args.probe_sweep is not None:
         case = wl.config3(args.probe_sweep)
-        so = SparseOp(M, torch, case, copies=2)
+        nb = int(2.5 * case.rows * case.cols * (1 - args.probe_sweep / 100.0))
+        nc = copies_for(nb, 1 << 30)                    # rotate over >= 1 GiB so that no launch finds its matrix cached
+        so = SparseOp(M, torch, case, copies=nc)
         do = DenseOp(M, torch, case, copies=2)
-        ts = time_single_op(torch, so, stream_ptr, 2, 8)
+        ts = time_single_op(torch, so, stream_ptr, nc, 4 * nc)
         td = time_single_op(torch, do, stream_ptr, 2, 8)
-        log(f"probe-sweep {args.probe_sweep}%: spmv {ts * 1e6:.1f} us, dense gemv {td * 1e6:.1f} us (10 launches each)")
+        log(f"probe-sweep {args.probe_sweep}%: spmv {ts * 1e6:.1f} us ({5 * nc} launches over {nc} copies, "
+            f"{so.bytes} bytes each), dense gemv {td * 1e6:.1f} us (10 launches)")
+        print(json.dumps({"probe_sweep": args.probe_sweep, "spmv_us": round(ts * 1e6, 2), "spmv_bytes": int(so.bytes),
+                          "spmv_launches": 5 * nc, "gemv_us": round(td * 1e6, 2), "gemv_bytes": int(do.bytes)}))
         return
 
     # ---- workload: one Llama2-7B-shaped layer at 50 % ------------------------
