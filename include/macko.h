@@ -53,7 +53,8 @@ typedef enum macko_status {
   MACKO_E_UNSUPPORTED = -3,   /* shape or option this build has no kernel for               */
   MACKO_E_OUT_OF_MEMORY = -4, /* host or device allocation failed                           */
   MACKO_E_NOT_BOUND = -5,     /* device operation on a handle that has no device buffers    */
-  MACKO_E_HIP = -6            /* a HIP call failed; see macko_last_hip_error()              */
+  MACKO_E_HIP = -6,           /* a HIP call failed; see macko_last_hip_error()              */
+  MACKO_E_CORRUPT = -7        /* macko_check_device: the bound arrays are not a valid encoding */
 } macko_status;
 
 /* Opaque encoded matrix.  Created by the encode / wrap calls, released by
@@ -148,6 +149,17 @@ MACKO_API int macko_fetch_device(macko_handle_t h, uint16_t* values_host, uint8_
 /* Decode the host copy back to a dense rows x cols fp16 matrix (the format is
  * lossless; -0 inputs come back as +0). */
 MACKO_API int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld);
+
+/* Check, on the device, what the kernels take on trust about bound arrays
+ * (meant for macko_wrap_device: a loaded checkpoint, a copy made elsewhere):
+ * row_ptr[0] == 0, row_ptr never decreases, row_ptr[rows] == pad_nnz, and no
+ * entry decodes to a column >= cols (Section 4.1: a column is the sum of the
+ * row's deltas).  Returns MACKO_OK, or MACKO_E_CORRUPT with the smallest
+ * offending row in *first_bad_row (may be NULL).  Rows with bad pointers are
+ * reported without being decoded, so the check reads nothing outside the
+ * arrays' pad_nnz entries and rows + 1 pointers.  Synchronises `stream`;
+ * allocates and frees 4 bytes of device memory. */
+MACKO_API int macko_check_device(macko_handle_t h, void* stream, int64_t* first_bad_row);
 
 /* ---- expanding the format on the device ----------------------------------- */
 

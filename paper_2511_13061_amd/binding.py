@@ -16,9 +16,12 @@ EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
     "macko_wrap_device_ex", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
+
+
+MACKO_E_CORRUPT = -7
 
 
 class MackoError(RuntimeError):
@@ -98,6 +101,7 @@ def load_library():
     lib.macko_fetch_device.argtypes = [vp, vp, vp, vp]
     lib.macko_decode.argtypes = [vp, vp, i64]
     lib.macko_columns_device.argtypes = [vp, vp, vp]
+    lib.macko_check_device.argtypes = [vp, vp, i64p]
     lib.macko_decode_device.argtypes = [vp, vp, i64, vp]
     lib.macko_spmv.argtypes = [vp, vp, vp, vp]
     lib.macko_dense_gemv.argtypes = [vp, i64, i64, i64, vp, vp, vp]
@@ -252,6 +256,15 @@ class MackoMatrix:
         out = np.empty((rep.rows, rep.cols), dtype=np.uint16)
         _check(load_library().macko_decode(self._h, out.ctypes.data, rep.cols), "macko_decode")
         return out
+
+    def check_device(self, stream=None):
+        """macko_check_device: None if the bound arrays are a consistent encoding, else the first bad row."""
+        bad = ctypes.c_int64(-1)
+        st = load_library().macko_check_device(self._h, _stream_ptr(stream), ctypes.byref(bad))
+        if st == MACKO_E_CORRUPT:
+            return int(bad.value)
+        _check(st, "macko_check_device")
+        return None
 
     def columns_device(self, cols_dev=None, stream=None):
         """macko_columns_device: int32 column index of every stored entry (torch CUDA tensor [alloc_nnz])."""

@@ -72,6 +72,60 @@ expand_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ del
   }
 }
 
+// What the product kernels take on trust about an encoding, checked row by row:
+// row_ptr starts at 0, never decreases and ends at pad_nnz, and no entry decodes
+// to a column at or beyond cols.  The smallest offending row number is left in
+// *first_bad (which the caller sets to `rows` beforehand).  A row whose pointers
+// are out of order or out of range is reported without being decoded, so the
+// check itself reads nothing outside [0, pad_nnz).
+template <int BD>
+__global__ void __launch_bounds__(kExpandBlock)
+check_kernel(const uint32_t* __restrict__ deltas, const uint32_t* __restrict__ row_ptr, const int rows,
+             const int cols, const uint32_t pad_nnz, unsigned int* __restrict__ first_bad) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kExpandBlock / 64) + (threadIdx.x >> 6)));
+  const int nwaves = (int)gridDim.x * (kExpandBlock / 64);
+  for (int row = wave; row < rows; row += nwaves) {          // wavefront-uniform
+    const uint32_t start = (uint32_t)__builtin_amdgcn_readfirstlane((int)row_ptr[row]);
+    const uint32_t end = (uint32_t)__builtin_amdgcn_readfirstlane((int)row_ptr[row + 1]);
+    bool bad = end < start || end > pad_nnz || (row == 0 && start != 0u) || (row == rows - 1 && end != pad_nnz);
+    if (!bad && end > start) {
+      const uint32_t a0 = start & ~7u;
+      const int nsteps = (int)((end - a0 + 511u) >> 9);
+      int base2 = 0;
+      bool lane_bad = false;
+      for (int step = 0; step < nsteps; ++step) {
+        const uint32_t e0 = a0 + 512u * (uint32_t)step + 8u * (uint32_t)lane;
+        const uint32_t chunk = min(e0, end - 1u) >> 3;
+        LaneCodes<BD> w;
+        w.load(deltas, chunk);
+        w.keep_if(e0 < end);
+        w.decode();
+        const uint32_t tot = w.total();
+        const uint32_t incl = wave_incl_scan_u32(tot);
+        if (step == 0) {
+          const int before = (int)(start - a0);
+          if (before > 0) base2 = -(int)w.through(before - 1);
+        }
+        const int lanebase = base2 + (int)(incl - tot);
+#define MACKO_ENTRY(k)                                                                    \
+  {                                                                                       \
+    const uint32_t e = e0 + k;                                                            \
+    if (e >= start && e < end && ((lanebase + w.template offset<k>()) >> 1) >= cols) lane_bad = true; \
+  }
+        MACKO_ENTRY(0) MACKO_ENTRY(1) MACKO_ENTRY(2) MACKO_ENTRY(3)
+        MACKO_ENTRY(4) MACKO_ENTRY(5) MACKO_ENTRY(6) MACKO_ENTRY(7)
+#undef MACKO_ENTRY
+        base2 += (int)__builtin_amdgcn_readlane((int)incl, 63);
+        // a row that runs past the last column keeps running: stop before the positions overflow
+        if (__any(lane_bad)) break;
+      }
+      bad = __any(lane_bad);
+    }
+    if (bad && lane == 0) atomicMin(first_bad, (unsigned int)row);
+  }
+}
+
 // dense[r][0 .. cols) = +0 for every row (cells between cols and ld are left alone)
 template <bool VEC>
 __global__ void __launch_bounds__(256) zero_rows_kernel(uint16_t* __restrict__ dense, const int rows, const int cols,
@@ -117,6 +171,34 @@ int launch_expand(const SpmvProblem& p, int32_t* cols_out, uint16_t* dense, int6
 }
 
 }  // namespace
+
+int launch_check(const SpmvProblem& p, unsigned int* first_bad, hipStream_t stream) {
+  const int64_t waves_wanted = std::min<int64_t>(p.rows, (int64_t)device_cu_count() * 64);
+  const dim3 grid((unsigned)((waves_wanted + kExpandBlock / 64 - 1) / (kExpandBlock / 64))), block(kExpandBlock);
+  const uint32_t* deltas = reinterpret_cast<const uint32_t*>(p.deltas);
+  switch (p.b_delta) {
+    case 1:
+      hipLaunchKernelGGL(check_kernel<1>, grid, block, 0, stream, deltas, p.row_ptr, (int)p.rows, (int)p.cols,
+                         (uint32_t)p.pad_nnz, first_bad);
+      break;
+    case 2:
+      hipLaunchKernelGGL(check_kernel<2>, grid, block, 0, stream, deltas, p.row_ptr, (int)p.rows, (int)p.cols,
+                         (uint32_t)p.pad_nnz, first_bad);
+      break;
+    case 4:
+      hipLaunchKernelGGL(check_kernel<4>, grid, block, 0, stream, deltas, p.row_ptr, (int)p.rows, (int)p.cols,
+                         (uint32_t)p.pad_nnz, first_bad);
+      break;
+    case 8:
+      hipLaunchKernelGGL(check_kernel<8>, grid, block, 0, stream, deltas, p.row_ptr, (int)p.rows, (int)p.cols,
+                         (uint32_t)p.pad_nnz, first_bad);
+      break;
+    default:
+      return MACKO_E_UNSUPPORTED;
+  }
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
 
 int launch_columns(const SpmvProblem& p, int32_t* cols_out, hipStream_t stream) {
   if (p.rows == 0 || p.pad_nnz == 0) return MACKO_OK;

@@ -385,6 +385,36 @@ static int check_vec_ptrs(const void* x_dev, const void* y_dev, int64_t cols) {
   return MACKO_OK;
 }
 
+int macko_check_device(macko_handle_t h, void* stream, int64_t* first_bad_row) {
+  if (!h) return MACKO_E_INVALID_ARG;
+  if (!h->bound) return MACKO_E_NOT_BOUND;
+  if (first_bad_row) *first_bad_row = -1;
+  if (h->rows == 0) return h->pad_nnz == 0 ? MACKO_OK : MACKO_E_CORRUPT;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned int* d_first = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&d_first), sizeof(unsigned int));
+  if (e != hipSuccess) return e == hipErrorOutOfMemory ? MACKO_E_OUT_OF_MEMORY : macko::hip_fail(e);
+  unsigned int first = (unsigned int)h->rows;
+  int st = MACKO_OK;
+  e = hipMemcpyAsync(d_first, &first, sizeof(first), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) {
+    const macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
+                               nullptr, nullptr, h->b_delta};
+    st = macko::launch_check(p, d_first, s);
+    if (st == MACKO_OK) e = hipMemcpyAsync(&first, d_first, sizeof(first), hipMemcpyDeviceToHost, s);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(s);     // also on a failed launch: nothing may still use d_first
+  else (void)hipStreamSynchronize(s);
+  (void)hipFree(d_first);
+  if (st != MACKO_OK) return st;
+  if (e != hipSuccess) return macko::hip_fail(e);
+  if (first < (unsigned int)h->rows) {
+    if (first_bad_row) *first_bad_row = (int64_t)first;
+    return MACKO_E_CORRUPT;
+  }
+  return MACKO_OK;
+}
+
 int macko_columns_device(macko_handle_t h, int32_t* cols_dev, void* stream) {
   if (!h) return MACKO_E_INVALID_ARG;
   if (!h->bound) return MACKO_E_NOT_BOUND;
@@ -480,6 +510,7 @@ const char* macko_status_string(int status) {
     case MACKO_E_OUT_OF_MEMORY: return "out of memory";
     case MACKO_E_NOT_BOUND: return "handle has no device buffers";
     case MACKO_E_HIP: return "HIP error";
+    case MACKO_E_CORRUPT: return "the device arrays are not a valid encoding";
     default: return "unknown status";
   }
 }

@@ -696,3 +696,53 @@ def test_expand_special_values_errors_and_full_size():
     torch.cuda.synchronize()
     assert np.array_equal(cols.cpu().numpy()[: enc.pad_nnz], oracle.unpack(enc)[1])
     assert np.array_equal(dense.cpu().numpy().view(np.uint16), oracle.decode(enc))
+
+
+# ------------------------------------------------------------------ checking adopted device arrays
+
+@pytest.mark.parametrize("b_delta", [1, 2, 4, 8])
+def test_check_device_accepts_valid_encodings_and_names_the_first_bad_row(b_delta):
+    """Mistakes are planted in host copies of a valid encoding (made by the oracle), the copies are
+    adopted with macko_wrap_device, and macko_check_device must name the first row that is wrong.
+    No planted mistake makes a kernel read outside the arrays: bad pointers are reported undecoded."""
+    rows, cols = 300, 2100
+    W = wl.bernoulli(rows, cols, 0.4, 0.02, 71, b_delta)
+    W[17] = 0
+    W[299, cols - 1] = 0x3C00                                  # the last row reaches the last column
+    enc = oracle.encode(W, b_delta)
+
+    def wrapped(values, deltas, row_ptr, pad_nnz=None, ncols=cols):
+        v = torch.from_numpy(values.copy()).cuda()
+        d = torch.from_numpy(deltas.copy()).cuda()
+        r = torch.from_numpy(row_ptr.astype(np.int64).astype(np.uint32).view(np.int32).copy()).cuda()
+        return M.wrap_device(rows, ncols, enc.pad_nnz if pad_nnz is None else pad_nnz, v, d, r, b_delta)
+
+    assert wrapped(enc.values, enc.deltas, enc.row_ptr).check_device() is None
+    assert M.encode(W, b_delta).to_device().check_device() is None
+    assert M.encode_device(to_dev(W), b_delta=b_delta).check_device() is None
+
+    # one column too few: exactly the rows that reach the last column are wrong (row 299 does; find the first)
+    _, colidx = oracle.unpack(enc)
+    reach = [r for r in range(rows) if enc.row_ptr[r + 1] > enc.row_ptr[r] and colidx[enc.row_ptr[r + 1] - 1] == cols - 1]
+    assert wrapped(enc.values, enc.deltas, enc.row_ptr, ncols=cols - 1).check_device() == reach[0]
+
+    rp = enc.row_ptr.astype(np.int64)
+    bad = rp.copy(); bad[0] = 8
+    assert wrapped(enc.values, enc.deltas, bad).check_device() == 0                 # does not start at 0
+    assert rp[119] > 0
+    bad = rp.copy(); bad[120] = rp[119] - 1
+    assert wrapped(enc.values, enc.deltas, bad).check_device() == 119              # decreasing
+    bad = rp.copy(); bad[200] = enc.pad_nnz + 4096
+    assert wrapped(enc.values, enc.deltas, bad).check_device() == 199              # beyond the arrays
+    bad = rp.copy(); bad[rows] = enc.pad_nnz - 1
+    assert wrapped(enc.values, enc.deltas, bad, pad_nnz=enc.pad_nnz).check_device() == rows - 1   # does not end at pad_nnz
+    # a row boundary moved forward by a few entries: the row above it now decodes entries of the next row
+    # and, being long enough, runs past the last column
+    bad = rp.copy(); bad[51] = rp[53]
+    got = wrapped(enc.values, enc.deltas, bad).check_device()
+    assert got in (50, 51, 52)
+    # all-zero and empty
+    z = M.encode(np.zeros((4, 16), dtype=np.uint16), b_delta).to_device()
+    assert z.check_device() is None
+    lib = M.load_library()
+    assert lib.macko_check_device(M.encode(W, b_delta)._h, 0, None) < 0             # not bound
