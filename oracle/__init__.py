@@ -71,6 +71,18 @@ def _load():
     lib.oracle_spmv.restype = None
     lib.oracle_dense_matvec.argtypes = [u16p, i64, i64, i64, u16p, f64p, f64p]
     lib.oracle_dense_matvec.restype = None
+    lib.oracle_fp8_to_double_array.argtypes = [u8p, f64p, i64]
+    lib.oracle_fp8_to_double_array.restype = None
+    lib.oracle_count_entries8.argtypes = [u8p, i64, i64, i64, ci, i64p]
+    lib.oracle_count_entries8.restype = i64
+    lib.oracle_encode8.argtypes = [u8p, i64, i64, i64, ci, u8p, u8p, u32p, i64]
+    lib.oracle_encode8.restype = i64
+    lib.oracle_decode8.argtypes = [u8p, u8p, u32p, i64, i64, ci, u8p, i64]
+    lib.oracle_decode8.restype = i64
+    lib.oracle_spmv8.argtypes = [u8p, u8p, u32p, i64, i64, ci, u16p, f64p, f64p]
+    lib.oracle_spmv8.restype = None
+    lib.oracle_dense_matvec8.argtypes = [u8p, i64, i64, i64, u16p, f64p, f64p]
+    lib.oracle_dense_matvec8.restype = None
     lib.oracle_max_threads.argtypes = []
     lib.oracle_max_threads.restype = ci
     lib.oracle_set_threads.argtypes = [ci]
@@ -112,9 +124,10 @@ class Encoded:
     nnz: int
     pad_nnz: int
     alloc_nnz: int
-    values: np.ndarray     # uint16[alloc_nnz], fp16 bits
+    values: np.ndarray     # uint16[alloc_nnz], fp16 bits (uint8[alloc_nnz], E4M3 bits, when b_val == 8)
     deltas: np.ndarray     # uint8[alloc_nnz * b_delta / 8], packed codes (delta - 1)
     row_ptr: np.ndarray    # uint32[rows + 1], entry indices
+    b_val: int = 16        # bits per value
 
     @property
     def padding_entries(self) -> int:
@@ -122,7 +135,7 @@ class Encoded:
 
     @property
     def values_bytes(self) -> int:
-        return 2 * self.alloc_nnz
+        return self.alloc_nnz * self.b_val // 8
 
     @property
     def deltas_bytes(self) -> int:
@@ -138,7 +151,7 @@ class Encoded:
 
     @property
     def dense_bytes(self) -> int:
-        return 2 * self.rows * self.cols
+        return self.rows * self.cols * self.b_val // 8
 
     @property
     def effd(self) -> float:
@@ -239,6 +252,81 @@ def dense_matvec(dense, x):
     s = np.empty(W.shape[0], dtype=np.float64)
     _load().oracle_dense_matvec(_p(W, ctypes.c_uint16), W.shape[0], W.shape[1], W.shape[1],
                                 _p(xv, ctypes.c_uint16), _p(y, ctypes.c_double), _p(s, ctypes.c_double))
+    return y, s
+
+
+# ---- 8-bit values (OCP E4M3 bit patterns, one byte per element) ----------------
+
+def _as_u8_matrix(dense) -> np.ndarray:
+    a = np.asarray(dense)
+    if a.dtype != np.uint8 or a.ndim != 2:
+        raise TypeError("dense must be a 2-D uint8 array of E4M3 bit patterns")
+    return np.ascontiguousarray(a)
+
+
+def fp8_to_double(b) -> np.ndarray:
+    a = np.ascontiguousarray(b, dtype=np.uint8)
+    out = np.empty(a.shape, dtype=np.float64)
+    _load().oracle_fp8_to_double_array(_p(a, ctypes.c_uint8), _p(out, ctypes.c_double), a.size)
+    return out
+
+
+def encode8(dense, b_delta: int = 4) -> Encoded:
+    """Dense matrix of 8-bit values -> MACKO buffers with one byte per stored value."""
+    lib = _load()
+    W = _as_u8_matrix(dense)
+    R, C = W.shape
+    nnz = ctypes.c_int64(0)
+    pad_nnz = lib.oracle_count_entries8(_p(W, ctypes.c_uint8), R, C, C, b_delta, ctypes.byref(nnz))
+    if pad_nnz < 0:
+        raise ValueError("bad arguments")
+    g = alloc_granule(b_delta)
+    alloc = (pad_nnz + g - 1) // g * g
+    values = np.zeros(max(alloc, 1), dtype=np.uint8)[:alloc]
+    deltas = np.zeros(max(alloc * b_delta // 8, 1), dtype=np.uint8)[: alloc * b_delta // 8]
+    row_ptr = np.zeros(R + 1, dtype=np.uint32)
+    got = lib.oracle_encode8(_p(W, ctypes.c_uint8), R, C, C, b_delta, _p(values, ctypes.c_uint8),
+                             _p(deltas, ctypes.c_uint8), _p(row_ptr, ctypes.c_uint32), alloc)
+    if got == -2:
+        raise OverflowError("entry index does not fit the 32-bit row pointers")
+    if got != pad_nnz:
+        raise RuntimeError("oracle encoder: count and fill disagree")
+    return Encoded(R, C, b_delta, int(nnz.value), int(pad_nnz), int(alloc), values, deltas, row_ptr, 8)
+
+
+def decode8(enc: Encoded) -> np.ndarray:
+    out = np.empty((enc.rows, enc.cols), dtype=np.uint8)
+    rc = _load().oracle_decode8(_p(enc.values, ctypes.c_uint8), _p(enc.deltas, ctypes.c_uint8),
+                                _p(enc.row_ptr, ctypes.c_uint32), enc.rows, enc.cols, enc.b_delta,
+                                _p(out, ctypes.c_uint8), enc.cols)
+    if rc != 0:
+        raise ValueError(f"row {-rc - 1} decodes past the last column")
+    return out
+
+
+def spmv8(enc: Encoded, x):
+    """(y64, abs64) from the format buffers with 8-bit values."""
+    xv = _as_u16_vector(x)
+    if xv.size != enc.cols or enc.b_val != 8:
+        raise ValueError("x has the wrong length or the encoding does not hold 8-bit values")
+    y = np.empty(enc.rows, dtype=np.float64)
+    s = np.empty(enc.rows, dtype=np.float64)
+    _load().oracle_spmv8(_p(enc.values, ctypes.c_uint8), _p(enc.deltas, ctypes.c_uint8),
+                         _p(enc.row_ptr, ctypes.c_uint32), enc.rows, enc.cols, enc.b_delta,
+                         _p(xv, ctypes.c_uint16), _p(y, ctypes.c_double), _p(s, ctypes.c_double))
+    return y, s
+
+
+def dense_matvec8(dense, x):
+    """(y64, abs64): y_i = sum_j W_ij x_j by definition, 8-bit W, fp16 x, fp64 arithmetic."""
+    W = _as_u8_matrix(dense)
+    xv = _as_u16_vector(x)
+    if xv.size != W.shape[1]:
+        raise ValueError("x has the wrong length")
+    y = np.empty(W.shape[0], dtype=np.float64)
+    s = np.empty(W.shape[0], dtype=np.float64)
+    _load().oracle_dense_matvec8(_p(W, ctypes.c_uint8), W.shape[0], W.shape[1], W.shape[1],
+                                 _p(xv, ctypes.c_uint16), _p(y, ctypes.c_double), _p(s, ctypes.c_double))
     return y, s
 
 

@@ -35,7 +35,10 @@
  *
  * Parity pins (tests/test_oracle_*.py): the worked example of Section 4.1,
  * eqs. 8-10, exact round trip, brute force over all masks of a short row,
- * numpy's fp16 conversion and fp64 matmul.
+ * numpy's fp16 conversion and fp64 matmul.  The 8-bit-value functions at the
+ * end are pinned by tests/test_oracle_fp8.py (the 256 values against their
+ * closed form and a library conversion, the coordinates against the pinned
+ * 16-bit encoder, round trip, numpy fp64 matmul).
  */
 #include <math.h>
 #include <stdint.h>
@@ -267,6 +270,136 @@ ORACLE_API void oracle_dense_matvec(const uint16_t* dense, int64_t R, int64_t C,
     double acc = 0.0, mag = 0.0;
     for (int64_t c = 0; c < C; ++c) {
       double p = oracle_half_to_double(dense[r * ld + c]) * oracle_half_to_double(x[c]);
+      acc += p;
+      mag += fabs(p);
+    }
+    y64[r] = acc;
+    if (abs64) abs64[r] = mag;
+  }
+}
+
+/* ==========================================================================
+ * 8-bit values.  The paper names b_val = 8 as a setting the format covers and
+ * leaves its kernel to future work (Section 6, "Limitations"; Section 7); it
+ * does not say what an 8-bit value is.  Reading taken here and in the library:
+ * the OCP 8-bit floating point format E4M3 (1 sign, 4 exponent bits with bias
+ * 7, 3 fraction bits; exponent 0 holds zero and the subnormals f * 2^-9; there
+ * are no infinities, and exponent 15 with fraction 7 is the only NaN, so the
+ * largest finite value is 1.75 * 2^8 = 448).  The format itself does not
+ * change: values holds one byte per stored entry, a padding entry holds +0
+ * (0x00), an element is a zero when its bits other than the sign are 0, and
+ * the coordinates, the row pointers and the tail padding (alloc_nnz = pad_nnz
+ * rounded up to 128 / b_delta entries) are exactly those of the 16-bit case.
+ * x and y stay fp16 and the product is still sum_j w_ij * x_j.
+ * ========================================================================== */
+
+static double oracle_fp8_to_double(uint8_t b) {
+  int sign = (b >> 7) & 1;
+  int exp = (b >> 3) & 0xF;
+  int frac = b & 7;
+  double v;
+  if (exp == 0)                      v = ldexp((double)frac, -9);            /* zero / subnormal */
+  else if (exp == 15 && frac == 7)   v = NAN;
+  else                               v = ldexp((double)(frac + 8), exp - 10); /* 1.frac * 2^(exp-7) */
+  return sign ? -v : v;
+}
+
+ORACLE_API void oracle_fp8_to_double_array(const uint8_t* in, double* out, int64_t n) {
+  for (int64_t i = 0; i < n; ++i) out[i] = oracle_fp8_to_double(in[i]);
+}
+
+ORACLE_API int64_t oracle_count_entries8(const uint8_t* dense, int64_t R, int64_t C, int64_t ld,
+                                         int b_delta, int64_t* nnz_out) {
+  if (!oracle_valid_b(b_delta) || R < 0 || C < 0 || ld < C) return -1;
+  const int64_t D = (int64_t)1 << b_delta;
+  int64_t e = 0, nnz = 0;
+  for (int64_t r = 0; r < R; ++r) {
+    int64_t prev = -1;
+    for (int64_t c = 0; c < C; ++c) {
+      if ((dense[r * ld + c] & 0x7Fu) == 0) continue;
+      int64_t gap = c - prev;
+      while (gap > D) { ++e; prev += D; gap -= D; }
+      ++e; ++nnz; prev = c;
+    }
+  }
+  if (nnz_out) *nnz_out = nnz;
+  return e;
+}
+
+/* As oracle_encode, with one byte per value. */
+ORACLE_API int64_t oracle_encode8(const uint8_t* dense, int64_t R, int64_t C, int64_t ld,
+                                  int b_delta, uint8_t* values, uint8_t* deltas,
+                                  uint32_t* row_ptr, int64_t alloc_nnz) {
+  if (!oracle_valid_b(b_delta) || R < 0 || C < 0 || ld < C) return -1;
+  if (alloc_nnz >= ((int64_t)1 << 32)) return -2;
+  const int64_t D = (int64_t)1 << b_delta;
+  memset(values, 0, (size_t)alloc_nnz);
+  memset(deltas, 0, (size_t)(alloc_nnz * b_delta / 8));
+  int64_t e = 0;
+  row_ptr[0] = 0;
+  for (int64_t r = 0; r < R; ++r) {
+    int64_t prev = -1;
+    for (int64_t c = 0; c < C; ++c) {
+      uint8_t w = dense[r * ld + c];
+      if ((w & 0x7Fu) == 0) continue;          /* +0 and -0 are zeros */
+      int64_t gap = c - prev;
+      while (gap > D) {                        /* padding entry at column prev + D */
+        if (e >= alloc_nnz) return -1;
+        values[e] = 0;
+        oracle_put_code(deltas, e, b_delta, (unsigned)(D - 1));
+        ++e; prev += D; gap -= D;
+      }
+      if (e >= alloc_nnz) return -1;
+      values[e] = w;
+      oracle_put_code(deltas, e, b_delta, (unsigned)(gap - 1));
+      ++e; prev = c;
+    }
+    row_ptr[r + 1] = (uint32_t)e;
+  }
+  return e;
+}
+
+ORACLE_API int64_t oracle_decode8(const uint8_t* values, const uint8_t* deltas,
+                                  const uint32_t* row_ptr, int64_t R, int64_t C, int b_delta,
+                                  uint8_t* dense, int64_t ld) {
+  for (int64_t r = 0; r < R; ++r) memset(dense + r * ld, 0, (size_t)C);
+  for (int64_t r = 0; r < R; ++r) {
+    int64_t col = -1;
+    for (int64_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {
+      col += (int64_t)oracle_get_code(deltas, k, b_delta) + 1;
+      if (col >= C) return -(r + 1);
+      dense[r * ld + col] = values[k];
+    }
+  }
+  return 0;
+}
+
+ORACLE_API void oracle_spmv8(const uint8_t* values, const uint8_t* deltas, const uint32_t* row_ptr,
+                             int64_t R, int64_t C, int b_delta, const uint16_t* x,
+                             double* y64, double* abs64) {
+  (void)C;
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t r = 0; r < R; ++r) {
+    double acc = 0.0, mag = 0.0;
+    int64_t col = -1;
+    for (int64_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {
+      col += (int64_t)oracle_get_code(deltas, k, b_delta) + 1;
+      double p = oracle_fp8_to_double(values[k]) * oracle_half_to_double(x[col]);
+      acc += p;
+      mag += fabs(p);
+    }
+    y64[r] = acc;
+    if (abs64) abs64[r] = mag;
+  }
+}
+
+ORACLE_API void oracle_dense_matvec8(const uint8_t* dense, int64_t R, int64_t C, int64_t ld,
+                                     const uint16_t* x, double* y64, double* abs64) {
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < R; ++r) {
+    double acc = 0.0, mag = 0.0;
+    for (int64_t c = 0; c < C; ++c) {
+      double p = oracle_fp8_to_double(dense[r * ld + c]) * oracle_half_to_double(x[c]);
       acc += p;
       mag += fabs(p);
     }

@@ -13,7 +13,7 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "macko_oracle.c")
-PIN_TESTS = ["tests/test_oracle_encoding.py", "tests/test_oracle_spmv.py"]
+PIN_TESTS = ["tests/test_oracle_encoding.py", "tests/test_oracle_spmv.py", "tests/test_oracle_fp8.py"]
 
 MUTANTS = {
     "first_delta_measured_from_column_0": ("int64_t prev = -1;", "int64_t prev = 0;"),
@@ -34,6 +34,12 @@ MUTANTS = {
     "dense_product_skips_last_column": ("for (int64_t c = 0; c < C; ++c) {\n      double p =", "for (int64_t c = 0; c + 1 < C; ++c) {\n      double p ="),
     "subnormal_scale_wrong": ("v = ldexp((double)frac, -24);", "v = ldexp((double)frac, -25);"),
     "half_rounding_truncates": ("double q = nearbyint(ldexp(m, 11));", "double q = floor(ldexp(m, 11));"),
+    "fp8_exponent_bias_off_by_one": ("v = ldexp((double)(frac + 8), exp - 10);", "v = ldexp((double)(frac + 8), exp - 9);"),
+    "fp8_subnormal_scale_wrong": ("v = ldexp((double)frac, -9);", "v = ldexp((double)frac, -10);"),
+    "fp8_top_binade_all_nan": ("else if (exp == 15 && frac == 7)   v = NAN;", "else if (exp == 15)   v = NAN;"),
+    "fp8_negative_zero_kept_as_nonzero": ("if ((w & 0x7Fu) == 0) continue;          /* +0 and -0 are zeros */",
+                                          "if (w == 0) continue;"),
+    "fp8_count_and_fill_disagree_on_zero": ("if ((dense[r * ld + c] & 0x7Fu) == 0) continue;", "if (dense[r * ld + c] == 0) continue;"),
     "decoder_starts_at_column_0": ("int64_t col = -1;\n    for (int64_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {\n      col += (int64_t)oracle_get_code(deltas, k, b_delta) + 1;\n      if (col >= C) return -(r + 1);",
                                    "int64_t col = 0;\n    for (int64_t k = row_ptr[r]; k < row_ptr[r + 1]; ++k) {\n      col += (int64_t)oracle_get_code(deltas, k, b_delta) + 1;\n      if (col >= C) return -(r + 1);"),
 }

@@ -205,3 +205,19 @@ def appendix_d_case(rows: int, cols: int, sparsity_pct: int = 50, seed: int = BA
     """One shape of the Appendix-D list with exactly (1 - s) * cols kept per row."""
     W = half_row_matrix(rows, cols, 7000 + (rows * 31 + cols) % 997, sparsity=sparsity_pct / 100.0, seed=seed)
     return Case(f"appD_{rows}x{cols}_s{sparsity_pct}", W, x_vector(cols, seed, 7000))
+
+
+def fp8_values_of(W16: np.ndarray, scale: float = 32.0) -> np.ndarray:
+    """The same matrix with 8-bit values: every fp16 element times `scale`, rounded to the OCP E4M3
+    format by the framework's own conversion (torch.float8_e4m3fn), as uint8 bit patterns.  With the
+    default scale a N(0, 0.02) matrix becomes N(0, 0.64), which E4M3 holds with its full 3-bit
+    fraction.  Elements that round to zero become zeros (about 0.1 % of the kept ones)."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(W16).view(np.float16)).to(torch.float32) * scale
+    return t.to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+
+
+def fp8_case(rows: int, cols: int, sparsity_pct: int = 50, seed: int = BASE_SEED) -> Case:
+    """A matrix of 8-bit values with about (1 - s) * cols kept per row, and an fp16 x."""
+    c = appendix_d_case(rows, cols, sparsity_pct, seed)
+    return Case(f"fp8_{rows}x{cols}_s{sparsity_pct}", fp8_values_of(c.W), c.x)
