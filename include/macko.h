@@ -136,6 +136,35 @@ MACKO_API int macko_device_bytes(macko_handle_t h, int64_t* values_bytes, int64_
 MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas_dev,
                                 void* rowptr_dev, void* stream);
 
+/* ---- 8-bit values ---------------------------------------------------------- */
+
+/* The format with b_val = 8: one byte per stored value instead of two (Section
+ * 4.1 defines the format for any b_val; Section 6 names 8-bit values as a
+ * setting whose kernel is left to future work, and does not say what an 8-bit
+ * value is).  Reading taken: a value is a number of the OCP 8-bit floating
+ * point format E4M3 (1 sign, 4 exponent, 3 fraction bits, bias 7, no
+ * infinities, S.1111.111 = NaN, largest finite value 448); scaling, if any, is
+ * the caller's (y can be scaled per row afterwards).  An element is a zero when
+ * its bits other than the sign are 0; padding entries hold 0x00.  Coordinates
+ * (4-bit codes), row pointers and tail padding are those of the 16-bit format.
+ *
+ * dense_host: uint8 [rows x ld] E4M3 bit patterns, row-major.  The handle
+ * behaves like any other: macko_device_bytes (values: alloc_nnz bytes),
+ * macko_bind_device, macko_fetch_device (values_host then receives bytes),
+ * macko_get_report (b_val = 8; effd and dense_bytes relative to a dense 8-bit
+ * matrix), macko_spmv / macko_spmv_group (x and y stay fp16, fp32
+ * accumulation; the wave-per-row kernel serves every row length; x must fit
+ * LDS, about 78 K columns, otherwise MACKO_E_UNSUPPORTED), macko_columns_device,
+ * macko_check_device.
+ * macko_spmm, macko_decode, macko_decode_device and macko_host_buffers'
+ * `values` are MACKO_E_UNSUPPORTED for such a handle. */
+MACKO_API int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
+                               macko_handle_t* out, macko_report_t* report);
+/* Host copy of the values of a macko_encode_fp8 handle (borrowed, alloc_nnz bytes). */
+MACKO_API int macko_host_values_fp8(macko_handle_t h, const uint8_t** values);
+/* Decode the host copy back to a dense rows x cols matrix of 8-bit values. */
+MACKO_API int macko_decode_fp8(macko_handle_t h, uint8_t* dense_host_out, int64_t ld);
+
 /* Borrowed pointers to the host arrays (valid until macko_destroy); any output
  * pointer may be NULL.  MACKO_E_UNSUPPORTED for handles without host copies. */
 MACKO_API int macko_host_buffers(macko_handle_t h, const uint16_t** values, const uint8_t** deltas,

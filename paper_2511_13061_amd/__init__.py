@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     dense_gemv_group,
     encode,
     encode_device,
+    encode_fp8,
     get_tuning,
     library_path,
     load_library,

@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
     "macko_wrap_device_ex", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_encode_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -101,6 +101,9 @@ def load_library():
     lib.macko_fetch_device.argtypes = [vp, vp, vp, vp]
     lib.macko_decode.argtypes = [vp, vp, i64]
     lib.macko_columns_device.argtypes = [vp, vp, vp]
+    lib.macko_encode_fp8.argtypes = [vp, i64, i64, i64, hp, rp]
+    lib.macko_host_values_fp8.argtypes = [vp, hp]
+    lib.macko_decode_fp8.argtypes = [vp, vp, i64]
     lib.macko_check_device.argtypes = [vp, vp, i64p]
     lib.macko_decode_device.argtypes = [vp, vp, i64, vp]
     lib.macko_spmv.argtypes = [vp, vp, vp, vp]
@@ -228,23 +231,28 @@ class MackoMatrix:
         return list(self._keep)
 
     def host_buffers(self):
-        """Copies of the host arrays as numpy (values u16, deltas u8, row_ptr u32)."""
+        """Copies of the host arrays as numpy (values u16, or u8 for 8-bit values; deltas u8, row_ptr u32)."""
         v, d, r = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
-        _check(load_library().macko_host_buffers(self._h, ctypes.byref(v), ctypes.byref(d), ctypes.byref(r)),
-               "macko_host_buffers")
         rep = self.get_report()
+        if rep.b_val == 8:
+            _check(load_library().macko_host_buffers(self._h, None, ctypes.byref(d), ctypes.byref(r)),
+                   "macko_host_buffers")
+            _check(load_library().macko_host_values_fp8(self._h, ctypes.byref(v)), "macko_host_values_fp8")
+        else:
+            _check(load_library().macko_host_buffers(self._h, ctypes.byref(v), ctypes.byref(d), ctypes.byref(r)),
+                   "macko_host_buffers")
         def grab(ptr, nbytes, dtype):
             if nbytes == 0:
                 return np.zeros(0, dtype=dtype)
             raw = (ctypes.c_uint8 * nbytes).from_address(ptr.value)
             return np.frombuffer(raw, dtype=dtype).copy()
-        return (grab(v, rep.values_bytes, np.uint16), grab(d, rep.deltas_bytes, np.uint8),
-                grab(r, rep.rowptr_bytes, np.uint32))
+        return (grab(v, rep.values_bytes, np.uint8 if rep.b_val == 8 else np.uint16),
+                grab(d, rep.deltas_bytes, np.uint8), grab(r, rep.rowptr_bytes, np.uint32))
 
     def fetch_device(self):
         """Device arrays copied back to numpy (values u16, deltas u8, row_ptr u32)."""
         vb, db, rb = self.device_bytes()
-        v = np.zeros(vb // 2, dtype=np.uint16)
+        v = np.zeros(vb, dtype=np.uint8) if self.get_report().b_val == 8 else np.zeros(vb // 2, dtype=np.uint16)
         d = np.zeros(db, dtype=np.uint8)
         r = np.zeros(rb // 4, dtype=np.uint32)
         _check(load_library().macko_fetch_device(self._h, v.ctypes.data, d.ctypes.data, r.ctypes.data),
@@ -253,6 +261,10 @@ class MackoMatrix:
 
     def decode(self) -> np.ndarray:
         rep = self.get_report()
+        if rep.b_val == 8:
+            out = np.empty((rep.rows, rep.cols), dtype=np.uint8)
+            _check(load_library().macko_decode_fp8(self._h, out.ctypes.data, rep.cols), "macko_decode_fp8")
+            return out
         out = np.empty((rep.rows, rep.cols), dtype=np.uint16)
         _check(load_library().macko_decode(self._h, out.ctypes.data, rep.cols), "macko_decode")
         return out
@@ -327,6 +339,21 @@ def encode(dense, b_delta: int = 4) -> MackoMatrix:
     else:
         _check(load_library().macko_encode_ex(a.ctypes.data, a.shape[0], a.shape[1], ld, int(b_delta),
                                               ctypes.byref(h), ctypes.byref(rep)), "macko_encode_ex")
+    return MackoMatrix(h.value, Report._from_c(rep))
+
+
+def encode_fp8(dense) -> MackoMatrix:
+    """macko_encode_fp8 on a host matrix of 8-bit values (numpy uint8, OCP E4M3 bit patterns)."""
+    a = np.asarray(dense)
+    if a.dtype != np.uint8 or a.ndim != 2:
+        raise TypeError("dense must be a 2-D uint8 array of E4M3 bit patterns")
+    if a.size and a.strides[1] != 1:
+        a = np.ascontiguousarray(a)
+    h = ctypes.c_void_p()
+    rep = _CReport()
+    ld = a.strides[0] if a.size else a.shape[1]
+    _check(load_library().macko_encode_fp8(a.ctypes.data, a.shape[0], a.shape[1], ld,
+                                           ctypes.byref(h), ctypes.byref(rep)), "macko_encode_fp8")
     return MackoMatrix(h.value, Report._from_c(rep))
 
 

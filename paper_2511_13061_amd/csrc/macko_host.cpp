@@ -43,7 +43,7 @@ int device_cu_count() {
 // Storage report: eq. 2 for the measured effective density, eqs. 8-10 for the
 // best / worst / expected cases at the measured density.
 void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, int64_t pad_nnz,
-                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries, int b_delta) {
+                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries, int b_delta, int b_val) {
   const double max_delta = static_cast<double>(1 << b_delta);
   std::memset(rep, 0, sizeof(*rep));
   rep->rows = rows;
@@ -54,22 +54,22 @@ void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, i
   rep->padding_entries = nnz >= 0 ? pad_nnz - nnz : -1;
   rep->empty_rows = empty_rows;
   rep->max_row_entries = max_row_entries;
-  rep->values_bytes = alloc_nnz * 2;
+  rep->values_bytes = alloc_nnz * b_val / 8;
   rep->deltas_bytes = alloc_nnz * b_delta / 8;
   rep->rowptr_bytes = 4 * (rows + 1);
   rep->total_bytes = rep->values_bytes + rep->deltas_bytes + rep->rowptr_bytes;
-  rep->dense_bytes = 2 * rows * cols;
-  rep->b_val = 16;
+  rep->dense_bytes = rows * cols * b_val / 8;
+  rep->b_val = b_val;
   rep->b_delta = b_delta;
   const double cells = static_cast<double>(rows) * static_cast<double>(cols);
   const double nan = std::numeric_limits<double>::quiet_NaN();
-  rep->effd = cells > 0 ? static_cast<double>(rep->total_bytes) / (2.0 * cells) : 0.0;
+  rep->effd = cells > 0 ? static_cast<double>(rep->total_bytes) / (cells * b_val / 8.0) : 0.0;
   if (nnz < 0 || cells <= 0) {
     rep->density = rep->effd_best = rep->effd_expected = rep->effd_worst = cells > 0 ? nan : 0.0;
     return;
   }
   const double d = static_cast<double>(nnz) / cells;
-  const double per_entry = (16.0 + b_delta) / 16.0;
+  const double per_entry = static_cast<double>(b_val + b_delta) / b_val;
   rep->density = d;
   rep->effd_best = d * per_entry;
   rep->effd_worst = (d + (1.0 - d) / max_delta) * per_entry;
@@ -80,6 +80,7 @@ void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, i
 namespace {
 
 inline bool is_nonzero(uint16_t bits) { return (bits & 0x7FFFu) != 0; }
+inline bool is_nonzero(uint8_t bits) { return (bits & 0x7Fu) != 0; }    // 8-bit values: everything but the sign
 
 template <class F>
 void parallel_blocks(int64_t n, F&& body) {
@@ -100,9 +101,14 @@ void parallel_blocks(int64_t n, F&& body) {
   for (auto& th : pool) th.join();
 }
 
+template <class T> std::vector<T>& values_of(macko_matrix* m);
+template <> inline std::vector<uint16_t>& values_of<uint16_t>(macko_matrix* m) { return m->h_values; }
+template <> inline std::vector<uint8_t>& values_of<uint8_t>(macko_matrix* m) { return m->h_values8; }
+
 // Stored entries of one row: a non-zero whose distance to the previously
 // stored column is g costs (g-1) / 2^b_delta padding entries plus itself.
-inline void count_row(const uint16_t* row, int64_t cols, int b_delta, int64_t* entries, int64_t* nnz) {
+template <class T>
+inline void count_row(const T* row, int64_t cols, int b_delta, int64_t* entries, int64_t* nnz) {
   int64_t prev = -1, e = 0, n = 0;
   for (int64_t c = 0; c < cols; ++c) {
     if (!is_nonzero(row[c])) continue;
@@ -116,11 +122,12 @@ inline void count_row(const uint16_t* row, int64_t cols, int b_delta, int64_t* e
 
 // Write one row's entries; codes go to a byte-per-entry scratch array that is
 // packed afterwards (two rows may share a byte of the packed array).
-inline void fill_row(const uint16_t* row, int64_t cols, int b_delta, uint16_t* values, uint8_t* codes) {
+template <class T>
+inline void fill_row(const T* row, int64_t cols, int b_delta, T* values, uint8_t* codes) {
   const int64_t full = (int64_t{1} << b_delta) - 1;   // code of the largest delta
   int64_t prev = -1, k = 0;
   for (int64_t c = 0; c < cols; ++c) {
-    const uint16_t w = row[c];
+    const T w = row[c];
     if (!is_nonzero(w)) continue;
     const int64_t g1 = c - prev - 1;          // gap - 1
     for (int64_t p = g1 >> b_delta; p > 0; --p) {
@@ -135,7 +142,10 @@ inline void fill_row(const uint16_t* row, int64_t cols, int b_delta, uint16_t* v
   }
 }
 
-int encode_host(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta, macko_matrix* m) {
+template <class T>
+int encode_host(const T* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta, macko_matrix* m) {
+  constexpr int b_val = 8 * (int)sizeof(T);
+  std::vector<T>& h_values = values_of<T>(m);
   std::vector<int64_t> entries(rows), nnzs(rows);
   parallel_blocks(rows, [&](int64_t lo, int64_t hi) {
     for (int64_t r = lo; r < hi; ++r) count_row(dense + r * ld, cols, b_delta, &entries[r], &nnzs[r]);
@@ -153,13 +163,13 @@ int encode_host(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, i
   const int64_t granule = alloc_granule(b_delta);
   const int64_t alloc = (pad_nnz + granule - 1) / granule * granule;
   if (alloc >= (int64_t{1} << 32)) return MACKO_E_OVERFLOW;
-  m->h_values.assign(alloc, 0);
+  h_values.assign(alloc, 0);
   m->h_deltas.assign(alloc * b_delta / 8, 0);
   std::vector<uint8_t> codes(alloc, 0);
   parallel_blocks(rows, [&](int64_t lo, int64_t hi) {
     for (int64_t r = lo; r < hi; ++r) {
       const int64_t at = m->h_row_ptr[r];
-      fill_row(dense + r * ld, cols, b_delta, m->h_values.data() + at, codes.data() + at);
+      fill_row(dense + r * ld, cols, b_delta, h_values.data() + at, codes.data() + at);
     }
   });
   // entry k occupies bits [k * b_delta, (k + 1) * b_delta) of the packed array (low bits first)
@@ -176,8 +186,9 @@ int encode_host(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, i
   m->pad_nnz = pad_nnz;
   m->alloc_nnz = alloc;
   m->b_delta = b_delta;
+  m->b_val = b_val;
   m->has_host = true;
-  fill_report(&m->report, rows, cols, nnz, pad_nnz, alloc, empty, longest, b_delta);
+  fill_report(&m->report, rows, cols, nnz, pad_nnz, alloc, empty, longest, b_delta, b_val);
   return MACKO_OK;
 }
 
@@ -205,6 +216,32 @@ int macko_encode_ex(const uint16_t* dense_host, int64_t rows, int64_t cols, int6
   try {
     m = new macko_matrix();
     int st = macko::encode_host(dense_host, rows, cols, ld, b_delta, m);
+    if (st != MACKO_OK) {
+      delete m;
+      return st;
+    }
+  } catch (const std::bad_alloc&) {
+    delete m;
+    return MACKO_E_OUT_OF_MEMORY;
+  } catch (...) {
+    delete m;
+    return MACKO_E_INVALID_ARG;
+  }
+  if (report) *report = m->report;
+  *out = m;
+  return MACKO_OK;
+}
+
+int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
+                     macko_handle_t* out, macko_report_t* report) {
+  if (out) *out = nullptr;
+  if (!out || rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
+  if (!dense_host && rows > 0 && cols > 0) return MACKO_E_INVALID_ARG;
+  if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  macko_matrix* m = nullptr;
+  try {
+    m = new macko_matrix();
+    int st = macko::encode_host(dense_host, rows, cols, ld, macko::kDeltaBits, m);
     if (st != MACKO_OK) {
       delete m;
       return st;
@@ -306,7 +343,7 @@ int macko_get_report(macko_handle_t h, macko_report_t* report) {
 int macko_device_bytes(macko_handle_t h, int64_t* values_bytes, int64_t* deltas_bytes,
                        int64_t* rowptr_bytes) {
   if (!h) return MACKO_E_INVALID_ARG;
-  if (values_bytes) *values_bytes = h->alloc_nnz * 2;
+  if (values_bytes) *values_bytes = h->alloc_nnz * h->b_val / 8;
   if (deltas_bytes) *deltas_bytes = h->alloc_nnz * h->b_delta / 8;
   if (rowptr_bytes) *rowptr_bytes = 4 * (h->rows + 1);
   return MACKO_OK;
@@ -322,7 +359,8 @@ int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas_dev, void
     return MACKO_E_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (h->alloc_nnz > 0) {
-    MACKO_HIP_TRY(hipMemcpyAsync(values_dev, h->h_values.data(), h->alloc_nnz * 2, hipMemcpyHostToDevice, s));
+    const void* hv = h->b_val == 8 ? static_cast<const void*>(h->h_values8.data()) : static_cast<const void*>(h->h_values.data());
+    MACKO_HIP_TRY(hipMemcpyAsync(values_dev, hv, h->alloc_nnz * h->b_val / 8, hipMemcpyHostToDevice, s));
     MACKO_HIP_TRY(hipMemcpyAsync(deltas_dev, h->h_deltas.data(), h->alloc_nnz * h->b_delta / 8, hipMemcpyHostToDevice, s));
   }
   MACKO_HIP_TRY(hipMemcpyAsync(rowptr_dev, h->h_row_ptr.data(), 4 * (h->rows + 1), hipMemcpyHostToDevice, s));
@@ -340,6 +378,7 @@ int macko_host_buffers(macko_handle_t h, const uint16_t** values, const uint8_t*
                        const uint32_t** row_ptr) {
   if (!h) return MACKO_E_INVALID_ARG;
   if (!h->has_host) return MACKO_E_UNSUPPORTED;
+  if (values && h->b_val != 16) return MACKO_E_UNSUPPORTED;     // 8-bit values: macko_host_values_fp8
   if (values) *values = h->h_values.data();
   if (deltas) *deltas = h->h_deltas.data();
   if (row_ptr) *row_ptr = h->h_row_ptr.data();
@@ -352,7 +391,7 @@ int macko_fetch_device(macko_handle_t h, uint16_t* values_host, uint8_t* deltas_
   if (!h->bound) return MACKO_E_NOT_BOUND;
   if (h->alloc_nnz > 0) {
     if (!values_host || !deltas_host) return MACKO_E_INVALID_ARG;
-    MACKO_HIP_TRY(hipMemcpy(values_host, h->d_values, h->alloc_nnz * 2, hipMemcpyDeviceToHost));
+    MACKO_HIP_TRY(hipMemcpy(values_host, h->d_values, h->alloc_nnz * h->b_val / 8, hipMemcpyDeviceToHost));
     MACKO_HIP_TRY(hipMemcpy(deltas_host, h->d_deltas, h->alloc_nnz * h->b_delta / 8, hipMemcpyDeviceToHost));
   }
   MACKO_HIP_TRY(hipMemcpy(rowptr_host, h->d_row_ptr, 4 * (h->rows + 1), hipMemcpyDeviceToHost));
@@ -361,7 +400,7 @@ int macko_fetch_device(macko_handle_t h, uint16_t* values_host, uint8_t* deltas_
 
 int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld) {
   if (!h || ld < h->cols) return MACKO_E_INVALID_ARG;
-  if (!h->has_host) return MACKO_E_UNSUPPORTED;
+  if (!h->has_host || h->b_val != 16) return MACKO_E_UNSUPPORTED;
   if (!dense_host_out && h->rows > 0 && h->cols > 0) return MACKO_E_INVALID_ARG;
   for (int64_t r = 0; r < h->rows; ++r) {
     uint16_t* row = dense_host_out + r * ld;
@@ -373,6 +412,32 @@ int macko_decode(macko_handle_t h, uint16_t* dense_host_out, int64_t ld) {
       pos += ((h->h_deltas[bit >> 3] >> (bit & 7)) & ((1u << b) - 1u)) + 1;
       if (pos > h->cols) return MACKO_E_INVALID_ARG;
       row[pos - 1] = h->h_values[k];
+    }
+  }
+  return MACKO_OK;
+}
+
+int macko_host_values_fp8(macko_handle_t h, const uint8_t** values) {
+  if (!h || !values) return MACKO_E_INVALID_ARG;
+  if (!h->has_host || h->b_val != 8) return MACKO_E_UNSUPPORTED;
+  *values = h->h_values8.data();
+  return MACKO_OK;
+}
+
+int macko_decode_fp8(macko_handle_t h, uint8_t* dense_host_out, int64_t ld) {
+  if (!h || ld < h->cols) return MACKO_E_INVALID_ARG;
+  if (!h->has_host || h->b_val != 8) return MACKO_E_UNSUPPORTED;
+  if (!dense_host_out && h->rows > 0 && h->cols > 0) return MACKO_E_INVALID_ARG;
+  for (int64_t r = 0; r < h->rows; ++r) {
+    uint8_t* row = dense_host_out + r * ld;
+    std::fill(row, row + h->cols, uint8_t{0});
+    int64_t pos = 0;  // column + 1 of the last decoded entry
+    const int b = h->b_delta;
+    for (int64_t k = h->h_row_ptr[r]; k < h->h_row_ptr[r + 1]; ++k) {
+      const int64_t bit = k * b;
+      pos += ((h->h_deltas[bit >> 3] >> (bit & 7)) & ((1u << b) - 1u)) + 1;
+      if (pos > h->cols) return MACKO_E_INVALID_ARG;
+      row[pos - 1] = h->h_values8[k];
     }
   }
   return MACKO_OK;
@@ -428,6 +493,7 @@ int macko_columns_device(macko_handle_t h, int32_t* cols_dev, void* stream) {
 int macko_decode_device(macko_handle_t h, void* dense_dev, int64_t ld, void* stream) {
   if (!h) return MACKO_E_INVALID_ARG;
   if (!h->bound) return MACKO_E_NOT_BOUND;
+  if (h->b_val != 16) return MACKO_E_UNSUPPORTED;
   if (h->rows == 0 || h->cols == 0) return MACKO_OK;
   if (!dense_dev || ld < h->cols || (reinterpret_cast<uintptr_t>(dense_dev) & 1)) return MACKO_E_INVALID_ARG;
   const macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
@@ -452,7 +518,7 @@ int macko_spmv_group(int n, const macko_handle_t* handles, const void* const* x_
     int st = check_vec_ptrs(x_dev[i], y_dev[i], h->cols);
     if (st != MACKO_OK) return st;
     p[m++] = macko::SpmvProblem{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
-                                x_dev[i], y_dev[i], h->b_delta};
+                                x_dev[i], y_dev[i], h->b_delta, h->b_val};
   }
   if (m == 0) return MACKO_OK;
   return macko::launch_spmv_group(m, p, static_cast<hipStream_t>(stream));
@@ -462,6 +528,7 @@ int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void
                void* stream) {
   if (!h || batch < 0 || batch > MACKO_MAX_BATCH) return MACKO_E_INVALID_ARG;
   if (!h->bound) return MACKO_E_NOT_BOUND;
+  if (h->b_val != 16) return MACKO_E_UNSUPPORTED;       // 8-bit values: the matrix-vector product only
   if (h->rows == 0 || batch == 0) return MACKO_OK;
   if (ldx < h->cols || ldy < h->rows) return MACKO_E_INVALID_ARG;
   int st = check_vec_ptrs(X_dev, Y_dev, h->cols);

@@ -53,6 +53,7 @@ struct SpmvProblem {
   const void* x;
   void* y;
   int b_delta = kDeltaBits;
+  int b_val = 16;           // bits per value: 16 (fp16) or 8 (E4M3)
 };
 struct GemvProblem {
   const void* W;
@@ -79,7 +80,7 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
                      int64_t* max_row_entries);
 
 void fill_report(macko_report_t* rep, int64_t rows, int64_t cols, int64_t nnz, int64_t pad_nnz,
-                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries, int b_delta);
+                 int64_t alloc_nnz, int64_t empty_rows, int64_t max_row_entries, int b_delta, int b_val = 16);
 
 }  // namespace macko
 
@@ -87,10 +88,12 @@ struct macko_matrix {
   int64_t rows = 0, cols = 0;
   int64_t pad_nnz = 0, alloc_nnz = 0;
   int b_delta = macko::kDeltaBits;
+  int b_val = 16;            // 16: fp16 values; 8: OCP E4M3 values (h_values8 holds the host copy)
   macko_report_t report{};
   // host copy (empty for device-encoded and wrapped handles)
   bool has_host = false;
   std::vector<uint16_t> h_values;
+  std::vector<uint8_t> h_values8;
   std::vector<uint8_t> h_deltas;
   std::vector<uint32_t> h_row_ptr;
   // device binding

@@ -135,10 +135,52 @@ __device__ __forceinline__ float gather_x(const unsigned char* xbase, int q) {
   return f16_bits_to_f32(*reinterpret_cast<const uint16_t*>(xbase + q));
 }
 
+// The 8 values of a lane's chunk, 16 or 8 bits each.  16-bit values are fp16 and feed
+// v_fma_mix_f32 directly; 8-bit values are OCP E4M3 numbers, converted two at a time
+// with the hardware conversion (v_cvt_pk_f32_fp8).
+template <int VB>
+struct LaneValues;
+template <>
+struct LaneValues<16> {
+  uint4 v;
+  __device__ __forceinline__ void load(const void* __restrict__ values, uint32_t chunk) {
+    v = static_cast<const uint4*>(values)[chunk];
+  }
+  __device__ __forceinline__ void keep_first(uint32_t nv) {       // clear the values of entries nv, nv+1, ...
+    v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
+    v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
+    v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
+    v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
+  }
+  template <int K>
+  __device__ __forceinline__ float get() const {
+    const uint32_t w = (K >> 1) == 0 ? v.x : ((K >> 1) == 1 ? v.y : ((K >> 1) == 2 ? v.z : v.w));
+    return f16_bits_to_f32((uint16_t)((K & 1) ? (w >> 16) : (w & 0xFFFFu)));
+  }
+};
+template <>
+struct LaneValues<8> {
+  uint2 v;
+  __device__ __forceinline__ void load(const void* __restrict__ values, uint32_t chunk) {
+    v = static_cast<const uint2*>(values)[chunk];
+  }
+  __device__ __forceinline__ void keep_first(uint32_t nv) {
+    const uint32_t lo = nv >= 4 ? 4u : nv, hi = nv >= 8 ? 4u : (nv > 4 ? nv - 4u : 0u);
+    v.x &= lo == 4 ? 0xFFFFFFFFu : ((1u << (8u * lo)) - 1u);
+    v.y &= hi == 4 ? 0xFFFFFFFFu : ((1u << (8u * hi)) - 1u);
+  }
+  template <int K>
+  __device__ __forceinline__ float get() const {
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const float2v p = __builtin_amdgcn_cvt_pk_f32_fp8((int)(K < 4 ? v.x : v.y), (K & 2) != 0);
+    return (K & 1) ? p.y : p.x;
+  }
+};
+
 // One matrix of a grouped launch.  Its rows are dealt out evenly over its
 // workgroups: q rows each, one more for the first r of them.
 struct SpmvMat {
-  const uint4* values;
+  const void* values;       // uint4 per chunk (16-bit values) or uint2 (8-bit values)
   const uint32_t* deltas;
   const uint32_t* row_ptr;
   const uint16_t* x;
@@ -161,8 +203,8 @@ struct SpmvGroupHeader {
 
 // The work of one workgroup: workgroup number `wg` of the matrix given by the
 // pointers, whose rows are dealt out q (+1 for the first r workgroups) at a time.
-template <int RING, bool SIMPLE, int BD>
-__device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ values,
+template <int RING, bool SIMPLE, int BD, int VB = 16>
+__device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ values,
                                                    const uint32_t* __restrict__ deltas,
                                                    const uint32_t* __restrict__ row_ptr,
                                                    const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
@@ -188,7 +230,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
   uint32_t rp_lo = 0, rp_hi = 0;
   RowCursor ld, cp;                                    // load side, compute side
   LaneCodes<BD> wq[RING];
-  uint4 vq[RING];
+  LaneValues<VB> vq[RING];
 
   auto issue = [&](int j) {
     if (ld.i < nb) {
@@ -201,7 +243,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
     }                  // else a padding item: every lane re-reads its previous chunk (a line it has just
                        // used; one fixed address would make every wavefront queue at the same L2 channel)
     wq[j].load(deltas, chunk);
-    vq[j] = values[chunk];
+    vq[j].load(values, chunk);
   };
   auto fetch_row_ptrs = [&]() {                        // unconditional loads, clamped to the last row
     const int r = min(blk + lane, rows - 1);
@@ -233,7 +275,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
 #pragma unroll
       for (int j = 0; j < RING; ++j) {
         LaneCodes<BD> w = wq[j];
-        uint4 v = vq[j];
+        LaneValues<VB> v = vq[j];
 
         const bool live = cp.i < nb;                   // false for the padding items after the last row
         if (!live) base2 = 0;                          // keep the (unused) gathers of padding items in range
@@ -242,10 +284,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
         if (!live || cp.step == cp.nsteps - 1) {       // clear what lies past the row end
           const uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;   // valid entries in this lane's chunk
           w.keep_if(nv != 0);
-          v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
-          v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
-          v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
-          v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
+          v.keep_first(nv);
         }
         w.decode();
         const uint32_t tot = w.total();                // doubled sum of this lane's 8 deltas
@@ -257,19 +296,15 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
         }
         const int lanebase = base2 + (int)(incl - tot);   // byte offset in x of the lane's chunk start
 #define MACKO_X(k) gather_x(xbase, lanebase + w.template offset<k>())
-#define MACKO_LO(u) f16_bits_to_f32((uint16_t)((u) & 0xFFFFu))
-#define MACKO_HI(u) f16_bits_to_f32((uint16_t)((u) >> 16))
-        acc = fmaf(MACKO_LO(v.x), MACKO_X(0), acc);
-        acc = fmaf(MACKO_HI(v.x), MACKO_X(1), acc);
-        acc = fmaf(MACKO_LO(v.y), MACKO_X(2), acc);
-        acc = fmaf(MACKO_HI(v.y), MACKO_X(3), acc);
-        acc = fmaf(MACKO_LO(v.z), MACKO_X(4), acc);
-        acc = fmaf(MACKO_HI(v.z), MACKO_X(5), acc);
-        acc = fmaf(MACKO_LO(v.w), MACKO_X(6), acc);
-        acc = fmaf(MACKO_HI(v.w), MACKO_X(7), acc);
+        acc = fmaf(v.template get<0>(), MACKO_X(0), acc);
+        acc = fmaf(v.template get<1>(), MACKO_X(1), acc);
+        acc = fmaf(v.template get<2>(), MACKO_X(2), acc);
+        acc = fmaf(v.template get<3>(), MACKO_X(3), acc);
+        acc = fmaf(v.template get<4>(), MACKO_X(4), acc);
+        acc = fmaf(v.template get<5>(), MACKO_X(5), acc);
+        acc = fmaf(v.template get<6>(), MACKO_X(6), acc);
+        acc = fmaf(v.template get<7>(), MACKO_X(7), acc);
 #undef MACKO_X
-#undef MACKO_LO
-#undef MACKO_HI
         issue(j);                                      // refill the slot just consumed, RING items ahead
         base2 += (int)__builtin_amdgcn_readlane((int)incl, 63);
         if (live && ++cp.step == cp.nsteps) {          // row finished: reduce, keep the result, next row
@@ -287,7 +322,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const uint4* __restrict__ val
 }
 
 // Grouped launch (matrices of one code width): the workgroup first finds its matrix.
-template <int RING, bool SIMPLE, int BD>
+template <int RING, bool SIMPLE, int BD, int VB = 16>
 __global__ void __launch_bounds__(1024)
 spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4, const int wb5, const int wb6,
                      const int wb7, const int inv_nwaves, const SpmvGroupArgs g) {
@@ -300,7 +335,7 @@ spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4,
     mi = in ? i : mi;
     wg0 = in ? wbs[i] : wg0;
   }
-  spmv_wave_row_body<RING, SIMPLE, BD>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
+  spmv_wave_row_body<RING, SIMPLE, BD, VB>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
                                        g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
                                        inv_nwaves);
 }
@@ -315,6 +350,17 @@ spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
                      const int inv_nwaves) {
   spmv_wave_row_body<RING, SIMPLE, BD>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
                                        inv_nwaves);
+}
+
+// One matrix with 8-bit values (4-bit codes): 8 bytes of values and 4 bytes of codes per lane and step.
+template <bool SIMPLE>
+__global__ void __launch_bounds__(1024)
+spmv_wave_row_fp8_kernel(const uint2* __restrict__ values, const uint32_t* __restrict__ deltas,
+                         const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
+                         uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
+                         const int inv_nwaves) {
+  spmv_wave_row_body<2, SIMPLE, 4, 8>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
+                                      inv_nwaves);
 }
 
 // y = 0 for a matrix without stored entries
@@ -411,6 +457,34 @@ int launch_subwave(const SpmvProblem& p, int kernel_lanes, hipStream_t stream) {
 // The wave-per-row launch of a planned group whose matrices share the code width BD.
 template <int BD>
 int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, int nwr, const Plan& plan,
+                       int64_t max_lds, bool simple, int ring, hipStream_t stream);
+
+// 8-bit values (4-bit codes, two steps of loads in flight): single-matrix and grouped entry points
+int launch_wave_row_fp8(const SpmvGroupArgs& args, const SpmvGroupHeader& head, int nwr, const Plan& plan,
+                        int64_t max_lds, bool simple, hipStream_t stream) {
+  const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
+  if (nwr == 1) {
+    auto kfn = simple ? spmv_wave_row_fp8_kernel<true> : spmv_wave_row_fp8_kernel<false>;
+    int st = set_lds_limit(kfn, max_lds);
+    if (st != MACKO_OK) return st;
+    const SpmvMat& m = args.m[0];
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, static_cast<const uint2*>(m.values), m.deltas,
+                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves);
+  } else {
+    using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
+    KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, 4, 8> : (KG)spmv_wave_row_kernel<2, false, 4, 8>;
+    int st = set_lds_limit(kfn, max_lds);
+    if (st != MACKO_OK) return st;
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
+                       head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
+                       head.inv_nwaves, args);
+  }
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
+
+template <int BD>
+int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, int nwr, const Plan& plan,
                        int64_t max_lds, bool simple, int ring, hipStream_t stream) {
   const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
   if (nwr == 1) {
@@ -424,8 +498,8 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     const SpmvMat& m = args.m[0];
-    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.values, m.deltas, m.row_ptr, m.x, m.y,
-                       m.rows, m.cols, m.q, m.r, head.inv_nwaves);
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, static_cast<const uint4*>(m.values), m.deltas,
+                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves);
   } else {
     using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
     KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD> : (KG)spmv_wave_row_kernel<2, false, BD>;
@@ -444,7 +518,7 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
 }
 
 // One grouped wave-per-row launch for the matrices wr[0..nwr) (same code width).
-int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hipStream_t stream) {
+int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, int b_val, hipStream_t stream) {
   const Tuning& t = tuning();
   const int cus = device_cu_count();
   PlanInput in[kMaxGroup];
@@ -509,7 +583,7 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
   for (int i = 0; i < nwr; ++i) {
     const SpmvProblem& p = *wr[i];
     SpmvMat& m = args.m[i];
-    m.values = reinterpret_cast<const uint4*>(p.values);
+    m.values = p.values;
     m.deltas = reinterpret_cast<const uint32_t*>(p.deltas);
     m.row_ptr = p.row_ptr;
     m.x = static_cast<const uint16_t*>(p.x);
@@ -537,6 +611,7 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, hi
     for (int i = 1; i < nwr; ++i) min_steps = std::min(min_steps, in[i].steps_per_row);
     if (min_steps >= 8) ring = 4;
   }
+  if (b_val == 8) return launch_wave_row_fp8(args, head, nwr, plan, max_lds, simple, stream);
   switch (b_delta) {
     case 1: return launch_wave_row_bd<1>(args, head, nwr, plan, max_lds, simple, ring, stream);
     case 2: return launch_wave_row_bd<2>(args, head, nwr, plan, max_lds, simple, ring, stream);
@@ -568,6 +643,8 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
                          static_cast<uint16_t*>(p.y), (int)p.rows);
       hipError_t e0 = hipGetLastError();
       if (e0 != hipSuccess) return hip_fail(e0);
+    } else if (p.b_val == 8) {                          // 8-bit values: 4-bit codes, wave-per-row kernel only
+      if (p.b_delta != 4 || lds_bytes_for(p.cols, 4) > kMaxLdsBytes) return MACKO_E_UNSUPPORTED;
     } else if (!wants_wave_row(p)) {                    // short rows or x larger than LDS: own launch
       int st = launch_subwave(p, (int)t.spmv_lanes, stream);
       if (st != MACKO_OK) return st;
@@ -578,10 +655,21 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
     const SpmvProblem* wr[kMaxGroup];
     int nwr = 0;
     for (int i = 0; i < n; ++i)
-      if (problems[i].b_delta == bd && wants_wave_row(problems[i])) wr[nwr++] = &problems[i];
+      if (problems[i].b_delta == bd && problems[i].b_val == 16 && wants_wave_row(problems[i])) wr[nwr++] = &problems[i];
     if (nwr == 0) continue;
-    int st = launch_wave_row_group(nwr, wr, bd, stream);
+    int st = launch_wave_row_group(nwr, wr, bd, 16, stream);
     if (st != MACKO_OK) return st;
+  }
+  // and one for the matrices with 8-bit values
+  {
+    const SpmvProblem* wr[kMaxGroup];
+    int nwr = 0;
+    for (int i = 0; i < n; ++i)
+      if (problems[i].b_val == 8 && problems[i].rows > 0 && problems[i].pad_nnz > 0) wr[nwr++] = &problems[i];
+    if (nwr > 0) {
+      int st = launch_wave_row_group(nwr, wr, 4, 8, stream);
+      if (st != MACKO_OK) return st;
+    }
   }
   return MACKO_OK;
 }

@@ -746,3 +746,90 @@ def test_check_device_accepts_valid_encodings_and_names_the_first_bad_row(b_delt
     assert z.check_device() is None
     lib = M.load_library()
     assert lib.macko_check_device(M.encode(W, b_delta)._h, 0, None) < 0             # not bound
+
+
+# ------------------------------------------------------------------ 8-bit values
+
+def check_y8(y_dev, W8, x, what=""):
+    y64, s64 = oracle.dense_matvec8(W8, x)
+    y = y_dev.float().cpu().numpy().astype(np.float64)
+    err = np.abs(y - y64)
+    tol = 1e-2 * s64 + 1e-3
+    assert (err <= tol).all(), f"{what}: worst excess {float((err - tol).max()):.3e} at row {int((err - tol).argmax())}"
+
+
+def test_fp8_every_bit_pattern_is_converted_like_the_oracle():
+    """One row per E4M3 pattern (NaNs aside), a single entry each, x = 1: y must be the value itself,
+    exactly (every E4M3 number is an fp16 number), including subnormals and both signs."""
+    codes = np.array([c for c in range(256) if (c & 0x7F) not in (0, 0x7F)], dtype=np.uint8)
+    W = np.zeros((len(codes), 512), dtype=np.uint8)
+    W[np.arange(len(codes)), (np.arange(len(codes)) * 37) % 512] = codes
+    W = np.repeat(W, 3, axis=0)                         # several rows per wavefront
+    x = np.full(512, 0x3C00, dtype=np.uint16)
+    m = M.encode_fp8(W).to_device()
+    y = m.spmv(to_dev(x))
+    torch.cuda.synchronize()
+    want = oracle.fp8_to_double(np.repeat(codes, 3))
+    assert np.array_equal(y.float().cpu().numpy().astype(np.float64), want)
+
+
+FP8_CASES = {
+    "half_1200x3000": lambda: wl.fp8_case(1200, 3000, 50),
+    "dense_300x1031": lambda: wl.fp8_case(300, 1031, 0),
+    "sparse90_600x9000": lambda: wl.fp8_case(600, 9000, 90),
+    "ragged_301x777": lambda: wl.fp8_case(301, 777, 30),
+    "one_row_20000": lambda: wl.fp8_case(1, 20000, 70),
+    "short_rows_2000x96": lambda: wl.fp8_case(2000, 96, 50),
+}
+
+
+@pytest.mark.parametrize("variant", ["auto", "resident", "many_wgs_b256", "many_wgs_r37_b128"])
+@pytest.mark.parametrize("case", list(FP8_CASES))
+def test_spmv_with_8_bit_values(case, variant):
+    knobs = {"auto": {}, "resident": {"spmv_resident": 2}, "many_wgs_b256": {"spmv_resident": 1, "spmv_block": 256},
+             "many_wgs_r37_b128": {"spmv_resident": 1, "spmv_rows_per_wg": 37, "spmv_block": 128}}[variant]
+    c = FP8_CASES[case]()
+    W = c.W.copy()
+    if W.shape[0] > 40:
+        W[10:30] = 0                                    # a run of empty rows
+    enc = oracle.encode8(W, 4)
+    for k, v in knobs.items():
+        M.set_tuning(k, v)
+    try:
+        m = M.encode_fp8(W).to_device()
+        v, d, r = m.fetch_device()
+        assert np.array_equal(v, enc.values) and np.array_equal(d, enc.deltas) and np.array_equal(r, enc.row_ptr)
+        y = m.spmv(to_dev(c.x))
+        torch.cuda.synchronize()
+    finally:
+        for k in knobs:
+            M.set_tuning(k, 0)
+    check_y8(y, W, c.x, f"{case}/{variant}")
+    if W.shape[0] > 40:
+        assert (y[10:30] == 0).all()
+    assert m.check_device() is None
+    assert np.array_equal(m.columns_device().cpu().numpy()[: enc.pad_nnz], oracle.unpack(enc)[1])
+
+
+def test_fp8_groups_unsupported_calls_and_full_size():
+    lib = M.load_library()
+    a, b = wl.fp8_case(700, 2048, 50), wl.fp8_case(900, 1024, 60)
+    c16 = wl.appendix_d_case(500, 2048, 50)
+    ma, mb, mc = M.encode_fp8(a.W).to_device(), M.encode_fp8(b.W).to_device(), M.encode(c16.W).to_device()
+    ys = M.spmv_group([ma, mc, mb], [to_dev(a.x), to_dev(c16.x), to_dev(b.x)])      # mixed value widths, one call
+    torch.cuda.synchronize()
+    check_y8(ys[0], a.W, a.x, "group/a")
+    check_y(ys[1], c16.W, c16.x, "group/16-bit")
+    check_y8(ys[2], b.W, b.x, "group/b")
+    X = torch.zeros((2, 2048), dtype=torch.float16, device="cuda")
+    Y = torch.zeros((2, 700), dtype=torch.float16, device="cuda")
+    assert lib.macko_spmm(ma._h, 2, X.data_ptr(), 2048, Y.data_ptr(), 700, 0) == -3
+    D = torch.zeros((700, 2048), dtype=torch.float16, device="cuda")
+    assert lib.macko_decode_device(ma._h, D.data_ptr(), 2048, 0) == -3
+    # the layer shapes at full size
+    for (r, c) in ((4096, 4096), (11008, 4096), (4096, 11008)):
+        case = wl.fp8_case(r, c, 50)
+        m = M.encode_fp8(case.W).to_device()
+        y = m.spmv(to_dev(case.x))
+        torch.cuda.synchronize()
+        check_y8(y, case.W, case.x, case.name)

@@ -212,3 +212,54 @@ def test_launch_planner_covers_every_row_exactly_once(tmp_path):
                           stderr=subprocess.DEVNULL)
     out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=300)
     assert out.returncode == 0 and out.stdout.startswith("ok"), out.stdout + out.stderr
+
+
+# ------------------------------------------------------------------ 8-bit values (host side)
+
+@pytest.mark.parametrize("shape,density", [((64, 512), 0.5), ((33, 1031), 0.07), ((5, 40), 1.0), ((300, 2000), 0.3)])
+def test_host_encoder_for_8_bit_values_is_bit_exact_against_the_oracle(shape, density):
+    rng = np.random.default_rng(shape[0])
+    W = rng.integers(0, 256, size=shape, dtype=np.uint8)
+    W[rng.random(shape) >= density] = 0
+    W[0, :] = 0
+    W[1, 0] = 0x80                                         # -0 is a zero
+    W[2, shape[1] - 1] = 0xFF                              # a NaN pattern is a value like any other
+    enc = oracle.encode8(W, 4)
+    m = M.encode_fp8(W)
+    v, d, r = m.host_buffers()
+    assert v.dtype == np.uint8
+    assert np.array_equal(v, enc.values) and np.array_equal(d, enc.deltas) and np.array_equal(r, enc.row_ptr)
+    rep = m.get_report()
+    assert (rep.b_val, rep.b_delta, rep.nnz, rep.pad_nnz, rep.alloc_nnz) == (8, 4, enc.nnz, enc.pad_nnz, enc.alloc_nnz)
+    assert (rep.values_bytes, rep.deltas_bytes, rep.total_bytes, rep.dense_bytes) == \
+        (enc.values_bytes, enc.deltas_bytes, enc.total_bytes, enc.dense_bytes)
+    assert rep.effd == pytest.approx(enc.effd, rel=1e-12)
+    dd = enc.nnz / (shape[0] * shape[1])
+    assert rep.effd_best == pytest.approx(oracle.closed_forms.effd_macko_best(dd, 8, 4), rel=1e-12)
+    assert rep.effd_worst == pytest.approx(oracle.closed_forms.effd_macko_worst(dd, 8, 4), rel=1e-12)
+    assert rep.effd_expected == pytest.approx(oracle.closed_forms.effd_macko_expected(dd, 8, 4), rel=1e-12)
+    assert np.array_equal(m.decode(), oracle.decode8(enc))
+    assert m.device_bytes() == (enc.alloc_nnz, enc.alloc_nnz // 2, 4 * (shape[0] + 1))
+    # strided input
+    wide = np.zeros((shape[0], shape[1] + 7), dtype=np.uint8)
+    wide[:, :shape[1]] = W
+    v2, d2, r2 = M.encode_fp8(wide[:, :shape[1]]).host_buffers()
+    assert np.array_equal(v2, enc.values) and np.array_equal(d2, enc.deltas) and np.array_equal(r2, enc.row_ptr)
+
+
+def test_8_bit_handles_refuse_what_they_do_not_support():
+    lib = M.load_library()
+    W = np.full((4, 64), 0x38, dtype=np.uint8)
+    m8 = M.encode_fp8(W)
+    m16 = M.encode(np.full((4, 64), 0x3C00, dtype=np.uint16))
+    buf16 = np.zeros((4, 64), dtype=np.uint16)
+    buf8 = np.zeros((4, 64), dtype=np.uint8)
+    assert lib.macko_decode(m8._h, buf16.ctypes.data, 64) == -3            # MACKO_E_UNSUPPORTED
+    assert lib.macko_decode_fp8(m16._h, buf8.ctypes.data, 64) == -3
+    p = ctypes.c_void_p()
+    assert lib.macko_host_values_fp8(m16._h, ctypes.byref(p)) == -3
+    assert lib.macko_host_buffers(m8._h, ctypes.byref(p), None, None) == -3
+    assert lib.macko_encode_fp8(None, 4, 64, 64, ctypes.byref(p), None) == -1
+    assert lib.macko_encode_fp8(W.ctypes.data, 4, 64, 63, ctypes.byref(p), None) == -1
+    empty = M.encode_fp8(np.zeros((0, 16), dtype=np.uint8))
+    assert empty.get_report().pad_nnz == 0
