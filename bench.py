@@ -171,6 +171,7 @@ def main():
                     help="also time the two 8192x8192 padding stress matrices (configs[3])")
     ap.add_argument("--widths", action="store_true",
                     help="also time 2-, 4- and 8-bit codes on the 36864x12288 matrix (Appendix C of the paper)")
+    ap.add_argument("--fp8", action="store_true", help="also time the layer step with 8-bit (E4M3) values")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe for rocprofv3 --pmc: a 1 GiB device copy of known size, then a "
@@ -347,6 +348,36 @@ def main():
     log(f"layer, 4 grouped launches, 2-bit codes: {two_bit}")
     del gs2, sparse2
     torch.cuda.empty_cache()
+
+    # the same layer with 8-bit values (OCP E4M3; the paper leaves 8-bit values to future work):
+    # 1 byte of value + half a byte of code per stored entry.  Not `value`; no dense 8-bit baseline is built.
+    fp8 = None
+    if args.fp8:
+        class Fp8Op:
+            def __init__(self, case, copies):
+                W8 = wl.fp8_values_of(case.W)
+                self.handles = [M.encode_fp8(W8).to_device() for _ in range(copies)]
+                self.report = self.handles[0].report
+                self.x = torch.from_numpy(case.x.view(np.float16)).cuda()
+                self.y = torch.empty(case.rows, dtype=torch.float16, device="cuda")
+                self.bytes = spmv_bytes(self.report)
+        ops8 = {tag: Fp8Op(case, mult * n_layers) for case, (tag, mult) in zip(cases, layer_plan)}
+        gs8 = grouped_steps("sparse", ops8)
+        t8 = time_region(torch, make_grouped_step(gs8), args.warmup, args.steps)
+        bytes8 = sum(mult * ops8[tag].bytes for tag, mult in layer_plan)
+        fp8 = {
+            "ms_per_step": round(t8 / args.steps * 1e3, 5), "bytes_per_step": bytes8,
+            "GBps": round(bytes8 / (t8 / args.steps) / 1e9, 1),
+            "frac_of_hbm_peak": round(bytes8 / (t8 / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
+            "speedup_vs_dense_fp16_gemv": round(t_dense / t8, 3),
+            "speedup_vs_16_bit_values": round(t_sparse / t8, 3),
+            "memory_reduction_vs_dense_fp16": round(layer_dense_bytes / bytes8, 3),
+            "effd_vs_dense_8_bit": round(ops8["qkvo"].report.effd, 4),
+            "values": "OCP E4M3, the 16-bit layer times 32 rounded by the framework's conversion",
+        }
+        log(f"layer, 4 grouped launches, 8-bit values: {fp8}")
+        del gs8, ops8
+        torch.cuda.empty_cache()
 
     # ---- per-shape numbers (cold rotation over the same copies) ---------------
     per_shape = {}
@@ -668,6 +699,7 @@ def main():
         "separate_launches": single,
         "one_launch_independent_products": one_launch,
         "two_bit_codes": two_bit,
+        **({"eight_bit_values": fp8} if fp8 else {}),
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
