@@ -470,14 +470,14 @@ def main():
             # rotate over >= 1 GiB of copies: two copies of the 90 % matrix (278 MB) would half fit the 256 MB cache
             nc = copies_for(int(2.5 * case.rows * case.cols * (1 - s / 100.0)), 1 << 30)
             so = SparseOp(M, torch, case, copies=nc)
-            ts = time_single_op(torch, so, stream_ptr, max(5, nc), 40)
+            ts = time_single_op(torch, so, stream_ptr, max(20, nc), 100)
             row = {"macko_us": round(ts * 1e6, 1), "macko_GBps": round(so.bytes / ts / 1e9, 1),
                    "frac_of_peak": round(so.bytes / ts / 1e9 / HBM_PEAK_GBPS, 4),
                    "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
                    "effd": round(so.report.effd, 4), "padding_entries": so.report.padding_entries}
             if s == 0:
                 do = DenseOp(M, torch, case, copies=2)
-                dense_t = time_single_op(torch, do, stream_ptr, 5, 40)
+                dense_t = time_single_op(torch, do, stream_ptr, 20, 100)
                 row["dense_us"] = round(dense_t * 1e6, 1)
                 row["dense_GBps"] = round(do.bytes / dense_t / 1e9, 1)
                 del do
