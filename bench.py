@@ -101,6 +101,33 @@ def time_region(torch, fn, n_warm, n_timed):
     return start.elapsed_time(stop) * 1e-3
 
 
+def time_multi_stream(torch, launch, n_warm, n_timed, n_streams=3):
+    """launch(i, stream_ptr) enqueues the independent item i on the given stream.  Items go to
+    n_streams streams in turn, so the tail of one kernel overlaps the start of the next; returns
+    seconds per item between two events on torch's current stream that enclose all of them."""
+    main = torch.cuda.current_stream()
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]     # default priority
+    ptrs = [int(st.cuda_stream) for st in streams]
+
+    def burst(first, count):
+        start = torch.cuda.Event(enable_timing=True)
+        stop = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        start.record(main)
+        for st in streams:
+            st.wait_stream(main)
+        for i in range(first, first + count):
+            launch(i, ptrs[i % n_streams])
+        for st in streams:
+            main.wait_stream(st)
+        stop.record(main)
+        torch.cuda.synchronize()
+        return start.elapsed_time(stop) * 1e-3 / count
+
+    burst(0, n_warm)
+    return burst(n_warm, n_timed)
+
+
 def time_single_op(torch, op, stream_ptr, n_warm, n_timed):
     copies = len(op.handles) if hasattr(op, "handles") else len(op.W)
 
@@ -475,6 +502,14 @@ def main():
                    "frac_of_peak": round(so.bytes / ts / 1e9 / HBM_PEAK_GBPS, 4),
                    "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
                    "effd": round(so.report.effd, 4), "padding_entries": so.report.padding_entries}
+            # the same launches dealt to three streams in turn (independent products overlap at the seams)
+            def launch3(i, sp, so=so, nc=nc):
+                st = so.handles[i % nc].spmv_raw(so.x.data_ptr(), so.y.data_ptr(), sp)
+                if st != 0:
+                    raise RuntimeError(f"launch failed with status {st}")
+            t3 = time_multi_stream(torch, launch3, max(20, nc), 100)
+            row["three_streams_us"] = round(t3 * 1e6, 1)
+            row["three_streams_frac_of_peak"] = round(so.bytes / t3 / 1e9 / HBM_PEAK_GBPS, 4)
             if s == 0:
                 do = DenseOp(M, torch, case, copies=2)
                 dense_t = time_single_op(torch, do, stream_ptr, 20, 100)
@@ -653,6 +688,28 @@ def main():
         td1 = time_region(torch, stack_pass(dops13), 2, 10) / 10
         ts = time_region(torch, grouped_stack("sparse"), 2, 10) / 10
         td = time_region(torch, grouped_stack("dense"), 2, 10) / 10
+        # the same 128 grouped launches dealt to three streams in turn: the products of this workload are
+        # independent, and kernels of different streams overlap (the next one starts on the compute units
+        # the previous one has already left)
+        def over_streams(kind):
+            groups = []
+            for layer in range(32):
+                def pick(tag, ks):
+                    op = (ops13 if kind == "sparse" else dops13)[tag]
+                    mult = dict(plan13)[tag]
+                    mats = [(op.handles if kind == "sparse" else op.W)[layer * mult + k] for k in ks]
+                    return mats, [op.x] * len(ks), [torch.empty_like(op.y) for _ in ks]
+                Group = M.SpmvGroup if kind == "sparse" else M.GemvGroup
+                groups += [Group(*pick("qkvo", [0, 1, 2])), Group(*pick("qkvo", [3])),
+                           Group(*pick("gate_up", [0, 1])), Group(*pick("down", [0]))]
+
+            def launch(i, sp):
+                st = groups[i % len(groups)].launch_raw(sp)
+                if st != 0:
+                    raise RuntimeError(f"grouped launch failed with status {st}")
+            return launch
+        ts3 = time_multi_stream(torch, over_streams("sparse"), 2 * 128, 10 * 128) * 128
+        td3 = time_multi_stream(torch, over_streams("dense"), 2 * 128, 10 * 128) * 128
         sb = 32 * sum(m * ops13[t].bytes for t, m in plan13)
         db = 32 * sum(m * dops13[t].bytes for t, m in plan13)
         stack_key = "stack_llama2_13b_32layers"
@@ -661,6 +718,10 @@ def main():
             "separate_launches_224": {"macko_us": round(ts1 * 1e6, 1), "dense_us": round(td1 * 1e6, 1)},
             "one_launch_per_layer_32": {"macko_us": round(ts32 * 1e6, 1), "dense_us": round(td32 * 1e6, 1),
                                         "macko_GBps": round(0 / 1e9, 1), "dense_GBps": round(0 / 1e9, 1)},
+            "three_streams_128": {"macko_us": round(ts3 * 1e6, 1), "dense_us": round(td3 * 1e6, 1),
+                                  "macko_GBps": round(sb / ts3 / 1e9, 1), "dense_GBps": round(db / td3 / 1e9, 1),
+                                  "macko_frac_of_hbm_peak": round(sb / ts3 / 1e9 / HBM_PEAK_GBPS, 4),
+                                  "speedup_vs_dense": round(td3 / ts3, 3)},
             "macko_GB": round(sb / 1e9, 3), "dense_GB": round(db / 1e9, 3),
             "macko_GBps": round(sb / ts / 1e9, 1), "dense_GBps": round(db / td / 1e9, 1),
             "speedup_vs_dense": round(td / ts, 3),
