@@ -708,6 +708,17 @@ def main():
                 if st != 0:
                     raise RuntimeError(f"grouped launch failed with status {st}")
             return launch
+        def separate_over_streams(ops):
+            seq = [(tag, layer * mult + k) for layer in range(32) for tag, mult in plan13 for k in range(mult)]
+
+            def launch(i, sp):
+                tag, copy = seq[i % len(seq)]
+                st = ops[tag].launch(copy, sp)
+                if st != 0:
+                    raise RuntimeError(f"launch failed with status {st}")
+            return launch
+        ts224 = time_multi_stream(torch, separate_over_streams(ops13), 2 * 224, 10 * 224) * 224
+        td224 = time_multi_stream(torch, separate_over_streams(dops13), 2 * 224, 10 * 224) * 224
         ts3 = time_multi_stream(torch, over_streams("sparse"), 2 * 128, 10 * 128) * 128
         td3 = time_multi_stream(torch, over_streams("dense"), 2 * 128, 10 * 128) * 128
         sb = 32 * sum(m * ops13[t].bytes for t, m in plan13)
@@ -722,6 +733,9 @@ def main():
                                   "macko_GBps": round(sb / ts3 / 1e9, 1), "dense_GBps": round(db / td3 / 1e9, 1),
                                   "macko_frac_of_hbm_peak": round(sb / ts3 / 1e9 / HBM_PEAK_GBPS, 4),
                                   "speedup_vs_dense": round(td3 / ts3, 3)},
+            "three_streams_224_separate": {"macko_us": round(ts224 * 1e6, 1), "dense_us": round(td224 * 1e6, 1),
+                                           "macko_frac_of_hbm_peak": round(sb / ts224 / 1e9 / HBM_PEAK_GBPS, 4),
+                                           "speedup_vs_dense": round(td224 / ts224, 3)},
             "macko_GB": round(sb / 1e9, 3), "dense_GB": round(db / 1e9, 3),
             "macko_GBps": round(sb / ts / 1e9, 1), "dense_GBps": round(db / td / 1e9, 1),
             "speedup_vs_dense": round(td / ts, 3),
