@@ -160,6 +160,10 @@ MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas
  * `values` are MACKO_E_UNSUPPORTED for such a handle. */
 MACKO_API int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                                macko_handle_t* out, macko_report_t* report);
+/* macko_wrap_device for arrays that hold 8-bit values (values_dev: alloc_nnz bytes,
+ * 16-byte aligned; 4-bit codes).  Same rules: trusted, not validated, caller owned. */
+MACKO_API int macko_wrap_device_fp8(int64_t rows, int64_t cols, int64_t pad_nnz, const void* values_dev,
+                                    const void* deltas_dev, const void* rowptr_dev, macko_handle_t* out);
 /* Host copy of the values of a macko_encode_fp8 handle (borrowed, alloc_nnz bytes). */
 MACKO_API int macko_host_values_fp8(macko_handle_t h, const uint8_t** values);
 /* Decode the host copy back to a dense rows x cols matrix of 8-bit values. */

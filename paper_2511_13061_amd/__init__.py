@@ -22,4 +22,5 @@ from .binding import (  # noqa: F401
     spmv_group,
     status_string,
     wrap_device,
+    wrap_device_fp8,
 )

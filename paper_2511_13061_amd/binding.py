@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
     "macko_wrap_device_ex", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_encode_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_encode_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -103,6 +103,7 @@ def load_library():
     lib.macko_columns_device.argtypes = [vp, vp, vp]
     lib.macko_encode_fp8.argtypes = [vp, i64, i64, i64, hp, rp]
     lib.macko_host_values_fp8.argtypes = [vp, hp]
+    lib.macko_wrap_device_fp8.argtypes = [i64, i64, i64, vp, vp, vp, hp]
     lib.macko_decode_fp8.argtypes = [vp, vp, i64]
     lib.macko_check_device.argtypes = [vp, vp, i64p]
     lib.macko_decode_device.argtypes = [vp, vp, i64, vp]
@@ -385,6 +386,16 @@ def wrap_device(rows: int, cols: int, pad_nnz: int, values_dev, deltas_dev, rowp
         _check(load_library().macko_wrap_device_ex(rows, cols, pad_nnz, int(b_delta), _dev_ptr(values_dev),
                                                    _dev_ptr(deltas_dev), _dev_ptr(rowptr_dev), ctypes.byref(h)),
                "macko_wrap_device_ex")
+    m = MackoMatrix(h.value, None)
+    m._keep = [values_dev, deltas_dev, rowptr_dev]
+    return m
+
+
+def wrap_device_fp8(rows: int, cols: int, pad_nnz: int, values_dev, deltas_dev, rowptr_dev) -> MackoMatrix:
+    """macko_wrap_device_fp8: adopt device arrays that hold an encoding with 8-bit values."""
+    h = ctypes.c_void_p()
+    _check(load_library().macko_wrap_device_fp8(rows, cols, pad_nnz, _dev_ptr(values_dev), _dev_ptr(deltas_dev),
+                                                _dev_ptr(rowptr_dev), ctypes.byref(h)), "macko_wrap_device_fp8")
     m = MackoMatrix(h.value, None)
     m._keep = [values_dev, deltas_dev, rowptr_dev]
     return m

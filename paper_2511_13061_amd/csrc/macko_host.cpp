@@ -334,6 +334,15 @@ int macko_wrap_device_ex(int64_t rows, int64_t cols, int64_t pad_nnz, int b_delt
   return MACKO_OK;
 }
 
+int macko_wrap_device_fp8(int64_t rows, int64_t cols, int64_t pad_nnz, const void* values_dev,
+                          const void* deltas_dev, const void* rowptr_dev, macko_handle_t* out) {
+  int st = macko_wrap_device_ex(rows, cols, pad_nnz, macko::kDeltaBits, values_dev, deltas_dev, rowptr_dev, out);
+  if (st != MACKO_OK) return st;
+  (*out)->b_val = 8;
+  macko::fill_report(&(*out)->report, rows, cols, -1, pad_nnz, (*out)->alloc_nnz, -1, -1, macko::kDeltaBits, 8);
+  return MACKO_OK;
+}
+
 int macko_get_report(macko_handle_t h, macko_report_t* report) {
   if (!h || !report) return MACKO_E_INVALID_ARG;
   *report = h->report;

@@ -821,6 +821,13 @@ def test_fp8_groups_unsupported_calls_and_full_size():
     check_y8(ys[0], a.W, a.x, "group/a")
     check_y(ys[1], c16.W, c16.x, "group/16-bit")
     check_y8(ys[2], b.W, b.x, "group/b")
+    # adopt a copy of the device arrays (a checkpoint loaded elsewhere)
+    v, d, r = [t.clone() for t in ma.device_buffers()]
+    w = M.wrap_device_fp8(700, 2048, ma.report.pad_nnz, v, d, r)
+    assert w.get_report().b_val == 8 and w.check_device() is None
+    yw = w.spmv(to_dev(a.x))
+    torch.cuda.synchronize()
+    assert torch.equal(yw, ys[0])
     X = torch.zeros((2, 2048), dtype=torch.float16, device="cuda")
     Y = torch.zeros((2, 700), dtype=torch.float16, device="cuda")
     assert lib.macko_spmm(ma._h, 2, X.data_ptr(), 2048, Y.data_ptr(), 700, 0) == -3
