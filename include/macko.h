@@ -160,6 +160,11 @@ MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas
  * `values` are MACKO_E_UNSUPPORTED for such a handle. */
 MACKO_API int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                                macko_handle_t* out, macko_report_t* report);
+/* macko_encode_device for a dense matrix of 8-bit values in device memory (uint8 [rows x ld]);
+ * same contract, bit-identical to macko_encode_fp8; the encoder's scratch holds 3 bytes per
+ * stored entry for such a call. */
+MACKO_API int macko_encode_device_fp8(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, void* stream,
+                                      macko_handle_t* out, macko_report_t* report);
 /* macko_wrap_device for arrays that hold 8-bit values (values_dev: alloc_nnz bytes,
  * 16-byte aligned; 4-bit codes).  Same rules: trusted, not validated, caller owned. */
 MACKO_API int macko_wrap_device_fp8(int64_t rows, int64_t cols, int64_t pad_nnz, const void* values_dev,

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     encode,
     encode_device,
     encode_fp8,
+    encode_device_fp8,
     get_tuning,
     library_path,
     load_library,

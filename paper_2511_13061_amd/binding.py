@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
     "macko_wrap_device_ex", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_encode_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_encode_fp8", "macko_encode_device_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -103,6 +103,7 @@ def load_library():
     lib.macko_columns_device.argtypes = [vp, vp, vp]
     lib.macko_encode_fp8.argtypes = [vp, i64, i64, i64, hp, rp]
     lib.macko_host_values_fp8.argtypes = [vp, hp]
+    lib.macko_encode_device_fp8.argtypes = [vp, i64, i64, i64, vp, hp, rp]
     lib.macko_wrap_device_fp8.argtypes = [i64, i64, i64, vp, vp, vp, hp]
     lib.macko_decode_fp8.argtypes = [vp, vp, i64]
     lib.macko_check_device.argtypes = [vp, vp, i64p]
@@ -355,6 +356,21 @@ def encode_fp8(dense) -> MackoMatrix:
     ld = a.strides[0] if a.size else a.shape[1]
     _check(load_library().macko_encode_fp8(a.ctypes.data, a.shape[0], a.shape[1], ld,
                                            ctypes.byref(h), ctypes.byref(rep)), "macko_encode_fp8")
+    return MackoMatrix(h.value, Report._from_c(rep))
+
+
+def encode_device_fp8(dense_dev, stream=None) -> MackoMatrix:
+    """macko_encode_device_fp8 on a torch uint8 CUDA matrix of E4M3 bit patterns (row-major)."""
+    if dense_dev.dim() != 2 or (dense_dev.shape[1] > 1 and dense_dev.stride(1) != 1):
+        raise ValueError("dense_dev must be a row-major 2-D tensor")
+    if dense_dev.element_size() != 1:
+        raise TypeError("dense_dev must hold one byte per element")
+    h = ctypes.c_void_p()
+    rep = _CReport()
+    ld = dense_dev.stride(0) if dense_dev.shape[0] > 1 else max(dense_dev.shape[1], 1)
+    _check(load_library().macko_encode_device_fp8(_dev_ptr(dense_dev), dense_dev.shape[0], dense_dev.shape[1], ld,
+                                                  _stream_ptr(stream), ctypes.byref(h), ctypes.byref(rep)),
+           "macko_encode_device_fp8")
     return MackoMatrix(h.value, Report._from_c(rep))
 
 

@@ -36,9 +36,31 @@ struct Chunk {
 // Loads only; columns at or beyond `cols` read as +0.  The caller decodes the
 // result one loop iteration later, so the load is in flight behind the work on
 // the current chunk.
-__device__ __forceinline__ RawChunk load_raw(const uint16_t* __restrict__ row, int col0, int cols,
-                                             bool vec_ok) {
+//
+// 8-bit values (IN8) are widened on the way in, sign to bit 15 and the other seven bits in
+// place, so that "neither +0 nor -0" is the same test for both widths; the fill pass then
+// writes 16-bit values to scratch and a last pass narrows them again.
+__device__ __forceinline__ uint32_t widen8(uint32_t b) { return (b & 0x7Fu) | ((b & 0x80u) << 8); }
+
+template <bool IN8>
+__device__ __forceinline__ RawChunk load_raw(const void* __restrict__ row_v, int col0, int cols, bool vec_ok) {
   RawChunk r;
+  if (IN8) {
+    const uint8_t* row = static_cast<const uint8_t*>(row_v);
+    uint32_t b[8];
+    if (vec_ok && col0 + 8 <= cols) {
+      const uint2 q = *reinterpret_cast<const uint2*>(row + col0);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) b[k] = ((k < 4 ? q.x : q.y) >> (8 * (k & 3))) & 0xFFu;
+    } else {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) b[k] = (col0 + k < cols) ? row[col0 + k] : 0u;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r.u[k] = widen8(b[2 * k]) | (widen8(b[2 * k + 1]) << 16);
+    return r;
+  }
+  const uint16_t* row = static_cast<const uint16_t*>(row_v);
   if (vec_ok && col0 + 8 <= cols) {
     const uint4 q = *reinterpret_cast<const uint4*>(row + col0);
     r.u[0] = q.x; r.u[1] = q.y; r.u[2] = q.z; r.u[3] = q.w;
@@ -100,21 +122,22 @@ __device__ __forceinline__ LaneView view_chunk(unsigned mask, int col0, int lane
   return v;
 }
 
+template <bool IN8>
 __global__ void __launch_bounds__(256)
-encode_count_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok, int b_delta,
+encode_count_kernel(const void* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok, int b_delta,
                     uint32_t* __restrict__ row_entries, uint32_t* __restrict__ row_nnz) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int nwaves = blockDim.x >> 6;
   for (int row = blockIdx.x * nwaves + wave; row < rows; row += gridDim.x * nwaves) {
-    const uint16_t* src = dense + (int64_t)row * ld;
+    const void* src = static_cast<const unsigned char*>(dense) + (int64_t)row * ld * (IN8 ? 1 : 2);
     uint32_t carry = 0;
     unsigned entries = 0, nnz = 0;
-    RawChunk nxt = load_raw(src, lane * 8, cols, vec_ok);
+    RawChunk nxt = load_raw<IN8>(src, lane * 8, cols, vec_ok);
     for (int base = 0; base < cols; base += 512) {
       const int col0 = base + lane * 8;
       const Chunk c = decode_chunk(nxt);
-      nxt = load_raw(src, col0 + 512, cols, vec_ok);                 // next step's columns, in flight
+      nxt = load_raw<IN8>(src, col0 + 512, cols, vec_ok);            // next step's columns, in flight
       const LaneView v = view_chunk(c.mask, col0, lane, b_delta, &carry);
       entries += v.entries;
       nnz += v.nnz;
@@ -263,8 +286,9 @@ encode_row_ptr_kernel(const uint32_t* __restrict__ row_entries, int rows, const 
 constexpr int kStage = 1024;
 constexpr int kFillWaves = 4;
 
+template <bool IN8>
 __global__ void __launch_bounds__(64 * kFillWaves)
-encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok, int b_delta,
+encode_fill_kernel(const void* __restrict__ dense, int rows, int cols, int64_t ld, bool vec_ok, int b_delta,
                    const uint32_t* __restrict__ row_ptr, uint16_t* __restrict__ values,
                    uint8_t* __restrict__ codes8, uint32_t pad_nnz, uint32_t alloc_nnz) {
   // the zero tail of both arrays (fewer than 128 entries): the first workgroup writes it
@@ -282,14 +306,14 @@ encode_fill_kernel(const uint16_t* __restrict__ dense, int rows, int cols, int64
   uint16_t* sv = stage_v[wave];
   uint8_t* sc = stage_c[wave];
   for (int row = blockIdx.x * nwaves + wave; row < rows; row += gridDim.x * nwaves) {
-    const uint16_t* src = dense + (int64_t)row * ld;
+    const void* src = static_cast<const unsigned char*>(dense) + (int64_t)row * ld * (IN8 ? 1 : 2);
     uint32_t carry = 0;
     uint32_t cursor = row_ptr[row];              // first entry of this step
-    RawChunk nxt = load_raw(src, lane * 8, cols, vec_ok);
+    RawChunk nxt = load_raw<IN8>(src, lane * 8, cols, vec_ok);
     for (int base = 0; base < cols; base += 512) {
       const int col0 = base + lane * 8;
       const Chunk c = decode_chunk(nxt);
-      nxt = load_raw(src, col0 + 512, cols, vec_ok);                 // next step's columns, in flight
+      nxt = load_raw<IN8>(src, col0 + 512, cols, vec_ok);            // next step's columns, in flight
       const LaneView v = view_chunk(c.mask, col0, lane, b_delta, &carry);
       const uint32_t incl = wave_incl_scan_u32(v.entries);
       const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
@@ -398,6 +422,19 @@ encode_pack_kernel(const uint8_t* __restrict__ codes8, int64_t words, int b_delt
   }
 }
 
+// 8-bit values: the widened 16-bit values of the fill pass back to bytes (4 entries per thread and step)
+__global__ void __launch_bounds__(256)
+encode_narrow_kernel(const uint16_t* __restrict__ wide, int64_t quads, uint32_t* __restrict__ values8) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < quads; i += (int64_t)gridDim.x * blockDim.x) {
+    const uint2 q = reinterpret_cast<const uint2*>(wide)[i];
+    const uint32_t h[4] = {q.x & 0xFFFFu, q.x >> 16, q.y & 0xFFFFu, q.y >> 16};
+    uint32_t w = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w |= ((h[k] & 0x7Fu) | ((h[k] >> 8) & 0x80u)) << (8 * k);
+    values8[i] = w;
+  }
+}
+
 struct DeviceBuf {
   void* p = nullptr;
   ~DeviceBuf() {
@@ -438,13 +475,15 @@ constexpr size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // The handle's three arrays live in ONE allocation (*block, to be released with hipFree):
 // values first, then deltas, then row_ptr, each at a multiple of 256 bytes.
-int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta,
+int encode_on_device(const void* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta, int b_val,
                      hipStream_t stream, void** block,
-                     uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
+                     void** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
                      int64_t* pad_nnz, int64_t* alloc_nnz, int64_t* empty_rows,
                      int64_t* max_row_entries) {
   const int cus = device_cu_count();
-  const bool vec_ok = (ld % 8 == 0) && (reinterpret_cast<uintptr_t>(dense) & 15) == 0;
+  const bool in8 = b_val == 8;
+  // 8 columns per load: 16 bytes of fp16, 8 bytes of 8-bit values
+  const bool vec_ok = (ld % 8 == 0) && (reinterpret_cast<uintptr_t>(dense) & (in8 ? 7 : 15)) == 0;
   int dev = 0;
   MACKO_HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) return MACKO_E_UNSUPPORTED;
@@ -483,8 +522,12 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
 
   const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((rows + 3) / 4, (int64_t)cus * 16));
   if (rows > 0) {
-    hipLaunchKernelGGL(encode_count_kernel, dim3(grid), dim3(256), 0, stream, dense, (int)rows,
-                       (int)cols, ld, vec_ok, b_delta, counts, nnzs);
+    if (in8)
+      hipLaunchKernelGGL(encode_count_kernel<true>, dim3(grid), dim3(256), 0, stream, dense, (int)rows,
+                         (int)cols, ld, vec_ok, b_delta, counts, nnzs);
+    else
+      hipLaunchKernelGGL(encode_count_kernel<false>, dim3(grid), dim3(256), 0, stream, dense, (int)rows,
+                         (int)cols, ld, vec_ok, b_delta, counts, nnzs);
     hipLaunchKernelGGL(encode_block_sums_kernel, dim3((unsigned)nblocks), dim3(1024), 0, stream, counts, nnzs,
                        (int)rows, sums);
   }
@@ -504,7 +547,7 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
   // (nothing in the old scratch but the per-row counts is needed any more, so they are
   // turned into row pointers before the scratch moves)
   const size_t b_values = 0;
-  const size_t b_deltas = align_up(b_values + (size_t)alloc * 2, 256);
+  const size_t b_deltas = align_up(b_values + (size_t)alloc * (in8 ? 1 : 2), 256);
   const size_t b_rowptr = align_up(b_deltas + (size_t)alloc * b_delta / 8, 256);
   const size_t b_total = b_rowptr + 4 * (size_t)(rows + 1);
   DeviceBuf out;
@@ -513,7 +556,7 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
     return MACKO_E_OUT_OF_MEMORY;
   }
   unsigned char* ob = static_cast<unsigned char*>(out.p);
-  uint16_t* vals = reinterpret_cast<uint16_t*>(ob + b_values);
+  void* vals = ob + b_values;
   uint32_t* dels = reinterpret_cast<uint32_t*>(ob + b_deltas);
   uint32_t* rp = reinterpret_cast<uint32_t*>(ob + b_rowptr);
   if (rows > 0)
@@ -521,9 +564,12 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
                        boff, rp, (uint32_t)pad);
   else
     MACKO_HIP_TRY(hipMemsetAsync(rp, 0, 4, stream));
-  if (o_codes + (size_t)alloc + 256 > ws.cap) {
+  // scratch after the counts: one code byte per entry, and for 8-bit values the widened values
+  const size_t o_wide = align_up(o_codes + (size_t)alloc + 256, 256);
+  const size_t scratch_needed = in8 ? o_wide + 2 * (size_t)alloc + 256 : o_codes + (size_t)alloc + 256;
+  if (scratch_needed > ws.cap) {
     MACKO_HIP_TRY(hipStreamSynchronize(stream));       // the launch above reads the old scratch
-    if (workspace_reserve(ws, o_codes + (size_t)alloc + 256) != hipSuccess) {
+    if (workspace_reserve(ws, scratch_needed) != hipSuccess) {
       (void)hipGetLastError();
       return MACKO_E_OUT_OF_MEMORY;
     }
@@ -531,9 +577,20 @@ int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t 
   uint8_t* codes = static_cast<unsigned char*>(ws.p) + o_codes;
 
   if (rows > 0 && alloc > 0) {
-    hipLaunchKernelGGL(encode_fill_kernel, dim3(grid), dim3(64 * kFillWaves), 0, stream, dense, (int)rows,
-                       (int)cols, ld, vec_ok, b_delta, static_cast<const uint32_t*>(rp), vals, codes,
-                       (uint32_t)pad, (uint32_t)alloc);
+    if (in8) {
+      uint16_t* wide = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws.p) + o_wide);
+      hipLaunchKernelGGL(encode_fill_kernel<true>, dim3(grid), dim3(64 * kFillWaves), 0, stream, dense, (int)rows,
+                         (int)cols, ld, vec_ok, b_delta, static_cast<const uint32_t*>(rp), wide, codes,
+                         (uint32_t)pad, (uint32_t)alloc);
+      const int64_t quads = alloc / 4;                   // alloc is a multiple of 16
+      const unsigned ngrid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((quads + 255) / 256, (int64_t)cus * 16));
+      hipLaunchKernelGGL(encode_narrow_kernel, dim3(ngrid), dim3(256), 0, stream, static_cast<const uint16_t*>(wide),
+                         quads, static_cast<uint32_t*>(vals));
+    } else {
+      hipLaunchKernelGGL(encode_fill_kernel<false>, dim3(grid), dim3(64 * kFillWaves), 0, stream, dense, (int)rows,
+                         (int)cols, ld, vec_ok, b_delta, static_cast<const uint32_t*>(rp),
+                         static_cast<uint16_t*>(vals), codes, (uint32_t)pad, (uint32_t)alloc);
+    }
     const int64_t words = alloc * b_delta / 32;
     const unsigned pgrid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((words + 255) / 256, (int64_t)cus * 16));
     hipLaunchKernelGGL(encode_pack_kernel, dim3(pgrid), dim3(256), 0, stream, static_cast<const uint8_t*>(codes),

@@ -263,20 +263,33 @@ int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64
   return macko_encode_device_ex(dense_dev, rows, cols, ld, macko::kDeltaBits, stream, out, report);
 }
 
+static int encode_device_any(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, int b_delta, int b_val,
+                             void* stream, macko_handle_t* out, macko_report_t* report);
+
 int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, int b_delta,
                            void* stream, macko_handle_t* out, macko_report_t* report) {
+  return encode_device_any(dense_dev, rows, cols, ld, b_delta, 16, stream, out, report);
+}
+
+int macko_encode_device_fp8(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, void* stream,
+                            macko_handle_t* out, macko_report_t* report) {
+  return encode_device_any(dense_dev, rows, cols, ld, macko::kDeltaBits, 8, stream, out, report);
+}
+
+static int encode_device_any(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld, int b_delta, int b_val,
+                             void* stream, macko_handle_t* out, macko_report_t* report) {
   if (out) *out = nullptr;
   if (!out || rows < 0 || cols < 0 || ld < cols || !valid_b_delta(b_delta)) return MACKO_E_INVALID_ARG;
   if (!dense_dev && rows > 0 && cols > 0) return MACKO_E_INVALID_ARG;
   if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
   macko_matrix* m = new (std::nothrow) macko_matrix();
   if (!m) return MACKO_E_OUT_OF_MEMORY;
-  uint16_t* v = nullptr;
+  void* v = nullptr;
   uint8_t* d = nullptr;
   uint32_t* rp = nullptr;
   int64_t nnz = 0, pad = 0, alloc = 0, empty = 0, longest = 0;
   void* block = nullptr;
-  int st = macko::encode_on_device(static_cast<const uint16_t*>(dense_dev), rows, cols, ld, b_delta,
+  int st = macko::encode_on_device(dense_dev, rows, cols, ld, b_delta, b_val,
                                    static_cast<hipStream_t>(stream), &block, &v, &d, &rp, &nnz, &pad, &alloc,
                                    &empty, &longest);
   if (st != MACKO_OK) {
@@ -287,14 +300,15 @@ int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, in
   m->cols = cols;
   m->pad_nnz = pad;
   m->alloc_nnz = alloc;
-  m->d_values = v;
+  m->d_values = static_cast<const uint16_t*>(v);
   m->d_deltas = d;
   m->d_row_ptr = rp;
   m->b_delta = b_delta;
+  m->b_val = b_val;
   m->bound = true;
   m->owns_device = true;
   m->d_block = block;
-  macko::fill_report(&m->report, rows, cols, nnz, pad, alloc, empty, longest, b_delta);
+  macko::fill_report(&m->report, rows, cols, nnz, pad, alloc, empty, longest, b_delta, b_val);
   if (report) *report = m->report;
   *out = m;
   return MACKO_OK;

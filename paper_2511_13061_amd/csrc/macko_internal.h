@@ -73,9 +73,9 @@ int launch_columns(const SpmvProblem& p, int32_t* cols_out, hipStream_t stream);
 int launch_check(const SpmvProblem& p, unsigned int* first_bad, hipStream_t stream);
 int launch_decode(const SpmvProblem& p, uint16_t* dense, int64_t ld, hipStream_t stream);
 // GPU encoder: counting pass + fill pass.  The three arrays are parts of one hipMalloc'd *block.
-int encode_on_device(const uint16_t* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta,
+int encode_on_device(const void* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta, int b_val,
                      hipStream_t stream, void** block,
-                     uint16_t** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
+                     void** values, uint8_t** deltas, uint32_t** row_ptr, int64_t* nnz,
                      int64_t* pad_nnz, int64_t* alloc_nnz, int64_t* empty_rows,
                      int64_t* max_row_entries);
 

@@ -807,6 +807,13 @@ def test_spmv_with_8_bit_values(case, variant):
     check_y8(y, W, c.x, f"{case}/{variant}")
     if W.shape[0] > 40:
         assert (y[10:30] == 0).all()
+    g = M.encode_device_fp8(torch.from_numpy(W).cuda())        # the GPU encoder: same bytes, same report
+    gv, gd, gr = g.fetch_device()
+    assert np.array_equal(gv, enc.values) and np.array_equal(gd, enc.deltas) and np.array_equal(gr, enc.row_ptr)
+    rep = g.get_report()
+    assert (rep.b_val, rep.nnz, rep.pad_nnz, rep.alloc_nnz, rep.total_bytes) == \
+        (8, enc.nnz, enc.pad_nnz, enc.alloc_nnz, enc.total_bytes)
+    assert torch.equal(g.spmv(to_dev(c.x)), y)
     assert m.check_device() is None
     assert np.array_equal(m.columns_device().cpu().numpy()[: enc.pad_nnz], oracle.unpack(enc)[1])
 
@@ -840,3 +847,28 @@ def test_fp8_groups_unsupported_calls_and_full_size():
         y = m.spmv(to_dev(case.x))
         torch.cuda.synchronize()
         check_y8(y, case.W, case.x, case.name)
+
+
+def test_fp8_gpu_encoder_special_patterns_and_strided_unaligned_input():
+    rng = np.random.default_rng(81)
+    W = rng.integers(0, 256, size=(123, 1001), dtype=np.uint8)
+    W[rng.random(W.shape) < 0.6] = 0
+    W[3, 10:16] = [0x80, 0x7F, 0xFF, 0x01, 0x81, 0x00]      # -0 is a zero; NaN patterns and subnormals are values
+    W[7] = 0
+    enc = oracle.encode8(W, 4)
+    big = torch.zeros((123, 1001 + 11), dtype=torch.uint8, device="cuda")
+    big[:, 3: 3 + 1001] = torch.from_numpy(W).cuda()
+    view = big[:, 3: 3 + 1001]                               # unaligned start, odd leading dimension
+    lib = M.load_library()
+    import ctypes
+    h = ctypes.c_void_p()
+    assert lib.macko_encode_device_fp8(view.data_ptr(), 123, 1001, big.stride(0), 0, ctypes.byref(h), None) == 0
+    g = M.binding.MackoMatrix(h.value, None)
+    gv, gd, gr = g.fetch_device()
+    assert np.array_equal(gv, enc.values) and np.array_equal(gd, enc.deltas) and np.array_equal(gr, enc.row_ptr)
+    # a layer shape at full size, against the host encoder's bytes
+    case = wl.fp8_case(11008, 4096, 50)
+    hv, hd, hr = M.encode_fp8(case.W).host_buffers()
+    gv, gd, gr = M.encode_device_fp8(torch.from_numpy(case.W).cuda()).fetch_device()
+    assert np.array_equal(gv, hv) and np.array_equal(gd, hd) and np.array_equal(gr, hr)
+    assert np.array_equal(hv, oracle.encode8(case.W, 4).values)
