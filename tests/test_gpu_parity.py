@@ -872,3 +872,41 @@ def test_fp8_gpu_encoder_special_patterns_and_strided_unaligned_input():
     gv, gd, gr = M.encode_device_fp8(torch.from_numpy(case.W).cuda()).fetch_device()
     assert np.array_equal(gv, hv) and np.array_equal(gd, hd) and np.array_equal(gr, hr)
     assert np.array_equal(hv, oracle.encode8(case.W, 4).values)
+
+
+# ------------------------------------------------------------------ maximum sizes
+
+def test_more_than_2_pow_31_stored_entries():
+    """46400 x 46400, fully dense: 2.15e9 stored entries, past the sign bit of a 32-bit index and half
+    way to the format's limit of 2^32.  The encoding of a dense matrix is known in closed form (every
+    code 0, row r starts at r * C, values = the matrix), so the GPU encoder is checked without the
+    oracle's encoder; the product is checked against the oracle's dense product of the 464 distinct rows."""
+    R = C = 46400
+    blk = wl.bernoulli(464, C, 1.0, 0.02, 99, 1)            # 464 distinct rows, repeated 100 times
+    assert ((blk & 0x7FFF) != 0).all()
+    x = wl.x_vector(C, 99, 1)
+    Wd = torch.from_numpy(blk.view(np.float16)).cuda().repeat(100, 1)
+    m = M.encode_device(Wd)
+    rep = m.get_report()
+    assert rep.pad_nnz == R * C > 2 ** 31 and rep.nnz == R * C and rep.alloc_nnz == R * C
+    vals, dels, rp = m.fetch_device()
+    assert np.array_equal(rp.astype(np.int64), np.arange(R + 1, dtype=np.int64) * C)
+    assert not dels.any()
+    for row in (0, 463, 464, 23199, R - 1):
+        assert np.array_equal(vals[row * C:(row + 1) * C], blk[row % 464]), row
+    del vals, dels
+    assert m.check_device() is None
+    xd = to_dev(x)
+    y = m.spmv(xd)
+    torch.cuda.synchronize()
+    y64, s64 = oracle.dense_matvec(blk, x)
+    err = np.abs(y.float().cpu().numpy().astype(np.float64).reshape(100, 464) - y64[None, :])
+    assert (err <= 1e-2 * s64[None, :] + 1e-3).all(), float(err.max())
+    cols = m.columns_device()
+    torch.cuda.synchronize()
+    for row in (0, 1, 30000, R - 1):                          # entries beyond index 2^31 included
+        assert torch.equal(cols[row * C:(row + 1) * C].cpu(), torch.arange(C, dtype=torch.int32)), row
+    yd = M.dense_gemv(Wd, xd)
+    torch.cuda.synchronize()
+    err = np.abs(yd.float().cpu().numpy().astype(np.float64).reshape(100, 464) - y64[None, :])
+    assert (err <= 1e-2 * s64[None, :] + 1e-3).all(), float(err.max())
