@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     MackoMatrix,
     Report,
     SpmvGroup,
+    SpmvMany,
     dense_gemv,
     dense_gemv_group,
     encode,

@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
     "macko_wrap_device_ex", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_encode_fp8", "macko_encode_device_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_encode_fp8", "macko_encode_device_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_spmv_many", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -112,6 +112,7 @@ def load_library():
     lib.macko_dense_gemv.argtypes = [vp, i64, i64, i64, vp, vp, vp]
     vpp = ctypes.POINTER(vp)
     lib.macko_spmv_group.argtypes = [ci, vpp, vpp, vpp, vp]
+    lib.macko_spmv_many.argtypes = [i64, vpp, vpp, vpp, vp]
     lib.macko_dense_gemv_group.argtypes = [ci, vpp, i64p, i64p, i64p, vpp, vpp, vp]
     lib.macko_spmm.argtypes = [vp, ci, vp, i64, vp, i64, vp]
     lib.macko_destroy.argtypes = [vp]
@@ -447,6 +448,25 @@ class SpmvGroup:
 
     def launch(self, stream=None) -> None:
         _check(self.launch_raw(_stream_ptr(stream)), "macko_spmv_group")
+
+
+class SpmvMany:
+    """Pre-marshalled arguments of macko_spmv_many: any number of independent products."""
+
+    def __init__(self, matrices, xs, ys):
+        n = len(matrices)
+        self.n = n
+        self._keep = (list(matrices), list(xs), list(ys))
+        VP = ctypes.c_void_p * max(n, 1)
+        self._h = VP(*[m._h.value for m in matrices])
+        self._x = VP(*[_dev_ptr(x) for x in xs])
+        self._y = VP(*[_dev_ptr(y) for y in ys])
+
+    def launch_raw(self, stream_ptr: int) -> int:
+        return load_library().macko_spmv_many(self.n, self._h, self._x, self._y, stream_ptr)
+
+    def launch(self, stream=None) -> None:
+        _check(self.launch_raw(_stream_ptr(stream)), "macko_spmv_many")
 
 
 class GemvGroup:

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -545,6 +546,75 @@ int macko_spmv_group(int n, const macko_handle_t* handles, const void* const* x_
   }
   if (m == 0) return MACKO_OK;
   return macko::launch_spmv_group(m, p, static_cast<hipStream_t>(stream));
+}
+
+namespace {
+
+// Side streams of macko_spmv_many, one set per device, created on first use and kept until the
+// process ends (default priority).  The mutex covers creation and every call's enqueue phase:
+// the fork / join events are shared.
+constexpr int kManyStreams = 3;
+struct ManyStreams {
+  bool ready = false;
+  hipStream_t side[kManyStreams] = {};
+  hipEvent_t fork = nullptr;
+  hipEvent_t join[kManyStreams] = {};
+};
+std::mutex g_many_mutex;
+ManyStreams g_many[64];
+
+int many_streams_for(int dev, ManyStreams** out) {
+  if (dev < 0 || dev >= 64) return MACKO_E_UNSUPPORTED;
+  ManyStreams& ms = g_many[dev];
+  if (!ms.ready) {
+    MACKO_HIP_TRY(hipEventCreateWithFlags(&ms.fork, hipEventDisableTiming));
+    for (int i = 0; i < kManyStreams; ++i) {
+      MACKO_HIP_TRY(hipStreamCreateWithFlags(&ms.side[i], hipStreamNonBlocking));
+      MACKO_HIP_TRY(hipEventCreateWithFlags(&ms.join[i], hipEventDisableTiming));
+    }
+    ms.ready = true;
+  }
+  *out = &ms;
+  return MACKO_OK;
+}
+
+}  // namespace
+
+int macko_spmv_many(int64_t n, const macko_handle_t* handles, const void* const* x_dev, void* const* y_dev,
+                    void* stream) {
+  if (n < 0 || (n > 0 && (!handles || !x_dev || !y_dev))) return MACKO_E_INVALID_ARG;
+  for (int64_t i = 0; i < n; ++i) {                      // everything is checked before anything is enqueued
+    macko_handle_t h = handles[i];
+    if (!h) return MACKO_E_INVALID_ARG;
+    if (!h->bound) return MACKO_E_NOT_BOUND;
+    if (h->rows == 0) continue;
+    int st = check_vec_ptrs(x_dev[i], y_dev[i], h->cols);
+    if (st != MACKO_OK) return st;
+  }
+  if (n <= MACKO_MAX_GROUP) return n == 0 ? MACKO_OK : macko_spmv_group((int)n, handles, x_dev, y_dev, stream);
+  int dev = 0;
+  MACKO_HIP_TRY(hipGetDevice(&dev));
+  std::lock_guard<std::mutex> lock(g_many_mutex);
+  ManyStreams* ms = nullptr;
+  int st = many_streams_for(dev, &ms);
+  if (st != MACKO_OK) return st;
+  hipStream_t main = static_cast<hipStream_t>(stream);
+  // fork: the side streams start after everything already enqueued on the caller's stream
+  MACKO_HIP_TRY(hipEventRecord(ms->fork, main));
+  for (int i = 0; i < kManyStreams; ++i) MACKO_HIP_TRY(hipStreamWaitEvent(ms->side[i], ms->fork, 0));
+  int result = MACKO_OK;
+  int turn = 0;
+  for (int64_t at = 0; at < n && result == MACKO_OK; at += MACKO_MAX_GROUP, ++turn) {
+    const int count = (int)std::min<int64_t>(MACKO_MAX_GROUP, n - at);
+    result = macko_spmv_group(count, handles + at, x_dev + at, y_dev + at, ms->side[turn % kManyStreams]);
+  }
+  // join, also after a failed launch: the caller's stream continues once every side stream is done
+  for (int i = 0; i < kManyStreams; ++i) {
+    hipError_t e = hipEventRecord(ms->join[i], ms->side[i]);
+    if (e == hipSuccess) e = hipStreamWaitEvent(main, ms->join[i], 0);
+    if (e != hipSuccess && result == MACKO_OK) result = macko::hip_fail(e);
+  }
+  return result;
 }
 
 int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void* Y_dev, int64_t ldy,

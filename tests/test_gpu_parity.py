@@ -910,3 +910,67 @@ def test_more_than_2_pow_31_stored_entries():
     torch.cuda.synchronize()
     err = np.abs(yd.float().cpu().numpy().astype(np.float64).reshape(100, 464) - y64[None, :])
     assert (err <= 1e-2 * s64[None, :] + 1e-3).all(), float(err.max())
+
+
+# ------------------------------------------------------------------ many independent products in one call
+
+def test_spmv_many_independent_products_eager_ordered_and_under_graph_capture():
+    """macko_spmv_many deals grouped launches to the library's side streams.  Every product must equal
+    the single-product call; work enqueued on the caller's stream before the call must be seen (the x
+    vectors are written by a kernel on that stream right before) and work enqueued after it must see
+    the results; captured into a graph, every replay must give the eager results again."""
+    shapes = [(600, 2048, 0.5), (333, 1024, 0.6), (1200, 4096, 0.4), (64, 512, 0.5), (2000, 1536, 0.7)]
+    mats, Ws = [], []
+    for i in range(21):                                         # 21 products: three launches over three streams
+        r, c, d = shapes[i % len(shapes)]
+        W = wl.bernoulli(r, c, d, 0.02, 91, i)
+        Ws.append(W)
+        mats.append(M.encode(W, [4, 2, 4, 8, 4][i % 5]).to_device() if i % 7 else M.encode_fp8(wl.fp8_values_of(W)).to_device())
+    xs_host = [wl.x_vector(W.shape[1], 91, i) for i, W in enumerate(Ws)]
+    src = [to_dev(x) for x in xs_host]
+    xs = [torch.zeros_like(s) for s in src]
+    ys = [torch.empty(W.shape[0], dtype=torch.float16, device="cuda") for W in Ws]
+    want = []
+    for m, s in zip(mats, src):
+        want.append(m.spmv(s).clone())
+    torch.cuda.synchronize()
+    many = M.SpmvMany(mats, xs, ys)
+    main = torch.cuda.Stream()
+    sums = [torch.zeros(1, dtype=torch.float32, device="cuda") for _ in ys]
+
+    def enqueue():
+        for x, s in zip(xs, src):                               # producers on the caller's stream ...
+            x.copy_(s)
+        many.launch(stream=torch.cuda.current_stream())
+        for y, acc in zip(ys, sums):                            # ... and consumers after the call
+            acc.copy_(y.float().abs().sum().reshape(1))
+
+    with torch.cuda.stream(main):
+        for rep in range(3):
+            for x in xs:
+                x.zero_()
+            for y in ys:
+                y.fill_(7.0)
+            enqueue()
+            main.synchronize()
+            for i, (y, w, acc) in enumerate(zip(ys, want, sums)):
+                assert torch.equal(y, w), f"eager rep {rep} product {i}"
+                assert float(acc) == float(w.float().abs().sum()), f"consumer saw stale y, product {i}"
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=main):
+            many.launch(stream=torch.cuda.current_stream())
+        for rep in range(3):
+            for y in ys:
+                y.fill_(7.0)
+            main.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for i, (y, w) in enumerate(zip(ys, want)):
+                assert torch.equal(y, w), f"replay {rep} product {i}"
+    # argument checks happen before anything is enqueued
+    lib = M.load_library()
+    assert lib.macko_spmv_many(-1, None, None, None, 0) < 0
+    assert lib.macko_spmv_many(0, None, None, None, 0) == 0
+    unbound = M.encode(Ws[0])
+    bad = M.SpmvMany(mats[:9] + [unbound], xs[:9] + [xs[0]], ys[:9] + [ys[0]])
+    assert bad.launch_raw(0) < 0
