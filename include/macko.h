@@ -6,7 +6,8 @@
  * b_val = 16 (fp16 values) and b_delta = 4 (4-bit delta-coded column
  * coordinates; 1, 2 and 8 bits through the _ex entry points, Appendix C), and
  * the product Y = M V of its Appendix A / Section 4.4, plus the dense fp16 GEMV
- * of Section 4.3 that the paper measures speedups against.
+ * of Section 4.3 that the paper measures speedups against.  The _fp8 entry
+ * points hold the same format with b_val = 8 (one byte per stored value).
  *
  * Conventions
  *   - Every function returns MACKO_OK (0) or a negative macko_status code; no
@@ -22,6 +23,7 @@
  *
  * Format layout (identical on host and device)
  *   values   uint16_t[alloc_nnz]   fp16 bits; +0 at padding entries and in the tail
+ *                                  (uint8_t[alloc_nnz], E4M3 bits, with 8-bit values)
  *   deltas   uint8_t [alloc_nnz/2] entry k is the 4-bit code (delta-1) in byte k>>1,
  *                                  bits 4*(k&1) .. 4*(k&1)+3
  *   row_ptr  uint32_t[rows+1]      index of each row's first entry
@@ -77,7 +79,7 @@ typedef struct macko_report {
   double effd_best;         /* eq. 8  at this d                                        */
   double effd_expected;     /* eq. 10 at this d                                        */
   double effd_worst;        /* eq. 9  at this d                                        */
-  int32_t b_val, b_delta;   /* 16; 4 unless an _ex call chose 1, 2 or 8                */
+  int32_t b_val, b_delta;   /* 16 (8 for the _fp8 calls); 4 unless an _ex call chose 1, 2 or 8 */
 } macko_report_t;
 
 /* ---- encoding (Section 4.1) ---------------------------------------------- */
