@@ -61,12 +61,12 @@ struct LaneCodesBytes {
 };
 template <>
 struct LaneCodes<4> : LaneCodesBytes<4> {
-  __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) { w = deltas[chunk]; }
+  __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) { w = load_stream(deltas + chunk); }
 };
 template <>
 struct LaneCodes<2> : LaneCodesBytes<2> {
   __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
-    w = reinterpret_cast<const uint16_t*>(deltas)[chunk];
+    w = load_stream(reinterpret_cast<const uint16_t*>(deltas) + chunk);
   }
 };
 
@@ -75,7 +75,7 @@ template <>
 struct LaneCodes<1> {
   uint32_t w;           // the 8 codes, entry k in bit k
   __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
-    w = reinterpret_cast<const uint8_t*>(deltas)[chunk];
+    w = load_stream(reinterpret_cast<const uint8_t*>(deltas) + chunk);
   }
   __device__ __forceinline__ void clear() { w = 0u; }
   __device__ __forceinline__ void keep_if(bool c) { w = c ? w : 0u; }
@@ -100,7 +100,7 @@ struct LaneCodes<8> {
   uint32_t X0, X1, X2, X3;
   uint32_t tot;
   __device__ __forceinline__ void load(const uint32_t* __restrict__ deltas, uint32_t chunk) {
-    const uint2 v = reinterpret_cast<const uint2*>(deltas)[chunk];
+    const uint2 v = load_stream(reinterpret_cast<const uint2*>(deltas) + chunk);
     w0 = v.x;
     w1 = v.y;
   }

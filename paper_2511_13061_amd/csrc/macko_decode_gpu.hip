@@ -41,7 +41,7 @@ expand_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ del
       LaneCodes<BD> w;
       w.load(deltas, chunk);
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (DENSE) v = values[chunk];
+      if (DENSE) v = load_stream(values + chunk);
       w.keep_if(e0 < end);
       w.decode();
       const uint32_t tot = w.total();

@@ -31,6 +31,24 @@ __host__ __device__ inline int64_t lds_bytes_for(int64_t cols, int b_delta = 4) 
   return front_pad_for(b_delta) + 16 * ((cols + 7) / 8) + back_pad_for(b_delta);
 }
 
+// ---- loads of data that is read once ------------------------------------------
+// The format arrays (and the dense matrix of the baseline) are streamed through once per
+// product; marking their loads non-temporal keeps them from displacing x, the row pointers
+// and each other's neighbours in the caches.  Measured on seven shapes: 3-5 % per product.
+typedef uint32_t macko_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t macko_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+  const macko_u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const macko_u32x4*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint2 load_stream(const uint2* p) {
+  const macko_u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const macko_u32x2*>(p));
+  return make_uint2(t.x, t.y);
+}
+__device__ __forceinline__ uint32_t load_stream(const uint32_t* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ uint16_t load_stream(const uint16_t* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ uint8_t load_stream(const uint8_t* p) { return __builtin_nontemporal_load(p); }
+
 // ---- DPP cross-lane primitives (wave64, GCN DPP controls) --------------------
 // row_shr:n shifts within a row of 16 lanes; row_bcast:15 / row_bcast:31 carry a
 // row's (half-wave's) last lane into the following rows.  Lanes without a source

@@ -85,7 +85,7 @@ __device__ __forceinline__ void gemv_wave_row_body(const uint4* __restrict__ W, 
         if (++ld_i < nb) src_next = src + ld8;
       }
     }
-    ring[j] = src[chunk];                                 // padding items re-read the previous address
+    ring[j] = load_stream(src + chunk);                   // padding items re-read the previous address
   };
   auto open_block = [&]() {
     ld_i = ld_step = cp_i = cp_step = 0;

@@ -172,7 +172,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
       chunk = 0;
     }
     wq[j].load(deltas, chunk);
-    vq[j] = values[chunk];
+    vq[j] = load_stream(values + chunk);
   };
   ld.i = 0;
   seek_nonempty(ld, nb, rp_lo, rp_hi);

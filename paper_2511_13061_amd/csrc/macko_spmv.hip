@@ -26,10 +26,10 @@ namespace {
 // The BD-bit codes of the 8 entries of chunk `chunk`, entry k in bits [BD k, BD (k+1)).
 template <int BD>
 __device__ __forceinline__ uint64_t load_chunk_codes(const uint32_t* __restrict__ deltas, uint32_t chunk) {
-  if (BD == 1) return reinterpret_cast<const uint8_t*>(deltas)[chunk];
-  if (BD == 2) return reinterpret_cast<const uint16_t*>(deltas)[chunk];
-  if (BD == 4) return deltas[chunk];
-  const uint2 v = reinterpret_cast<const uint2*>(deltas)[chunk];
+  if (BD == 1) return load_stream(reinterpret_cast<const uint8_t*>(deltas) + chunk);
+  if (BD == 2) return load_stream(reinterpret_cast<const uint16_t*>(deltas) + chunk);
+  if (BD == 4) return load_stream(deltas + chunk);
+  const uint2 v = load_stream(reinterpret_cast<const uint2*>(deltas) + chunk);
   return (uint64_t)v.x | ((uint64_t)v.y << 32);
 }
 
@@ -62,7 +62,7 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
       uint4 v = make_uint4(0, 0, 0, 0);
       if (e0 < end) {                  // the 8-entry chunk intersects [start, end)
         w = load_chunk_codes<BD>(deltas, e0 >> 3);
-        v = values[e0 >> 3];
+        v = load_stream(values + (e0 >> 3));
       }
       const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
       int d[8];
@@ -144,7 +144,7 @@ template <>
 struct LaneValues<16> {
   uint4 v;
   __device__ __forceinline__ void load(const void* __restrict__ values, uint32_t chunk) {
-    v = static_cast<const uint4*>(values)[chunk];
+    v = load_stream(static_cast<const uint4*>(values) + chunk);
   }
   __device__ __forceinline__ void keep_first(uint32_t nv) {       // clear the values of entries nv, nv+1, ...
     v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
@@ -162,7 +162,7 @@ template <>
 struct LaneValues<8> {
   uint2 v;
   __device__ __forceinline__ void load(const void* __restrict__ values, uint32_t chunk) {
-    v = static_cast<const uint2*>(values)[chunk];
+    v = load_stream(static_cast<const uint2*>(values) + chunk);
   }
   __device__ __forceinline__ void keep_first(uint32_t nv) {
     const uint32_t lo = nv >= 4 ? 4u : nv, hi = nv >= 8 ? 4u : (nv > 4 ? nv - 4u : 0u);
