@@ -298,6 +298,8 @@ MACKO_API int macko_last_hip_error(void);
  *   "spmv_resident_steps"  largest launch, in wavefront steps (512 entries) per compute unit,
  *                       that "spmv_resident" = 0 runs as one resident round, 0 default
  *   "spmv_steps_per_wave"  larger launches: steps of work per wavefront, 0 default
+ *   "spmv_step_align"   stored entries that the first step of every row is aligned to in the
+ *                       wave-per-row kernel (power of two, 8..512), 0 auto (by row length)
  *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8), "gemv_resident",
  *   "gemv_wgs_per_cu"   the same for the dense GEMV
  * Settings are process wide and not thread safe. */

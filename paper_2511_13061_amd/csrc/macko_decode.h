@@ -16,7 +16,7 @@ namespace macko {
 //   total()              doubled sum of the lane's 8 deltas
 //   offset<K>()          doubled position of entry K relative to the lane's start, minus 2
 //                        (= byte offset of its column in x when the lane starts at column 0)
-//   through(k)           lane 0's doubled position after entry k (k wavefront-uniform)
+//   through(k, l)        lane l's doubled position after its entry k (k and l wavefront-uniform)
 // ---------------------------------------------------------------------------
 template <int BD>
 struct LaneCodes;
@@ -54,8 +54,8 @@ struct LaneCodesBytes {
   __device__ __forceinline__ int offset() const {
     return (int)((((K & 1) ? P2 : E2) >> (8 * (K >> 1))) & 0xFFu);
   }
-  __device__ __forceinline__ uint32_t through(int k) const {
-    const uint32_t src = __builtin_amdgcn_readfirstlane((k & 1) ? P : E);
+  __device__ __forceinline__ uint32_t through(int k, int l = 0) const {
+    const uint32_t src = (uint32_t)__builtin_amdgcn_readlane((int)((k & 1) ? P : E), l);
     return ((src >> (8 * (k >> 1))) & 0xFFu) + 2u * (uint32_t)(k + 1);
   }
 };
@@ -85,8 +85,8 @@ struct LaneCodes<1> {
   __device__ __forceinline__ int offset() const {
     return 2 * __builtin_popcount(w & ((2u << K) - 1u)) + 2 * K;
   }
-  __device__ __forceinline__ uint32_t through(int k) const {
-    const uint32_t s = __builtin_amdgcn_readfirstlane(w);
+  __device__ __forceinline__ uint32_t through(int k, int l = 0) const {
+    const uint32_t s = (uint32_t)__builtin_amdgcn_readlane((int)w, l);
     return 2u * (uint32_t)__builtin_popcount(s & ((2u << k) - 1u)) + 2u * (uint32_t)(k + 1);
   }
 };
@@ -132,10 +132,10 @@ struct LaneCodes<8> {
     const uint32_t x = (K >> 1) == 0 ? X0 : ((K >> 1) == 1 ? X1 : ((K >> 1) == 2 ? X2 : X3));
     return (int)((K & 1) ? (x >> 16) : (x & 0xFFFFu)) - 2;
   }
-  __device__ __forceinline__ uint32_t through(int k) const {
-    // lane 0's four words as scalars, then a scalar choice
-    const uint32_t s0 = __builtin_amdgcn_readfirstlane(X0), s1 = __builtin_amdgcn_readfirstlane(X1);
-    const uint32_t s2 = __builtin_amdgcn_readfirstlane(X2), s3 = __builtin_amdgcn_readfirstlane(X3);
+  __device__ __forceinline__ uint32_t through(int k, int l = 0) const {
+    // lane l's four words as scalars, then a scalar choice
+    const uint32_t s0 = (uint32_t)__builtin_amdgcn_readlane((int)X0, l), s1 = (uint32_t)__builtin_amdgcn_readlane((int)X1, l);
+    const uint32_t s2 = (uint32_t)__builtin_amdgcn_readlane((int)X2, l), s3 = (uint32_t)__builtin_amdgcn_readlane((int)X3, l);
     const int i = k >> 1;
     const uint32_t src = i == 0 ? s0 : (i == 1 ? s1 : (i == 2 ? s2 : s3));
     return (k & 1) ? (src >> 16) : (src & 0xFFFFu);

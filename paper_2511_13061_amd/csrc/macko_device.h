@@ -148,13 +148,17 @@ __device__ __forceinline__ float f16_bits_to_f32(uint16_t b) {
 struct RowCursor {
   int i;               // row index within the block (== nb when exhausted)
   uint32_t start, end; // its entry range
-  uint32_t a0;         // start rounded down to 8 entries (reverse-offset alignment)
+  uint32_t a0;         // start rounded down to ALIGN entries: where the row's first step begins
   int nsteps, step;
 };
 
 // Move the cursor to the first non-empty row at or after cur.i.  Only lanes
 // below nb hold pointers of the wavefront's rows; others are never selected.
-__device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t rp_lo, uint32_t rp_hi) {
+// amask + 1 is the alignment of the row's first step in entries: 8 is the reverse-offset
+// alignment of the paper (a lane's 16-byte chunk never straddles the row start); larger powers
+// of two up to 512 make every step of the row begin on a multiple of that many entries.
+__device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t rp_lo, uint32_t rp_hi,
+                                              uint32_t amask = 7u) {
   cur.start = cur.end = 0;
   while (cur.i < nb) {
     cur.start = (uint32_t)__builtin_amdgcn_readlane((int)rp_lo, cur.i);
@@ -162,7 +166,7 @@ __device__ __forceinline__ void seek_nonempty(RowCursor& cur, int nb, uint32_t r
     if (cur.end > cur.start) break;
     ++cur.i;
   }
-  cur.a0 = cur.start & ~7u;
+  cur.a0 = cur.start & ~amask;
   cur.nsteps = (int)((cur.end - cur.a0 + 511u) >> 9);
   cur.step = 0;
 }

@@ -690,6 +690,7 @@ static int64_t* tuning_slot(const char* name) {
   if (n == "spmv_wgs_per_cu") return &t.spmv_wgs_per_cu;
   if (n == "spmv_steps_per_wave") return &t.spmv_steps_per_wave;
   if (n == "spmv_resident_steps") return &t.spmv_resident_steps;
+  if (n == "spmv_step_align") return &t.spmv_step_align;
   if (n == "gemv_resident") return &t.gemv_resident;
   if (n == "gemv_wgs_per_cu") return &t.gemv_wgs_per_cu;
   if (n == "gemv_block") return &t.gemv_block;
@@ -709,6 +710,8 @@ int macko_set_tuning(const char* name, int64_t value) {
   if ((n == "spmv_wgs_per_cu" || n == "gemv_wgs_per_cu") && value > 4) return MACKO_E_INVALID_ARG;
   if (n == "spmv_steps_per_wave" && value > 4096) return MACKO_E_INVALID_ARG;
   if (n == "spmv_resident_steps" && value > (int64_t{1} << 30)) return MACKO_E_INVALID_ARG;
+  if (n == "spmv_step_align" && value != 0 && (value < 8 || value > 512 || (value & (value - 1)) != 0))
+    return MACKO_E_INVALID_ARG;
   if (n == "spmv_lanes" && value != 0 && value != 16 && value != 32 && value != 64) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_block" || n == "gemv_block") && value != 0 && (value % 64 != 0 || value > 1024))
     return MACKO_E_INVALID_ARG;

@@ -23,6 +23,7 @@ struct Tuning {
   int64_t spmv_resident = 0;      // 0 auto, 1 never, 2 always one resident round of workgroups
   int64_t spmv_wgs_per_cu = 0;    // resident round: workgroups per compute unit (0 = planner's choice)
   int64_t spmv_steps_per_wave = 0; // many-workgroup regime: steps of work per wavefront (0 = default)
+  int64_t spmv_step_align = 0;     // entries a row's first step is aligned to (8 ... 512, power of two; 0 = by row length)
   int64_t spmv_resident_steps = 0; // largest work (steps per compute unit) launched as one resident round (0 = default)
   int64_t gemv_block = 0;
   int64_t gemv_rows_per_wg = 0;

@@ -186,7 +186,8 @@ struct SpmvMat {
   const uint16_t* x;
   uint16_t* y;
   int rows, cols, q, r;
-  int pad[2];
+  int amask;                // alignment of a row's first step in entries, minus 1 (7 ... 511)
+  int pad;
 };
 struct SpmvGroupArgs {
   SpmvMat m[kMaxGroup];
@@ -201,6 +202,25 @@ struct SpmvGroupHeader {
   int inv_nwaves;          // floor(65536 / wavefronts per workgroup) + 1
 };
 
+// Rows of at least kAlignMinEntries stored entries begin their first step on a multiple of
+// kStepAlign entries instead of where the row begins, so that the 1024 bytes of values and the
+// 64 * BD bytes of codes a wavefront requests per step are whole, aligned cache lines that no
+// other step touches (otherwise nine lines are touched for eight lines of values, and
+// neighbouring steps share lines).  The lanes of the first step that lie wholly before the row
+// are cleared and re-read the row's first chunk; the row costs a quarter step more on average.
+// Measured on 36864 x 12288: 4-9 % faster from 25 % to 80 % sparsity (rows of 5 steps and
+// more), 5-8 % slower at 90 % (3 steps), hence the threshold.  256 entries align the codes of
+// 4-bit matrices to their 128-byte lines as well; 512 was no better.
+constexpr int kStepAlign = 256;
+constexpr int kMaxStepAlign = 512;                     // what the "spmv_step_align" knob may ask for
+constexpr int64_t kAlignMinEntries = 1700;
+// cleared lanes in front of a row advance 16 bytes each below x[0]: the front guard grows by that
+constexpr int kAlignFrontPad = 2 * kMaxStepAlign;
+__host__ __device__ constexpr int spmv_front_pad(int b_delta) { return front_pad_for(b_delta) + kAlignFrontPad; }
+__host__ __device__ inline int64_t spmv_lds_bytes(int64_t cols, int b_delta) {
+  return lds_bytes_for(cols, b_delta) + kAlignFrontPad;
+}
+
 // The work of one workgroup: workgroup number `wg` of the matrix given by the
 // pointers, whose rows are dealt out q (+1 for the first r workgroups) at a time.
 template <int RING, bool SIMPLE, int BD, int VB = 16>
@@ -209,7 +229,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
                                                    const uint32_t* __restrict__ row_ptr,
                                                    const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
                                                    const int rows, const int cols, const int q, const int r,
-                                                   const int wg, const int inv_nwaves) {
+                                                   const int wg, const int inv_nwaves, const uint32_t amask) {
   extern __shared__ __align__(16) unsigned char lds[];
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
   const int row_begin = wg * q + min(wg, r);
@@ -217,7 +237,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
   const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const unsigned char* xbase = lds + front_pad_for(BD);   // LDS address of x[0]
+  const unsigned char* xbase = lds + spmv_front_pad(BD);   // LDS address of x[0]
   const uint32_t lane8 = 8u * lane;
   const int per_wave = (wg_rows * inv_nwaves) >> 16;   // wg_rows / nwaves (exact for wg_rows <= 1024)
   const int extra = wg_rows - per_wave * nwaves;         // wg_rows % nwaves
@@ -235,10 +255,11 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
   auto issue = [&](int j) {
     if (ld.i < nb) {
       const uint32_t e0 = ld.a0 + 512u * ld.step + lane8;
-      chunk = min(e0, ld.end - 1u) >> 3;
+      // lanes before the row (first step) or past it (last step) re-read its first / last chunk
+      chunk = min(max(e0, ld.start & ~7u), ld.end - 1u) >> 3;
       if (++ld.step == ld.nsteps) {
         ++ld.i;
-        seek_nonempty(ld, nb, rp_lo, rp_hi);
+        seek_nonempty(ld, nb, rp_lo, rp_hi, amask);
       }
     }                  // else a padding item: every lane re-reads its previous chunk (a line it has just
                        // used; one fixed address would make every wavefront queue at the same L2 channel)
@@ -252,7 +273,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
   };
   auto prime_ring = [&]() {
     ld.i = 0;
-    seek_nonempty(ld, nb, rp_lo, rp_hi);
+    seek_nonempty(ld, nb, rp_lo, rp_hi, amask);
     cp = ld;
 #pragma unroll
     for (int j = 0; j < RING; ++j) issue(j);
@@ -265,7 +286,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
   fetch_row_ptrs();
   stage_x_begin(xst, x, cols);
   prime_ring();
-  stage_x_finish<SIMPLE>(lds, xst, x, cols, front_pad_for(BD), back_pad_for(BD));  // ends with a barrier
+  stage_x_finish<SIMPLE>(lds, xst, x, cols, spmv_front_pad(BD), back_pad_for(BD));  // ends with a barrier
 
   {
     float yv = 0.0f;                                   // lane i: result of row blk + i
@@ -281,18 +302,23 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
         if (!live) base2 = 0;                          // keep the (unused) gathers of padding items in range
         const uint32_t end_eff = live ? cp.end : 0u;
         const uint32_t e0 = cp.a0 + 512u * cp.step + lane8;
-        if (!live || cp.step == cp.nsteps - 1) {       // clear what lies past the row end
-          const uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;   // valid entries in this lane's chunk
+        const bool first = live && cp.step == 0;
+        const int before = (int)(cp.start - cp.a0);    // entries in front of the row in its first step
+        if (!live || cp.step == cp.nsteps - 1 || (first && before >= 8)) {
+          // clear what lies past the row end, and the lanes that lie wholly before its start
+          uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;   // valid entries in this lane's chunk
+          if (first && (int)lane8 + 8 <= before) nv = 0u;
           w.keep_if(nv != 0);
           v.keep_first(nv);
         }
         w.decode();
         const uint32_t tot = w.total();                // doubled sum of this lane's 8 deltas
         const uint32_t incl = wave_incl_scan_u32(tot);
-        if (live && cp.step == 0) {
-          base2 = 0;
-          const int before = (int)(cp.start - cp.a0);  // entries of the previous row in lane 0's chunk
-          if (before > 0) base2 = -(int)w.through(before - 1);
+        if (first) {
+          // the row's first entry must land on its own column: the cleared lanes in front of it advance
+          // 16 bytes each, and the lane that holds the start counts its entries of the previous row
+          base2 = -2 * (before & ~7);
+          if (before & 7) base2 -= (int)w.through((before & 7) - 1, before >> 3);
         }
         const int lanebase = base2 + (int)(incl - tot);   // byte offset in x of the lane's chunk start
 #define MACKO_X(k) gather_x(xbase, lanebase + w.template offset<k>())
@@ -313,7 +339,7 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
           yv = lane == cp.i ? __builtin_bit_cast(float, tbits) : yv;
           acc = 0.0f;
           ++cp.i;
-          seek_nonempty(cp, nb, rp_lo, rp_hi);
+          seek_nonempty(cp, nb, rp_lo, rp_hi, amask);
         }
       }
     }
@@ -337,19 +363,19 @@ spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4,
   }
   spmv_wave_row_body<RING, SIMPLE, BD, VB>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
                                        g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
-                                       inv_nwaves);
+                                       inv_nwaves, (uint32_t)g.m[mi].amask);
 }
 
-// One matrix: everything the workgroup needs is a scalar argument (15 registers),
+// One matrix: everything the workgroup needs is a scalar argument (16 registers),
 // so a starting wavefront goes straight to its row pointers without any argument load.
 template <int RING, bool SIMPLE, int BD>
 __global__ void __launch_bounds__(1024)
 spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
                      const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
                      uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
-                     const int inv_nwaves) {
+                     const int inv_nwaves, const int amask) {
   spmv_wave_row_body<RING, SIMPLE, BD>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
-                                       inv_nwaves);
+                                       inv_nwaves, (uint32_t)amask);
 }
 
 // One matrix with 8-bit values (4-bit codes): 8 bytes of values and 4 bytes of codes per lane and step.
@@ -358,9 +384,9 @@ __global__ void __launch_bounds__(1024)
 spmv_wave_row_fp8_kernel(const uint2* __restrict__ values, const uint32_t* __restrict__ deltas,
                          const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
                          uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
-                         const int inv_nwaves) {
+                         const int inv_nwaves, const int amask) {
   spmv_wave_row_body<2, SIMPLE, 4, 8>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
-                                      inv_nwaves);
+                                      inv_nwaves, (uint32_t)amask);
 }
 
 // y = 0 for a matrix without stored entries
@@ -469,7 +495,7 @@ int launch_wave_row_fp8(const SpmvGroupArgs& args, const SpmvGroupHeader& head, 
     if (st != MACKO_OK) return st;
     const SpmvMat& m = args.m[0];
     hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, static_cast<const uint2*>(m.values), m.deltas,
-                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves);
+                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves, m.amask);
   } else {
     using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
     KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, 4, 8> : (KG)spmv_wave_row_kernel<2, false, 4, 8>;
@@ -489,7 +515,7 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
   const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
   if (nwr == 1) {
     using K1 = void (*)(const uint4*, const uint32_t*, const uint32_t*, const uint16_t*, uint16_t*, int, int, int,
-                        int, int);
+                        int, int, int);
     K1 kfn = simple ? (K1)spmv_wave_row_kernel<2, true, BD> : (K1)spmv_wave_row_kernel<2, false, BD>;
     if (BD == 4 && ring == 4)
       kfn = simple ? (K1)spmv_wave_row_kernel<4, true, 4> : (K1)spmv_wave_row_kernel<4, false, 4>;
@@ -499,7 +525,7 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
     if (st != MACKO_OK) return st;
     const SpmvMat& m = args.m[0];
     hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, static_cast<const uint4*>(m.values), m.deltas,
-                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves);
+                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves, m.amask);
   } else {
     using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
     KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD> : (KG)spmv_wave_row_kernel<2, false, BD>;
@@ -527,7 +553,7 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, in
     const SpmvProblem& p = *wr[i];
     in[i].rows = p.rows;
     in[i].steps_per_row = std::max<int64_t>(1, (p.pad_nnz / p.rows + 511) / 512);
-    in[i].lds_bytes = lds_bytes_for(p.cols, b_delta);
+    in[i].lds_bytes = spmv_lds_bytes(p.cols, b_delta);
     total_steps += in[i].rows * in[i].steps_per_row;
     max_lds = std::max(max_lds, in[i].lds_bytes);
   }
@@ -541,7 +567,7 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, in
   // the better (4-8 % measured on the 18944 .. 49152 column shapes).
   const int64_t resident_steps = t.spmv_resident_steps ? t.spmv_resident_steps : kResidentStepsPerCu;
   const bool small = total_steps <= (int64_t)cus * resident_steps;
-  const bool wide = max_lds >= kWideLdsBytes;
+  const bool wide = max_lds - kAlignFrontPad >= kWideLdsBytes;
   if (t.spmv_rows_per_wg == 0 && (t.spmv_resident == 2 || (t.spmv_resident == 0 && (small || wide)))) {
     const int k = t.spmv_wgs_per_cu ? (int)t.spmv_wgs_per_cu : (wide ? 1 : 0);
     planned = plan_resident(plan, nwr, in, cus, (int)t.spmv_block, k);
@@ -555,7 +581,7 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, in
     // launches of 30-70 us, fewer than 6 slower again on short rows.  Every workgroup holds its own
     // copy of x in LDS; when that copy is large (more than ~24 K columns) only
     // one to three fit a compute unit, so each brings 16 wavefronts instead of 8.
-    const int block = t.spmv_block ? (int)t.spmv_block : (max_lds > 48 * 1024 ? 1024 : 512);
+    const int block = t.spmv_block ? (int)t.spmv_block : (max_lds - kAlignFrontPad > 48 * 1024 ? 1024 : 512);
     const int nwaves = block / 64;
     int64_t group_rows = 0;
     for (int i = 0; i < nwr; ++i) group_rows += in[i].rows;
@@ -592,6 +618,10 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, in
     m.cols = (int)p.cols;
     m.q = plan.m[i].q;
     m.r = plan.m[i].r;
+    const int64_t align_knob = t.spmv_step_align;      // 0: by row length
+    const int align = align_knob ? (int)align_knob : (p.pad_nnz / p.rows >= kAlignMinEntries ? kStepAlign : 8);
+    m.amask = std::min(std::max(align, 8), kMaxStepAlign) - 1;
+    m.pad = 0;
     head.wg_begin[i] = (int)wg_begin;
     wg_begin += plan.m[i].nwg;
     // the lean start-up path needs an aligned x whose length is a multiple of 8 and fits the staging registers
@@ -628,7 +658,7 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   const Tuning& t = tuning();
   auto wants_wave_row = [&](const SpmvProblem& p) {
     if (p.rows == 0 || p.pad_nnz == 0) return false;
-    if (lds_bytes_for(p.cols, p.b_delta) > kMaxLdsBytes) return false;
+    if (spmv_lds_bytes(p.cols, p.b_delta) > kMaxLdsBytes) return false;
     if (t.spmv_kernel != 0) return t.spmv_kernel == 2;
     return p.pad_nnz / p.rows >= kWaveRowMinEntries;
   };
@@ -644,7 +674,7 @@ int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
       hipError_t e0 = hipGetLastError();
       if (e0 != hipSuccess) return hip_fail(e0);
     } else if (p.b_val == 8) {                          // 8-bit values: 4-bit codes, wave-per-row kernel only
-      if (p.b_delta != 4 || lds_bytes_for(p.cols, 4) > kMaxLdsBytes) return MACKO_E_UNSUPPORTED;
+      if (p.b_delta != 4 || spmv_lds_bytes(p.cols, 4) > kMaxLdsBytes) return MACKO_E_UNSUPPORTED;
     } else if (!wants_wave_row(p)) {                    // short rows or x larger than LDS: own launch
       int st = launch_subwave(p, (int)t.spmv_lanes, stream);
       if (st != MACKO_OK) return st;

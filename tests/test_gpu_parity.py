@@ -25,7 +25,7 @@ def _need_gpu_and_library():
     M.load_library()          # raises if libmacko.so is missing: no fallback
     yield
     for knob in ("spmv_kernel", "spmv_lanes", "spmv_block", "spmv_rows_per_wg", "spmv_ring", "spmv_resident",
-                 "spmv_wgs_per_cu", "spmv_resident_steps", "spmv_steps_per_wave", "gemv_block", "gemv_rows_per_wg", "gemv_ring", "gemv_resident",
+                 "spmv_wgs_per_cu", "spmv_resident_steps", "spmv_steps_per_wave", "spmv_step_align", "gemv_block", "gemv_rows_per_wg", "gemv_ring", "gemv_resident",
                  "gemv_wgs_per_cu"):
         M.set_tuning(knob, 0)
 
@@ -93,6 +93,10 @@ VARIANTS = {
     "wave_row_b64_r200": {"spmv_kernel": 2, "spmv_block": 64, "spmv_rows_per_wg": 200},
     "wave_row_b256_r37": {"spmv_kernel": 2, "spmv_block": 256, "spmv_rows_per_wg": 37},
     "wave_row_b128_r63": {"spmv_kernel": 2, "spmv_block": 128, "spmv_rows_per_wg": 63},
+    # every step of a row on a multiple of 64 / 256 / 512 stored entries (lanes before the row cleared)
+    "wave_row_align64": {"spmv_kernel": 2, "spmv_step_align": 64},
+    "wave_row_align256_b256_r37": {"spmv_kernel": 2, "spmv_step_align": 256, "spmv_block": 256, "spmv_rows_per_wg": 37},
+    "wave_row_align512": {"spmv_kernel": 2, "spmv_step_align": 512},
 }
 
 
@@ -117,7 +121,8 @@ def test_spmv_empty_rows_mixed_with_full_rows_and_row_boundaries_inside_chunks()
         cols = rng.choice(C, size=(r - 39) % 10 + 1, replace=False)
         W[r, cols] = wl.normal_f16(cols.size, 1.0, 11, r, nonzero=True)
     x = wl.x_vector(C, 11, 1)
-    for variant in ("auto", "wave_row", "sub16", "wave_row_b64_r200", "wave_row_b256_r37", "wave_row_b128_r63"):
+    for variant in ("auto", "wave_row", "sub16", "wave_row_b64_r200", "wave_row_b256_r37", "wave_row_b128_r63",
+                    "wave_row_align64", "wave_row_align256_b256_r37", "wave_row_align512"):
         y = spmv_case(W, x, **VARIANTS[variant])
         check_y(y, W, x, variant)
         assert (y[10:30] == 0).all() and (y[395:] == 0).all()
@@ -283,7 +288,8 @@ WIDTH_CASES = {
 }
 
 
-@pytest.mark.parametrize("variant", ["auto", "sub32", "wave_row", "wave_row_b64_r200", "wave_row_b256_r37"])
+@pytest.mark.parametrize("variant", ["auto", "sub32", "wave_row", "wave_row_b64_r200", "wave_row_b256_r37",
+                                     "wave_row_align64", "wave_row_align256_b256_r37", "wave_row_align512"])
 @pytest.mark.parametrize("b_delta", [1, 2, 8])
 @pytest.mark.parametrize("case", list(WIDTH_CASES))
 def test_spmv_other_code_widths(case, b_delta, variant):
@@ -783,11 +789,13 @@ FP8_CASES = {
 }
 
 
-@pytest.mark.parametrize("variant", ["auto", "resident", "many_wgs_b256", "many_wgs_r37_b128"])
+@pytest.mark.parametrize("variant", ["auto", "resident", "many_wgs_b256", "many_wgs_r37_b128", "align64",
+                                     "align512_b256"])
 @pytest.mark.parametrize("case", list(FP8_CASES))
 def test_spmv_with_8_bit_values(case, variant):
     knobs = {"auto": {}, "resident": {"spmv_resident": 2}, "many_wgs_b256": {"spmv_resident": 1, "spmv_block": 256},
-             "many_wgs_r37_b128": {"spmv_resident": 1, "spmv_rows_per_wg": 37, "spmv_block": 128}}[variant]
+             "many_wgs_r37_b128": {"spmv_resident": 1, "spmv_rows_per_wg": 37, "spmv_block": 128},
+             "align64": {"spmv_step_align": 64}, "align512_b256": {"spmv_step_align": 512, "spmv_block": 256}}[variant]
     c = FP8_CASES[case]()
     W = c.W.copy()
     if W.shape[0] > 40:
@@ -813,7 +821,14 @@ def test_spmv_with_8_bit_values(case, variant):
     rep = g.get_report()
     assert (rep.b_val, rep.nnz, rep.pad_nnz, rep.alloc_nnz, rep.total_bytes) == \
         (8, enc.nnz, enc.pad_nnz, enc.alloc_nnz, enc.total_bytes)
-    assert torch.equal(g.spmv(to_dev(c.x)), y)
+    for k, v in knobs.items():                          # same launch shape, hence the same summation order
+        M.set_tuning(k, v)
+    try:
+        yg = g.spmv(to_dev(c.x))
+    finally:
+        for k in knobs:
+            M.set_tuning(k, 0)
+    assert torch.equal(yg, y)
     assert m.check_device() is None
     assert np.array_equal(m.columns_device().cpu().numpy()[: enc.pad_nnz], oracle.unpack(enc)[1])
 

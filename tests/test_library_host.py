@@ -162,6 +162,12 @@ def test_empty_shapes_and_error_codes():
     M.set_tuning("spmv_block", 256)
     assert M.get_tuning("spmv_block") == 256
     M.set_tuning("spmv_block", 0)
+    for bad in (4, 100, 1024):                            # a power of two from 8 to 512
+        with pytest.raises(M.MackoError):
+            M.set_tuning("spmv_step_align", bad)
+    M.set_tuning("spmv_step_align", 128)
+    assert M.get_tuning("spmv_step_align") == 128
+    M.set_tuning("spmv_step_align", 0)
     lib.macko_destroy(None)
 
 
