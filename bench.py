@@ -138,6 +138,13 @@ def time_single_op(torch, op, stream_ptr, n_warm, n_timed):
     return time_region(torch, fn, n_warm, n_timed) / n_timed
 
 
+# Secondary measurements (sweep, shapes, widths, small batch, stress matrices): the paper's protocol of
+# 100 warm-up and 1000 timed launches (Section 5.1).  Short regions read up to 8 % slow: the
+# clocks need tens of milliseconds of load to settle after the set-up work in between.
+SIDE_WARM, SIDE_TIMED = 100, 1000
+STACK_WARM, STACK_TIMED = 10, 40      # passes over the 32-layer stack (2-4 ms each)
+
+
 def copies_for(nbytes, total=2 << 30):
     """Enough copies that consecutive uses of one copy are separated by more than
     the last-level cache, within a bounded footprint."""
@@ -499,7 +506,7 @@ def main():
             # rotate over >= 1 GiB of copies: two copies of the 90 % matrix (278 MB) would half fit the 256 MB cache
             nc = copies_for(int(2.5 * case.rows * case.cols * (1 - s / 100.0)), 1 << 30)
             so = SparseOp(M, torch, case, copies=nc)
-            ts = time_single_op(torch, so, stream_ptr, max(20, nc), 100)
+            ts = time_single_op(torch, so, stream_ptr, max(SIDE_WARM, nc), SIDE_TIMED)
             row = {"macko_us": round(ts * 1e6, 1), "macko_GBps": round(so.bytes / ts / 1e9, 1),
                    "frac_of_peak": round(so.bytes / ts / 1e9 / HBM_PEAK_GBPS, 4),
                    "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
@@ -509,12 +516,12 @@ def main():
                 st = so.handles[i % nc].spmv_raw(so.x.data_ptr(), so.y.data_ptr(), sp)
                 if st != 0:
                     raise RuntimeError(f"launch failed with status {st}")
-            t3 = time_multi_stream(torch, launch3, max(20, nc), 100)
+            t3 = time_multi_stream(torch, launch3, max(SIDE_WARM, nc), SIDE_TIMED)
             row["three_streams_us"] = round(t3 * 1e6, 1)
             row["three_streams_frac_of_peak"] = round(so.bytes / t3 / 1e9 / HBM_PEAK_GBPS, 4)
             if s == 0:
                 do = DenseOp(M, torch, case, copies=2)
-                dense_t = time_single_op(torch, do, stream_ptr, 20, 100)
+                dense_t = time_single_op(torch, do, stream_ptr, SIDE_WARM, SIDE_TIMED)
                 row["dense_us"] = round(dense_t * 1e6, 1)
                 row["dense_GBps"] = round(do.bytes / dense_t / 1e9, 1)
                 del do
@@ -531,8 +538,8 @@ def main():
         for case in (wl.config4(), wl.config4b()):
             so = SparseOp(M, torch, case, copies=12)
             do = DenseOp(M, torch, case, copies=8)
-            ts = time_single_op(torch, so, stream_ptr, 10, 100)
-            td = time_single_op(torch, do, stream_ptr, 10, 100)
+            ts = time_single_op(torch, so, stream_ptr, SIDE_WARM, SIDE_TIMED)
+            td = time_single_op(torch, do, stream_ptr, SIDE_WARM, SIDE_TIMED)
             rep = so.report
             table[case.name] = {
                 "macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
@@ -568,7 +575,7 @@ def main():
                     st = ms[i % nc].spmv_raw(x.data_ptr(), y.data_ptr(), stream_ptr)
                     if st != 0:
                         raise RuntimeError(f"macko_spmv failed with status {st}")
-                t = time_region(torch, f, max(5, nc), 30 + nc) / (30 + nc)
+                t = time_region(torch, f, max(SIDE_WARM, nc), SIDE_TIMED) / SIDE_TIMED
                 row[f"b_delta_{b}"] = {"macko_us": round(t * 1e6, 1), "GBps": round(spmv_bytes(rep) / t / 1e9),
                                        "effd": round(rep.effd, 4),
                                        "padding_per_nnz": round(rep.padding_entries / max(rep.nnz, 1), 4)}
@@ -601,8 +608,8 @@ def main():
                 def g(i):
                     torch.matmul(X, Wd[i % 8].t(), out=Y)          # library GEMM on the dense matrix
 
-                ts = time_region(torch, f, 10, 200) / 200
-                td = time_region(torch, g, 10, 200) / 200
+                ts = time_region(torch, f, SIDE_WARM, SIDE_TIMED) / SIDE_TIMED
+                td = time_region(torch, g, SIDE_WARM, SIDE_TIMED) / SIDE_TIMED
                 row[f"batch{B}"] = {"macko_us": round(ts * 1e6, 2), "dense_library_gemm_us": round(td * 1e6, 2),
                                     "format_GBps": round(so.bytes / ts / 1e9)}
             table[f"{case.rows}x{case.cols}"] = row
@@ -620,9 +627,8 @@ def main():
                 nb = int(2.5 * r * c * (1 - pct / 100.0))
                 so = SparseOp(M, torch, case, copies=copies_for(nb, 1 << 30))
                 do = DenseOp(M, torch, case, copies=copies_for(2 * r * c, 1 << 30))
-                n = 200 if nb < (100 << 20) else 40
-                ts = time_single_op(torch, so, stream_ptr, 10, n)
-                td = time_single_op(torch, do, stream_ptr, 10, n)
+                ts = time_single_op(torch, so, stream_ptr, SIDE_WARM, SIDE_TIMED)
+                td = time_single_op(torch, do, stream_ptr, SIDE_WARM, SIDE_TIMED)
                 table[f"{r}x{c}"] = {"macko_us": round(ts * 1e6, 1), "dense_us": round(td * 1e6, 1),
                                      "macko_GBps": round(so.bytes / ts / 1e9), "dense_GBps": round(do.bytes / td / 1e9),
                                      "speedup_vs_dense": round(td / ts, 3)}
@@ -684,12 +690,12 @@ def main():
                     g.launch_raw(stream_ptr)
             return run
 
-        ts32 = time_region(torch, layer_groups("sparse"), 2, 10) / 10
-        td32 = time_region(torch, layer_groups("dense"), 2, 10) / 10
-        ts1 = time_region(torch, stack_pass(ops13), 2, 10) / 10
-        td1 = time_region(torch, stack_pass(dops13), 2, 10) / 10
-        ts = time_region(torch, grouped_stack("sparse"), 2, 10) / 10
-        td = time_region(torch, grouped_stack("dense"), 2, 10) / 10
+        ts32 = time_region(torch, layer_groups("sparse"), STACK_WARM, STACK_TIMED) / STACK_TIMED
+        td32 = time_region(torch, layer_groups("dense"), STACK_WARM, STACK_TIMED) / STACK_TIMED
+        ts1 = time_region(torch, stack_pass(ops13), STACK_WARM, STACK_TIMED) / STACK_TIMED
+        td1 = time_region(torch, stack_pass(dops13), STACK_WARM, STACK_TIMED) / STACK_TIMED
+        ts = time_region(torch, grouped_stack("sparse"), STACK_WARM, STACK_TIMED) / STACK_TIMED
+        td = time_region(torch, grouped_stack("dense"), STACK_WARM, STACK_TIMED) / STACK_TIMED
         # the same 128 grouped launches dealt to three streams in turn: the products of this workload are
         # independent, and kernels of different streams overlap (the next one starts on the compute units
         # the previous one has already left)
@@ -728,12 +734,12 @@ def main():
             st = many.launch_raw(stream_ptr)
             if st != 0:
                 raise RuntimeError(f"macko_spmv_many failed with status {st}")
-        tsm = time_region(torch, many_pass, 2, 10) / 10
+        tsm = time_region(torch, many_pass, STACK_WARM, STACK_TIMED) / STACK_TIMED
         del many
-        ts224 = time_multi_stream(torch, separate_over_streams(ops13), 2 * 224, 10 * 224) * 224
-        td224 = time_multi_stream(torch, separate_over_streams(dops13), 2 * 224, 10 * 224) * 224
-        ts3 = time_multi_stream(torch, over_streams("sparse"), 2 * 128, 10 * 128) * 128
-        td3 = time_multi_stream(torch, over_streams("dense"), 2 * 128, 10 * 128) * 128
+        ts224 = time_multi_stream(torch, separate_over_streams(ops13), STACK_WARM * 224, STACK_TIMED * 224) * 224
+        td224 = time_multi_stream(torch, separate_over_streams(dops13), STACK_WARM * 224, STACK_TIMED * 224) * 224
+        ts3 = time_multi_stream(torch, over_streams("sparse"), STACK_WARM * 128, STACK_TIMED * 128) * 128
+        td3 = time_multi_stream(torch, over_streams("dense"), STACK_WARM * 128, STACK_TIMED * 128) * 128
         sb = 32 * sum(m * ops13[t].bytes for t, m in plan13)
         db = 32 * sum(m * dops13[t].bytes for t, m in plan13)
         stack_key = "stack_llama2_13b_32layers"
