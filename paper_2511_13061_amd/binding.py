@@ -83,6 +83,13 @@ def load_library():
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2511_13061_amd.build` "
             "(or __graft_entry__.build()); there is no CPU fallback")
+    # PyTorch ships its own copy of the HIP runtime.  When it is going to be used in this process it has
+    # to be loaded before this library, so that both bind to the same runtime: the other order leaves
+    # the process without a visible device (hipErrorNoDevice from the first call that touches the GPU).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     i64p = ctypes.POINTER(i64)
