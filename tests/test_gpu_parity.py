@@ -617,6 +617,11 @@ EXPAND_CASES["empty_rows_257x1500"] = lambda: (_with_empty_rows(wl.bernoulli(257
                                                 wl.x_vector(1500, 61, 1))
 EXPAND_CASES["first_nonzero_late_64x5000"] = lambda: (_late_start(wl.bernoulli(64, 5000, 0.6, 0.02, 61, 2)),
                                                        wl.x_vector(5000, 61, 2))
+# row buffers of the one-pass decoder: two wavefronts per workgroup, one, and rows too long for LDS
+EXPAND_CASES["wide_6x30000"] = lambda: (wl.bernoulli(6, 30000, 0.5, 0.02, 61, 3), wl.x_vector(30000, 61, 3))
+EXPAND_CASES["wide_5x45000"] = lambda: (wl.bernoulli(5, 45000, 0.4, 0.02, 61, 4), wl.x_vector(45000, 61, 4))
+EXPAND_CASES["too_wide_for_lds_3x90000"] = lambda: (wl.bernoulli(3, 90000, 0.3, 0.02, 61, 5),
+                                                     wl.x_vector(90000, 61, 5))
 
 
 def _with_empty_rows(W):
