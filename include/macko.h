@@ -216,10 +216,11 @@ MACKO_API int macko_columns_device(macko_handle_t h, int32_t* cols_dev, void* st
 /* The dense rows x cols fp16 matrix back from the bound device arrays (the
  * format is lossless, Section 5.2; -0 inputs come back as +0).
  * dense_dev: fp16 [rows x ld] on the device, ld >= cols elements, 2-byte
- * aligned (16-byte aligned with ld and cols multiples of 8 for the fast zero
- * fill), caller owned, must not overlap the format arrays.  Cells [r][0, cols)
- * are overwritten, cells between cols and ld are left untouched.  Enqueues two
- * kernels on `stream` and does not synchronise. */
+ * aligned (16-byte aligned with ld and cols multiples of 8 for full-width
+ * stores), caller owned, must not overlap the format arrays.  Cells [r][0, cols)
+ * are overwritten, cells between cols and ld are left untouched.  Enqueues one
+ * kernel on `stream` (two for rows of more than 81920 columns) and does not
+ * synchronise. */
 MACKO_API int macko_decode_device(macko_handle_t h, void* dense_dev, int64_t ld, void* stream);
 
 /* ---- the product (Section 4.4; Y = M V of Appendix A) --------------------- */
