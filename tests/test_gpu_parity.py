@@ -128,6 +128,32 @@ def test_spmv_empty_rows_mixed_with_full_rows_and_row_boundaries_inside_chunks()
         assert (y[10:30] == 0).all() and (y[395:] == 0).all()
 
 
+@pytest.mark.parametrize("b_delta", [1, 4, 8])
+def test_aligned_steps_with_rows_starting_at_chosen_offsets(b_delta):
+    """Rows whose first k columns are non-zero (no padding), so that every row starts at a known
+    entry: multiples of the step alignment, one entry after, eight after, one before; rows of one
+    entry, empty rows and rows of exactly one and two steps between them.  Each alignment of the
+    wave-per-row kernel, and the choice it makes by itself."""
+    C = 4096
+    lengths = [512, 256, 1, 7, 8, 9, 247, 248, 1, 255, 256, 257, 0, 0, 3, 1024, 511, 513, 2048, 64, 63, 65,
+               4096, 1, 4095, 0, 1536, 8, 504, 16, 1000, 3000, 2, 510, 4096, 4096, 5, 251]
+    W = np.zeros((len(lengths), C), dtype=np.uint16)
+    for r, n in enumerate(lengths):
+        if n:
+            W[r, :n] = wl.normal_f16(n, 1.0, 77, r, nonzero=True)
+    x = wl.x_vector(C, 77, 1)
+    enc = oracle.encode(W, b_delta)
+    assert enc.pad_nnz == sum(lengths) and list(np.diff(enc.row_ptr.astype(np.int64))) == lengths
+    for knobs in ({}, {"spmv_kernel": 2}, {"spmv_kernel": 2, "spmv_step_align": 64},
+                  {"spmv_kernel": 2, "spmv_step_align": 256, "spmv_block": 128, "spmv_rows_per_wg": 5},
+                  {"spmv_kernel": 2, "spmv_step_align": 512, "spmv_block": 64, "spmv_rows_per_wg": 38},
+                  {"spmv_kernel": 2, "spmv_step_align": 512, "spmv_ring": 4},
+                  {"spmv_kernel": 2, "spmv_step_align": 16, "spmv_ring": 3}):
+        y = spmv_case(W, x, b_delta, **knobs)
+        check_y(y, W, x, f"b{b_delta}/{knobs}")
+        assert y[12] == 0 and y[13] == 0 and y[25] == 0
+
+
 RESIDENT_VARIANTS = {
     "auto": {},
     "never": {"spmv_resident": 1},
