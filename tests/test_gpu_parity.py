@@ -646,6 +646,8 @@ EXPAND_CASES["first_nonzero_late_64x5000"] = lambda: (_late_start(wl.bernoulli(6
 # row buffers of the one-pass decoder: two wavefronts per workgroup, one, and rows too long for LDS
 EXPAND_CASES["wide_6x30000"] = lambda: (wl.bernoulli(6, 30000, 0.5, 0.02, 61, 3), wl.x_vector(30000, 61, 3))
 EXPAND_CASES["wide_5x45000"] = lambda: (wl.bernoulli(5, 45000, 0.4, 0.02, 61, 4), wl.x_vector(45000, 61, 4))
+EXPAND_CASES["exactly_lds_2x81920"] = lambda: (wl.bernoulli(2, 81920, 0.2, 0.02, 61, 6), wl.x_vector(81920, 61, 6))
+EXPAND_CASES["just_over_lds_2x81928"] = lambda: (wl.bernoulli(2, 81928, 0.2, 0.02, 61, 7), wl.x_vector(81928, 61, 7))
 EXPAND_CASES["too_wide_for_lds_3x90000"] = lambda: (wl.bernoulli(3, 90000, 0.3, 0.02, 61, 5),
                                                      wl.x_vector(90000, 61, 5))
 
