@@ -115,6 +115,17 @@ MACKO_API int macko_wrap_device(int64_t rows, int64_t cols, int64_t pad_nnz, con
  * other b_delta is MACKO_E_INVALID_ARG. */
 MACKO_API int macko_encode_ex(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                               int b_delta, macko_handle_t* out, macko_report_t* report);
+
+/* Storage of the matrix for every code width without encoding it (Section 4.2,
+ * eq. 8 with the padding counted exactly instead of estimated; Appendix C):
+ * total_bytes[i] = values + codes + row pointers for b_delta = 1, 2, 4, 8
+ * (i = 0..3), as macko_report.total_bytes would give it, or -1 for a width
+ * whose entry count does not fit 32-bit row pointers.  *best_b_delta (may be
+ * NULL) is the width with the fewest bytes, the paper's 4 bits on a tie with
+ * it, else the narrower one; 0 if no width fits.  dense_host as for
+ * macko_encode; one pass over the matrix per width. */
+MACKO_API int macko_storage_by_code_width(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
+                                          int64_t total_bytes[4], int* best_b_delta);
 MACKO_API int macko_encode_device_ex(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld,
                                      int b_delta, void* stream, macko_handle_t* out,
                                      macko_report_t* report);

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     set_tuning,
     spmv_group,
     status_string,
+    storage_by_code_width,
     wrap_device,
     wrap_device_fp8,
 )

@@ -14,7 +14,7 @@ _lib = None
 
 EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
-    "macko_wrap_device_ex", "macko_get_report",
+    "macko_wrap_device_ex", "macko_storage_by_code_width", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
     "macko_decode", "macko_encode_fp8", "macko_encode_device_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_spmv_many", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
@@ -101,6 +101,7 @@ def load_library():
     lib.macko_encode_ex.argtypes = [vp, i64, i64, i64, ci, hp, rp]
     lib.macko_encode_device_ex.argtypes = [vp, i64, i64, i64, ci, vp, hp, rp]
     lib.macko_wrap_device_ex.argtypes = [i64, i64, i64, ci, vp, vp, vp, hp]
+    lib.macko_storage_by_code_width.argtypes = [vp, i64, i64, i64, i64p, ctypes.POINTER(ci)]
     lib.macko_get_report.argtypes = [vp, rp]
     lib.macko_device_bytes.argtypes = [vp, i64p, i64p, i64p]
     lib.macko_bind_device.argtypes = [vp, vp, vp, vp, vp]
@@ -350,6 +351,17 @@ def encode(dense, b_delta: int = 4) -> MackoMatrix:
         _check(load_library().macko_encode_ex(a.ctypes.data, a.shape[0], a.shape[1], ld, int(b_delta),
                                               ctypes.byref(h), ctypes.byref(rep)), "macko_encode_ex")
     return MackoMatrix(h.value, Report._from_c(rep))
+
+
+def storage_by_code_width(dense):
+    """macko_storage_by_code_width: ({1: bytes, 2: bytes, 4: bytes, 8: bytes}, best width) for a host fp16 matrix."""
+    a = _host_u16_matrix(dense)
+    ld = a.strides[0] // 2 if a.size else a.shape[1]
+    out = (ctypes.c_int64 * 4)()
+    best = ctypes.c_int(0)
+    _check(load_library().macko_storage_by_code_width(a.ctypes.data, a.shape[0], a.shape[1], ld, out,
+                                                      ctypes.byref(best)), "macko_storage_by_code_width")
+    return {1: out[0], 2: out[1], 4: out[2], 8: out[3]}, best.value
 
 
 def encode_fp8(dense) -> MackoMatrix:

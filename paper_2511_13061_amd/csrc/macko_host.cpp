@@ -233,6 +233,39 @@ int macko_encode_ex(const uint16_t* dense_host, int64_t rows, int64_t cols, int6
   return MACKO_OK;
 }
 
+int macko_storage_by_code_width(const uint16_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
+                                int64_t total_bytes[4], int* best_b_delta) {
+  if (!total_bytes || rows < 0 || cols < 0 || ld < cols) return MACKO_E_INVALID_ARG;
+  if (!dense_host && rows > 0 && cols > 0) return MACKO_E_INVALID_ARG;
+  if (cols >= (int64_t{1} << 31) || rows >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
+  static const int widths[4] = {1, 2, 4, 8};
+  try {
+    std::vector<int64_t> entries(rows), nnzs(rows);
+    for (int i = 0; i < 4; ++i) {
+      const int b = widths[i];
+      macko::parallel_blocks(rows, [&](int64_t lo, int64_t hi) {
+        for (int64_t r = lo; r < hi; ++r) macko::count_row(dense_host + r * ld, cols, b, &entries[r], &nnzs[r]);
+      });
+      int64_t pad_nnz = 0;
+      for (int64_t r = 0; r < rows; ++r) pad_nnz += entries[r];
+      const int64_t granule = macko::alloc_granule(b);
+      const int64_t alloc = (pad_nnz + granule - 1) / granule * granule;
+      total_bytes[i] = alloc >= (int64_t{1} << 32) ? -1 : alloc * 2 + alloc * b / 8 + 4 * (rows + 1);
+    }
+  } catch (const std::bad_alloc&) {
+    return MACKO_E_OUT_OF_MEMORY;
+  }
+  if (best_b_delta) {
+    int best = -1;
+    for (int i : {2, 0, 1, 3}) {                       // ties: 4 bits first, then the narrower width
+      if (total_bytes[i] < 0) continue;
+      if (best < 0 || total_bytes[i] < total_bytes[best]) best = i;
+    }
+    *best_b_delta = best < 0 ? 0 : widths[best];
+  }
+  return MACKO_OK;
+}
+
 int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                      macko_handle_t* out, macko_report_t* report) {
   if (out) *out = nullptr;

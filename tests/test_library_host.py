@@ -269,3 +269,34 @@ def test_8_bit_handles_refuse_what_they_do_not_support():
     assert lib.macko_encode_fp8(W.ctypes.data, 4, 64, 63, ctypes.byref(p), None) == -1
     empty = M.encode_fp8(np.zeros((0, 16), dtype=np.uint8))
     assert empty.get_report().pad_nnz == 0
+
+
+def test_storage_by_code_width_equals_the_oracles_encodings():
+    """Bytes per code width counted without encoding (Section 4.2 / Appendix C) against the oracle's
+    encodings at each width, and the choice: 1 bit for dense rows, 2 bits around 40 %, 4 bits at
+    70 %, 8 bits at 97 % sparsity (the ranges of Appendix C)."""
+    cases = {
+        "dense": (wl.bernoulli(40, 1031, 1.0, 0.02, 91, 1), 1),
+        "sparsity40": (wl.bernoulli(64, 3000, 0.6, 0.02, 91, 2), 2),
+        "sparsity70": (wl.bernoulli(64, 3000, 0.3, 0.02, 91, 3), 4),
+        "sparsity97": (wl.bernoulli(300, 9000, 0.03, 1.0, 91, 4), 8),
+        "worked_example": (None, None),
+    }
+    for name, (W, want_best) in cases.items():
+        if W is None:
+            W = np.zeros((3, 12), dtype=np.uint16)
+            W[0, [0, 4, 11]] = 0x3C00
+            W[2, 7] = 0x4000
+        table, best = M.storage_by_code_width(W)
+        for b in (1, 2, 4, 8):
+            assert table[b] == oracle.encode(W, b).total_bytes, (name, b)
+        assert table[best] == min(table.values())
+        if want_best is not None:
+            assert best == want_best, (name, table)
+    # empty matrix: only the row pointers (and a tie, which goes to 4 bits)
+    table, best = M.storage_by_code_width(np.zeros((5, 0), dtype=np.uint16))
+    assert set(table.values()) == {4 * 6} and best == 4
+    lib = M.load_library()
+    out = (ctypes.c_int64 * 4)()
+    assert lib.macko_storage_by_code_width(None, 2, 2, 2, out, None) == -1
+    assert lib.macko_storage_by_code_width(W.ctypes.data, 3, 12, 4, out, None) == -1       # ld < cols
