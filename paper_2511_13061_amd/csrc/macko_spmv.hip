@@ -118,15 +118,19 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
 // The wavefront's rows form one stream of (row, step) items.  Loads run RING items
 // ahead of the arithmetic and cross row boundaries, so the memory pipeline does
 // not drain between rows.  Every item issues exactly one deltas load and one
-// values load, unconditionally (lanes past the row end re-read the row's last
-// chunk, items past the wavefront's last row re-read the last chunk once more), which
-// lets the compiler count outstanding loads exactly.
+// values load, unconditionally (lanes before the row start re-read the row's first
+// chunk, lanes past the row end its last, items past the wavefront's last row re-read
+// the last chunk once more), which lets the compiler count outstanding loads exactly.
 //
-// Entries of neighbouring rows that share a lane's 8-entry chunk:
-//  - before the row start: the base is set so that the row's first entry lands
-//    on its own column; earlier entries then decode to positions <= 0, which
-//    read the zero guard in front of x and contribute nothing;
-//  - after the row end (last step only): their codes and values are cleared.
+// A row's first step begins at its start rounded down to 8 entries (Section 4.5) or, for
+// long rows, to a larger power of two (see kStepAlign).  What a lane holds besides the row:
+//  - lanes that lie wholly before the row start (first step, larger alignments only):
+//    codes and values cleared; they advance 16 bytes each below x[0];
+//  - entries of the previous row in the lane that holds the row start: the base is set
+//    so that the row's first entry lands on its own column; the earlier entries then
+//    decode to positions <= 0, which read the zero guard in front of x and contribute
+//    nothing;
+//  - after the row end (last step only): codes and values cleared.
 // No load ever leaves [0, alloc_nnz).
 // ---------------------------------------------------------------------------
 // x element whose plain LDS offset relative to the start of x is q (q may be
