@@ -154,6 +154,33 @@ def test_aligned_steps_with_rows_starting_at_chosen_offsets(b_delta):
         assert y[12] == 0 and y[13] == 0 and y[25] == 0
 
 
+def test_random_matrices_with_random_launch_knobs():
+    """Forty seeded draws of shape, density, code width and launch knobs (kernel, block, rows per
+    workgroup, resident round, ring depth, step alignment): the planner has to turn every
+    combination into a launch that computes each row exactly once."""
+    rng = np.random.default_rng(20251113)
+    for case in range(40):
+        rows = int(rng.integers(1, 400))
+        cols = int(rng.choice([1, 7, 64, 500, 1031, 2048, 4096, 6000, 9000]))
+        dens = float(rng.choice([0.02, 0.1, 0.3, 0.5, 0.8, 1.0]))
+        b_delta = int(rng.choice([1, 2, 4, 8]))
+        W = wl.bernoulli(rows, cols, dens, 0.05, 700 + case, 1)
+        if rows > 5:
+            W[rng.choice(rows, rows // 5, replace=False)] = 0     # empty rows
+        x = wl.x_vector(cols, 700 + case, 2)
+        block = int(rng.choice([0, 64, 128, 192, 256, 512, 704, 1024]))
+        knobs = {"spmv_kernel": int(rng.choice([0, 2, 2, 2])), "spmv_block": block,
+                 "spmv_step_align": int(rng.choice([0, 8, 16, 32, 64, 128, 256, 512])),
+                 "spmv_ring": int(rng.choice([0, 2, 3, 4])), "spmv_resident": int(rng.choice([0, 1, 2]))}
+        if rng.random() < 0.5:
+            knobs["spmv_rows_per_wg"] = int(rng.integers(1, 64 * max(block, 64) // 64 + 1))
+        else:
+            knobs["spmv_wgs_per_cu"] = int(rng.choice([0, 1, 2, 3, 4]))
+            knobs["spmv_steps_per_wave"] = int(rng.choice([0, 1, 3, 8, 40]))
+        y = spmv_case(W, x, b_delta, **knobs)
+        check_y(y, W, x, f"case {case}: {rows}x{cols} d={dens} b={b_delta} {knobs}")
+
+
 RESIDENT_VARIANTS = {
     "auto": {},
     "never": {"spmv_resident": 1},
