@@ -168,8 +168,8 @@ MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas
  * matrix), macko_spmv / macko_spmv_group (x and y stay fp16, fp32
  * accumulation; the wave-per-row kernel serves every row length; x must fit
  * LDS, about 78 K columns, otherwise MACKO_E_UNSUPPORTED), macko_columns_device,
- * macko_check_device.
- * macko_spmm, macko_decode, macko_decode_device and macko_host_buffers'
+ * macko_check_device, macko_decode_device (the dense matrix as bytes).
+ * macko_spmm, macko_decode and macko_host_buffers'
  * `values` are MACKO_E_UNSUPPORTED for such a handle. */
 MACKO_API int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                                macko_handle_t* out, macko_report_t* report);
@@ -224,11 +224,12 @@ MACKO_API int macko_check_device(macko_handle_t h, void* stream, int64_t* first_
  * must be bound.  Only enqueues on `stream`. */
 MACKO_API int macko_columns_device(macko_handle_t h, int32_t* cols_dev, void* stream);
 
-/* The dense rows x cols fp16 matrix back from the bound device arrays (the
- * format is lossless, Section 5.2; -0 inputs come back as +0).
- * dense_dev: fp16 [rows x ld] on the device, ld >= cols elements, 2-byte
- * aligned (16-byte aligned with ld and cols multiples of 8 for full-width
- * stores), caller owned, must not overlap the format arrays.  Cells [r][0, cols)
+/* The dense rows x cols matrix back from the bound device arrays (the format
+ * is lossless, Section 5.2; -0 inputs come back as +0).
+ * dense_dev: fp16 [rows x ld] on the device (uint8 [rows x ld] for a matrix
+ * with 8-bit values, at most 163840 columns), ld >= cols elements, aligned to
+ * its element size (16-byte aligned with rows of a multiple of 16 bytes for
+ * full-width stores), caller owned, must not overlap the format arrays.  Cells [r][0, cols)
  * are overwritten, cells between cols and ld are left untouched.  Enqueues one
  * kernel on `stream` (two for rows of more than 81920 columns) and does not
  * synchronise. */

@@ -300,10 +300,12 @@ class MackoMatrix:
         return cols_dev
 
     def decode_device(self, dense_dev=None, stream=None):
-        """macko_decode_device: the dense fp16 matrix back, as a torch CUDA tensor [rows, cols]."""
+        """macko_decode_device: the dense matrix back, as a torch CUDA tensor [rows, cols] (float16, or
+        uint8 bit patterns for a matrix with 8-bit values)."""
         import torch
         if dense_dev is None:
-            dense_dev = torch.empty((self.rows, self.cols), dtype=torch.float16, device="cuda")
+            dt = torch.uint8 if self.get_report().b_val == 8 else torch.float16
+            dense_dev = torch.empty((self.rows, self.cols), dtype=dt, device="cuda")
         if dense_dev.dim() != 2 or (dense_dev.shape[1] > 1 and dense_dev.stride(1) != 1):
             raise ValueError("dense_dev must be a row-major [rows, >= cols] tensor")
         ld = dense_dev.stride(0) if dense_dev.shape[0] > 1 else max(dense_dev.shape[1], 1)

@@ -142,4 +142,55 @@ struct LaneCodes<8> {
   }
 };
 
+// The 8 values of a lane's chunk, 16 or 8 bits each.  16-bit values are fp16 and feed
+// v_fma_mix_f32 directly; 8-bit values are OCP E4M3 numbers, converted two at a time
+// with the hardware conversion (v_cvt_pk_f32_fp8).
+template <int VB>
+struct LaneValues;
+template <>
+struct LaneValues<16> {
+  uint4 v;
+  __device__ __forceinline__ void load(const void* __restrict__ values, uint32_t chunk) {
+    v = load_stream(static_cast<const uint4*>(values) + chunk);
+  }
+  __device__ __forceinline__ void keep_first(uint32_t nv) {       // clear the values of entries nv, nv+1, ...
+    v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
+    v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
+    v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
+    v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
+  }
+  template <int K>
+  __device__ __forceinline__ uint32_t bits() const {              // the stored bit pattern of entry K
+    const uint32_t w = (K >> 1) == 0 ? v.x : ((K >> 1) == 1 ? v.y : ((K >> 1) == 2 ? v.z : v.w));
+    return (K & 1) ? (w >> 16) : (w & 0xFFFFu);
+  }
+  template <int K>
+  __device__ __forceinline__ float get() const {
+    return f16_bits_to_f32((uint16_t)bits<K>());
+  }
+};
+template <>
+struct LaneValues<8> {
+  uint2 v;
+  __device__ __forceinline__ void load(const void* __restrict__ values, uint32_t chunk) {
+    v = load_stream(static_cast<const uint2*>(values) + chunk);
+  }
+  __device__ __forceinline__ void keep_first(uint32_t nv) {
+    const uint32_t lo = nv >= 4 ? 4u : nv, hi = nv >= 8 ? 4u : (nv > 4 ? nv - 4u : 0u);
+    v.x &= lo == 4 ? 0xFFFFFFFFu : ((1u << (8u * lo)) - 1u);
+    v.y &= hi == 4 ? 0xFFFFFFFFu : ((1u << (8u * hi)) - 1u);
+  }
+  template <int K>
+  __device__ __forceinline__ uint32_t bits() const {
+    return ((K < 4 ? v.x : v.y) >> (8 * (K & 3))) & 0xFFu;
+  }
+  template <int K>
+  __device__ __forceinline__ float get() const {
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const float2v p = __builtin_amdgcn_cvt_pk_f32_fp8((int)(K < 4 ? v.x : v.y), (K & 2) != 0);
+    return (K & 1) ? p.y : p.x;
+  }
+};
+
+
 }  // namespace macko

@@ -143,21 +143,22 @@ __global__ void __launch_bounds__(256) zero_rows_kernel(uint16_t* __restrict__ d
 // The dense matrix back, one pass: a wavefront builds its row in LDS (zeros, then the stored
 // values at their columns) and writes it out with full-width stores, so every byte of the dense
 // matrix is written exactly once and nothing of it is read.  Every wavefront of the workgroup has
-// a row buffer of cols rounded up to 8 halves.  VEC: 16-byte stores (dense and ld aligned
-// to 16 bytes, cols a multiple of 8).
-template <int BD, bool VEC>
+// a row buffer of cols values rounded up to 16 bytes.  VB: bits per value (16: fp16, 8: E4M3
+// bytes).  VEC: 16-byte stores (dense and ld aligned to 16 bytes, a row a multiple of 16 bytes).
+template <int BD, int VB, bool VEC>
 __global__ void __launch_bounds__(512)
-decode_rows_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
+decode_rows_kernel(const void* __restrict__ values, const uint32_t* __restrict__ deltas,
                    const uint32_t* __restrict__ row_ptr, const int rows, const int cols,
-                   uint16_t* __restrict__ dense, const int64_t ld) {
+                   void* __restrict__ dense, const int64_t ld) {
   extern __shared__ __align__(16) unsigned char lds[];
+  constexpr int EB = VB / 8;                                  // bytes per value
   const int lane = threadIdx.x & 63;
   const int wave_in_wg = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int waves_per_wg = (int)blockDim.x >> 6;
   const int wave = (int)blockIdx.x * waves_per_wg + wave_in_wg;
   const int nwaves = (int)gridDim.x * waves_per_wg;
-  const int chunks = (cols + 7) >> 3;                         // 16-byte chunks of the row buffer
-  uint16_t* rowbuf = reinterpret_cast<uint16_t*>(lds) + (size_t)wave_in_wg * chunks * 8;
+  const int chunks = (cols * EB + 15) >> 4;                   // 16-byte chunks of the row buffer
+  unsigned char* rowbuf = lds + (size_t)wave_in_wg * chunks * 16;
   uint4* rowbuf4 = reinterpret_cast<uint4*>(rowbuf);
   for (int row = wave; row < rows; row += nwaves) {          // wavefront-uniform
     const uint32_t start = (uint32_t)__builtin_amdgcn_readfirstlane((int)row_ptr[row]);
@@ -168,20 +169,20 @@ decode_rows_kernel(const uint4* __restrict__ values, const uint32_t* __restrict_
       const int nsteps = (int)((end - a0 + 511u) >> 9);
       int base2 = 0;
       LaneCodes<BD> wn;                                      // the next step's loads, one step ahead
-      uint4 vn;
+      LaneValues<VB> vn;
       {
         const uint32_t chunk = min(a0 + 8u * (uint32_t)lane, end - 1u) >> 3;
         wn.load(deltas, chunk);
-        vn = load_stream(values + chunk);
+        vn.load(values, chunk);
       }
       for (int step = 0; step < nsteps; ++step) {
         const uint32_t e0 = a0 + 512u * (uint32_t)step + 8u * (uint32_t)lane;
         LaneCodes<BD> w = wn;
-        const uint4 v = vn;
+        const LaneValues<VB> v = vn;
         {                                                    // lanes past the row end re-read its last chunk
           const uint32_t chunk = min(e0 + 512u, end - 1u) >> 3;
           wn.load(deltas, chunk);
-          vn = load_stream(values + chunk);
+          vn.load(values, chunk);
         }
         w.keep_if(e0 < end);
         w.decode();
@@ -192,12 +193,14 @@ decode_rows_kernel(const uint4* __restrict__ values, const uint32_t* __restrict_
           if (before > 0) base2 = -(int)w.through(before - 1);
         }
         const int lanebase = base2 + (int)(incl - tot);
-        const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
 #define MACKO_ENTRY(k)                                                                  \
   {                                                                                     \
     const uint32_t e = e0 + k;                                                          \
     const int col = (lanebase + w.template offset<k>()) >> 1;                           \
-    if (e >= start && e < end && col < cols) rowbuf[col] = (uint16_t)(vv[k >> 1] >> (16 * (k & 1))); \
+    if (e >= start && e < end && col < cols) {                                          \
+      if (VB == 16) reinterpret_cast<uint16_t*>(rowbuf)[col] = (uint16_t)v.template bits<k>(); \
+      else rowbuf[col] = (unsigned char)v.template bits<k>();                           \
+    }                                                                                   \
   }
         MACKO_ENTRY(0) MACKO_ENTRY(1) MACKO_ENTRY(2) MACKO_ENTRY(3)
         MACKO_ENTRY(4) MACKO_ENTRY(5) MACKO_ENTRY(6) MACKO_ENTRY(7)
@@ -209,7 +212,7 @@ decode_rows_kernel(const uint4* __restrict__ values, const uint32_t* __restrict_
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    uint16_t* out = dense + (int64_t)row * ld;
+    unsigned char* out = static_cast<unsigned char*>(dense) + (int64_t)row * ld * EB;
     if (VEC) {
       typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
       for (int c = lane; c < chunks; c += 64) {
@@ -217,6 +220,9 @@ decode_rows_kernel(const uint4* __restrict__ values, const uint32_t* __restrict_
         u32x4 q = {t.x, t.y, t.z, t.w};
         __builtin_nontemporal_store(q, reinterpret_cast<u32x4*>(out) + c);
       }
+    } else if (VB == 16) {
+      for (int c = lane; c < cols; c += 64)
+        reinterpret_cast<uint16_t*>(out)[c] = reinterpret_cast<const uint16_t*>(rowbuf)[c];
     } else {
       for (int c = lane; c < cols; c += 64) out[c] = rowbuf[c];
     }
@@ -226,22 +232,21 @@ decode_rows_kernel(const uint4* __restrict__ values, const uint32_t* __restrict_
   }
 }
 
-template <int BD>
-int launch_decode_rows_bd(const SpmvProblem& p, uint16_t* dense, int64_t ld, bool vec, int waves_per_wg,
+template <int BD, int VB>
+int launch_decode_rows_bd(const SpmvProblem& p, void* dense, int64_t ld, bool vec, int waves_per_wg,
                           int64_t lds_bytes, hipStream_t stream) {
   const int block = 64 * waves_per_wg;
   const int64_t waves_wanted = std::min<int64_t>(p.rows, (int64_t)device_cu_count() * 32);
   const dim3 grid((unsigned)((waves_wanted + waves_per_wg - 1) / waves_per_wg));
-  const uint4* values = reinterpret_cast<const uint4*>(p.values);
   const uint32_t* deltas = reinterpret_cast<const uint32_t*>(p.deltas);
-  auto kfn = vec ? decode_rows_kernel<BD, true> : decode_rows_kernel<BD, false>;
+  auto kfn = vec ? decode_rows_kernel<BD, VB, true> : decode_rows_kernel<BD, VB, false>;
   if (lds_bytes > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds_bytes);
     if (e != hipSuccess) return hip_fail(e);
   }
-  hipLaunchKernelGGL(kfn, grid, dim3(block), (size_t)lds_bytes, stream, values, deltas, p.row_ptr, (int)p.rows,
-                     (int)p.cols, dense, ld);
+  hipLaunchKernelGGL(kfn, grid, dim3(block), (size_t)lds_bytes, stream, static_cast<const void*>(p.values), deltas,
+                     p.row_ptr, (int)p.rows, (int)p.cols, dense, ld);
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
 }
@@ -311,25 +316,32 @@ int launch_columns(const SpmvProblem& p, int32_t* cols_out, hipStream_t stream) 
   return launch_expand<false>(p, cols_out, nullptr, 0, stream);
 }
 
-int launch_decode(const SpmvProblem& p, uint16_t* dense, int64_t ld, hipStream_t stream) {
+int launch_decode(const SpmvProblem& p, void* dense_any, int64_t ld, hipStream_t stream) {
   if (p.rows == 0 || p.cols == 0) return MACKO_OK;
-  const bool vec = p.cols % 8 == 0 && ld % 8 == 0 && (reinterpret_cast<uintptr_t>(dense) & 15) == 0;
+  const int eb = p.b_val / 8;                                // bytes per value
+  const bool vec = (p.cols * eb) % 16 == 0 && (ld * eb) % 16 == 0 && (reinterpret_cast<uintptr_t>(dense_any) & 15) == 0;
   // one pass through a row buffer in LDS per wavefront
-  const int64_t row_bytes = 16 * ((p.cols + 7) / 8);
+  const int64_t row_bytes = 16 * ((p.cols * eb + 15) / 16);
   constexpr int64_t kLdsLimit = 160 * 1024;
   if (row_bytes <= kLdsLimit) {
     // row buffers per compute unit: workgroups of 4 wavefronts while 8 or more fit, else one workgroup of 1..7
     const int per_cu = (int)(kLdsLimit / row_bytes);
     const int waves_per_wg = per_cu >= 8 ? 4 : per_cu;
     const int64_t lds_bytes = row_bytes * waves_per_wg;
+    if (p.b_val == 8) {                                      // 8-bit values come with 4-bit codes
+      if (p.b_delta != 4) return MACKO_E_UNSUPPORTED;
+      return launch_decode_rows_bd<4, 8>(p, dense_any, ld, vec, waves_per_wg, lds_bytes, stream);
+    }
     switch (p.b_delta) {
-      case 1: return launch_decode_rows_bd<1>(p, dense, ld, vec, waves_per_wg, lds_bytes, stream);
-      case 2: return launch_decode_rows_bd<2>(p, dense, ld, vec, waves_per_wg, lds_bytes, stream);
-      case 4: return launch_decode_rows_bd<4>(p, dense, ld, vec, waves_per_wg, lds_bytes, stream);
-      case 8: return launch_decode_rows_bd<8>(p, dense, ld, vec, waves_per_wg, lds_bytes, stream);
+      case 1: return launch_decode_rows_bd<1, 16>(p, dense_any, ld, vec, waves_per_wg, lds_bytes, stream);
+      case 2: return launch_decode_rows_bd<2, 16>(p, dense_any, ld, vec, waves_per_wg, lds_bytes, stream);
+      case 4: return launch_decode_rows_bd<4, 16>(p, dense_any, ld, vec, waves_per_wg, lds_bytes, stream);
+      case 8: return launch_decode_rows_bd<8, 16>(p, dense_any, ld, vec, waves_per_wg, lds_bytes, stream);
       default: return MACKO_E_UNSUPPORTED;
     }
   }
+  if (p.b_val != 16) return MACKO_E_UNSUPPORTED;             // 8-bit rows of more than 163840 columns
+  uint16_t* dense = static_cast<uint16_t*>(dense_any);
   // rows too long for LDS: clear the matrix, then scatter the stored values (two kernels in stream order)
   const int64_t stores = p.rows * (vec ? p.cols / 8 : p.cols);
   const int64_t wgs = std::min<int64_t>((stores + 255) / 256, (int64_t)device_cu_count() * 32);

@@ -550,12 +550,12 @@ int macko_columns_device(macko_handle_t h, int32_t* cols_dev, void* stream) {
 int macko_decode_device(macko_handle_t h, void* dense_dev, int64_t ld, void* stream) {
   if (!h) return MACKO_E_INVALID_ARG;
   if (!h->bound) return MACKO_E_NOT_BOUND;
-  if (h->b_val != 16) return MACKO_E_UNSUPPORTED;
   if (h->rows == 0 || h->cols == 0) return MACKO_OK;
-  if (!dense_dev || ld < h->cols || (reinterpret_cast<uintptr_t>(dense_dev) & 1)) return MACKO_E_INVALID_ARG;
+  if (!dense_dev || ld < h->cols) return MACKO_E_INVALID_ARG;
+  if (h->b_val == 16 && (reinterpret_cast<uintptr_t>(dense_dev) & 1)) return MACKO_E_INVALID_ARG;
   const macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
-                             nullptr, nullptr, h->b_delta};
-  return macko::launch_decode(p, static_cast<uint16_t*>(dense_dev), ld, static_cast<hipStream_t>(stream));
+                             nullptr, nullptr, h->b_delta, h->b_val};
+  return macko::launch_decode(p, dense_dev, ld, static_cast<hipStream_t>(stream));
 }
 
 int macko_spmv(macko_handle_t h, const void* x_dev, void* y_dev, void* stream) {

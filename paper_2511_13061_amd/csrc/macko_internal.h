@@ -72,7 +72,7 @@ int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64
 int launch_columns(const SpmvProblem& p, int32_t* cols_out, hipStream_t stream);
 // structural check of bound device arrays; *first_bad (device) must hold `rows` beforehand
 int launch_check(const SpmvProblem& p, unsigned int* first_bad, hipStream_t stream);
-int launch_decode(const SpmvProblem& p, uint16_t* dense, int64_t ld, hipStream_t stream);
+int launch_decode(const SpmvProblem& p, void* dense, int64_t ld, hipStream_t stream);
 // GPU encoder: counting pass + fill pass.  The three arrays are parts of one hipMalloc'd *block.
 int encode_on_device(const void* dense, int64_t rows, int64_t cols, int64_t ld, int b_delta, int b_val,
                      hipStream_t stream, void** block,

@@ -913,8 +913,19 @@ def test_fp8_groups_unsupported_calls_and_full_size():
     X = torch.zeros((2, 2048), dtype=torch.float16, device="cuda")
     Y = torch.zeros((2, 700), dtype=torch.float16, device="cuda")
     assert lib.macko_spmm(ma._h, 2, X.data_ptr(), 2048, Y.data_ptr(), 700, 0) == -3
-    D = torch.zeros((700, 2048), dtype=torch.float16, device="cuda")
-    assert lib.macko_decode_device(ma._h, D.data_ptr(), 2048, 0) == -3
+    # the dense matrix back on the device, as bytes: aligned, and into a wider unaligned buffer
+    for m, c in ((ma, a), (mb, b)):
+        want = oracle.decode8(oracle.encode8(c.W, 4))
+        back = m.decode_device()
+        torch.cuda.synchronize()
+        assert back.dtype == torch.uint8 and np.array_equal(back.cpu().numpy(), want)
+        rows, cols = c.W.shape
+        buf = torch.full((rows, cols + 5), 0x77, dtype=torch.uint8, device="cuda")
+        assert lib.macko_decode_device(m._h, buf[:, 3:].data_ptr(), buf.stride(0), 0) == 0
+        torch.cuda.synchronize()
+        host = buf.cpu().numpy()
+        assert np.array_equal(host[:, 3: 3 + cols], want)
+        assert (host[:, :3] == 0x77).all() and (host[:, 3 + cols:] == 0x77).all()
     # the layer shapes at full size
     for (r, c) in ((4096, 4096), (11008, 4096), (4096, 11008)):
         case = wl.fp8_case(r, c, 50)
