@@ -168,9 +168,11 @@ MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas
  * matrix), macko_spmv / macko_spmv_group (x and y stay fp16, fp32
  * accumulation; the wave-per-row kernel serves every row length; x must fit
  * LDS, about 78 K columns, otherwise MACKO_E_UNSUPPORTED), macko_columns_device,
- * macko_check_device, macko_decode_device (the dense matrix as bytes).
- * macko_spmm, macko_decode and macko_host_buffers'
- * `values` are MACKO_E_UNSUPPORTED for such a handle. */
+ * macko_check_device, macko_decode_device (the dense matrix as bytes),
+ * macko_spmm (the vectors of the batch run as independent matrix-vector
+ * products, up to 8 per launch: the matrix is read once per vector).
+ * macko_decode and macko_host_buffers' `values` are MACKO_E_UNSUPPORTED for
+ * such a handle (macko_decode_fp8, macko_host_values_fp8 instead). */
 MACKO_API int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
                                macko_handle_t* out, macko_report_t* report);
 /* macko_encode_device for a dense matrix of 8-bit values in device memory (uint8 [rows x ld]);

@@ -654,13 +654,12 @@ int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void
                void* stream) {
   if (!h || batch < 0 || batch > MACKO_MAX_BATCH) return MACKO_E_INVALID_ARG;
   if (!h->bound) return MACKO_E_NOT_BOUND;
-  if (h->b_val != 16) return MACKO_E_UNSUPPORTED;       // 8-bit values: the matrix-vector product only
   if (h->rows == 0 || batch == 0) return MACKO_OK;
   if (ldx < h->cols || ldy < h->rows) return MACKO_E_INVALID_ARG;
   int st = check_vec_ptrs(X_dev, Y_dev, h->cols);
   if (st != MACKO_OK) return st;
   macko::SpmvProblem p{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz, nullptr, nullptr,
-                       h->b_delta};
+                       h->b_delta, h->b_val};
   return macko::launch_spmm(p, X_dev, ldx, Y_dev, ldy, batch, static_cast<hipStream_t>(stream));
 }
 

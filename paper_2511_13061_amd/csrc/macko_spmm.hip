@@ -321,8 +321,9 @@ int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64
   }
   const int64_t one = lds_bytes_for(p.cols, p.b_delta);
   const int64_t limit = 160 * 1024 - 64;
-  // 1-bit codes have no batch kernel: they go through the matrix-vector path one vector at a time
-  const bool long_rows = p.pad_nnz / p.rows >= 384 && p.b_delta != 1;
+  // 1-bit codes and 8-bit values have no batch kernel: their vectors go through the matrix-vector
+  // path, up to 8 of them per launch as independent products
+  const bool long_rows = p.pad_nnz / p.rows >= 384 && p.b_delta != 1 && p.b_val == 16;
   int done = 0;
   while (done < batch) {
     const int left = batch - done;
@@ -340,11 +341,14 @@ int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64
       take = 2;
       st = launch_bt<2>(p, Xb, ldx, Yb, ldy, take, stream);
     } else {
-      take = 1;
-      SpmvProblem q = p;
-      q.x = Xb;
-      q.y = Yb;
-      st = launch_spmv_group(1, &q, stream);
+      take = long_rows ? 1 : std::min(left, kMaxGroup);
+      SpmvProblem q[kMaxGroup];
+      for (int i = 0; i < take; ++i) {
+        q[i] = p;
+        q[i].x = Xb + (int64_t)i * ldx;
+        q[i].y = Yb + (int64_t)i * ldy;
+      }
+      st = launch_spmv_group(take, q, stream);
     }
     if (st != MACKO_OK) return st;
     done += take;
