@@ -623,20 +623,27 @@ def test_config2_llama2_7b_shapes_full_size():
     grouped_like_the_bench(handles, xs, singles)
 
 
-@pytest.mark.parametrize("sparsity", [0, 50, 90])
+@pytest.mark.parametrize("sparsity", wl.SWEEP_SPARSITIES)
 def test_config3_sweep_matrix_full_size(sparsity):
+    """Every level of the sparsity sweep at its full size: both encoders byte for byte against the
+    oracle's encoding, y against the dense product by definition."""
     case = wl.config3(sparsity)
-    m = M.encode(case.W).to_device()
+    enc = oracle.encode(case.W)
+    m = M.encode(case.W)
+    assert_same_encoding(m.host_buffers(), enc)
+    m.to_device()
     y = m.spmv(to_dev(case.x))
     torch.cuda.synchronize()
     check_y(y, case.W, case.x, case.name)
     rep = m.report
     assert rep.effd_best <= rep.effd + 1e-9
-    if sparsity == 50:
-        enc = oracle.encode(case.W)
-        assert_same_encoding(m.fetch_device(), enc)
-        g = M.encode_device(to_dev(case.W))
-        assert_same_encoding(g.fetch_device(), enc)
+    assert rep.pad_nnz == enc.pad_nnz and rep.padding_entries == enc.pad_nnz - enc.nnz
+    assert_same_encoding(m.fetch_device(), enc)
+    g = M.encode_device(to_dev(case.W))
+    assert_same_encoding(g.fetch_device(), enc)
+    yg = g.spmv(to_dev(case.x))
+    torch.cuda.synchronize()
+    assert torch.equal(yg, y)
 
 
 def test_config4_adversarial_full_size():
@@ -661,6 +668,75 @@ def test_config5_llama2_13b_layer_shapes_full_size():
         check_y(y, case.W, case.x, case.name)
         handles.append(m); xs.append(to_dev(case.x)); singles.append(y)
     grouped_like_the_bench(handles, xs, singles)
+
+
+def test_config5_whole_stack_as_the_bench_issues_it():
+    """The 224 products of the 32-layer 13B-shaped stack, built the way bench.py builds them (one layer's
+    three matrices, the device buffers replicated to 224 distinct addresses: the first copy from the host
+    encoder, the others from the GPU encoder), once through macko_spmv_many and once as the 128 grouped
+    launches {q,k,v}, {o}, {gate,up}, {down} per layer.  Every one of the 448 results is compared with the
+    oracle's dense product of its matrix."""
+    plan = [("qkvo", 4), ("gate_up", 2), ("down", 1)]
+    handles, xs, want = {}, {}, {}
+    for case, (tag, mult) in zip(wl.config5_layer(), plan):
+        enc = oracle.encode(case.W)
+        first = M.encode(case.W).to_device()
+        Wd = to_dev(case.W)
+        hs = [first] + [M.encode_device(Wd) for _ in range(32 * mult - 1)]
+        del Wd
+        assert_same_encoding(hs[-1].fetch_device(), enc)
+        handles[tag], xs[tag] = hs, to_dev(case.x)
+        y64, s64 = oracle.dense_matvec(case.W, case.x)
+        want[tag] = (y64, REL_TOL * s64 + ABS_TOL)
+
+    def check(tag, y, what):
+        y64, bound = want[tag]
+        got = y.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all(), what
+        assert (np.abs(got - y64) <= bound).all(), what
+
+    seq = [(tag, layer * mult + k) for layer in range(32) for tag, mult in plan for k in range(mult)]
+    assert len(seq) == 224
+    # one library call
+    ys = [torch.full((handles[t][0].rows,), float("nan"), dtype=torch.float16, device="cuda") for t, _ in seq]
+    many = M.SpmvMany([handles[t][c] for t, c in seq], [xs[t] for t, _ in seq], ys)
+    many.launch()
+    torch.cuda.synchronize()
+    for i, (t, c) in enumerate(seq):
+        check(t, ys[i], f"spmv_many product {i} ({t} copy {c})")
+    first_of = {t: next(ys[i] for i, (tt, _) in enumerate(seq) if tt == t) for t, _ in plan}
+    for i, (t, _) in enumerate(seq):                      # same bytes, same kernel arithmetic: same bits
+        assert torch.equal(ys[i], first_of[t])
+    # 128 grouped launches on one stream
+    n_launches = 0
+    for layer in range(32):
+        for tag, ks in (("qkvo", [0, 1, 2]), ("qkvo", [3]), ("gate_up", [0, 1]), ("down", [0])):
+            mult = dict(plan)[tag]
+            hs = [handles[tag][layer * mult + k] for k in ks]
+            out = [torch.full((hs[0].rows,), float("nan"), dtype=torch.float16, device="cuda") for _ in ks]
+            M.SpmvGroup(hs, [xs[tag]] * len(ks), out).launch()
+            n_launches += 1
+            torch.cuda.synchronize()
+            for k, yk in zip(ks, out):
+                check(tag, yk, f"grouped launch layer {layer} {tag}[{k}]")
+    assert n_launches == 128
+
+
+# Appendix D: the 31 matrix shapes of the paper's runtime sweep, each at its full size.
+_APPD_SMALLEST = sorted(wl.APPENDIX_D_SHAPES, key=lambda rc: rc[0] * rc[1])[:5]
+_APPD_CASES = [(r, c, 50) for r, c in wl.APPENDIX_D_SHAPES] + [(r, c, 90) for r, c in _APPD_SMALLEST]
+
+
+@pytest.mark.parametrize("rows,cols,sparsity", _APPD_CASES, ids=[f"{r}x{c}_s{s}" for r, c, s in _APPD_CASES])
+def test_appendix_d_shapes_full_size(rows, cols, sparsity):
+    case = wl.appendix_d_case(rows, cols, sparsity)
+    m = M.encode(case.W).to_device()
+    y = m.spmv(to_dev(case.x))
+    torch.cuda.synchronize()
+    check_y(y, case.W, case.x, case.name)
+    yd = M.dense_gemv(to_dev(case.W), to_dev(case.x))
+    torch.cuda.synchronize()
+    check_y(yd, case.W, case.x, case.name + " dense")
 
 
 # ------------------------------------------------------------------ expanding the format on the device
