@@ -56,7 +56,8 @@ typedef enum macko_status {
   MACKO_E_OUT_OF_MEMORY = -4, /* host or device allocation failed                           */
   MACKO_E_NOT_BOUND = -5,     /* device operation on a handle that has no device buffers    */
   MACKO_E_HIP = -6,           /* a HIP call failed; see macko_last_hip_error()              */
-  MACKO_E_CORRUPT = -7        /* macko_check_device: the bound arrays are not a valid encoding */
+  MACKO_E_CORRUPT = -7,       /* macko_check_device: the bound arrays are not a valid encoding */
+  MACKO_E_WAIT_EXPIRED = -8   /* macko_chain_status: a chain's workgroups gave up waiting for each other */
 } macko_status;
 
 /* Opaque encoded matrix.  Created by the encode / wrap calls, released by
@@ -287,6 +288,48 @@ MACKO_API int macko_spmv_group(int n, const macko_handle_t* handles, const void*
  * macko_spmv_group.  Calls are serialised by a mutex while they enqueue. */
 MACKO_API int macko_spmv_many(int64_t n, const macko_handle_t* handles, const void* const* x_dev,
                               void* const* y_dev, void* stream);
+/* A chain of dependent products in ONE kernel launch (the linear layers of a decoder
+ * layer in the order a decoding step needs them, Appendix B and Section 5.2:
+ * {q,k,v} -> {o} -> {gate,up} -> {down}).  n_phases phases; phase p holds
+ * phase_sizes[p] independent products (1 .. MACKO_MAX_GROUP); handles, x_dev and
+ * y_dev list the products phase by phase.  Every product of phase p is complete,
+ * and its y visible, before any product of phase p + 1 reads its x: the x of a
+ * later phase may be the y of an earlier one.  Within a phase the rules of
+ * macko_spmv_group apply.  Per product the arithmetic is that of macko_spmv.
+ *
+ * How: a single resident round of workgroups that walk the phases together.  The
+ * matrix arrays of the next phase are requested before a workgroup waits for the
+ * others, so only x is on the dependent path; a kernel boundary between two
+ * dependent products costs about 3 us otherwise.
+ *
+ * Limits (MACKO_E_UNSUPPORTED otherwise): at most MACKO_MAX_CHAIN_PHASES phases
+ * and MACKO_MAX_CHAIN_PRODUCTS products; fp16 values; 2- or 4-bit codes, the same
+ * for all; no empty matrix; x of every product fits LDS next to another
+ * workgroup's; at most 64 rows per wavefront of the round (about 1.6 M rows per
+ * phase on 256 compute units); the device can hold the whole round at once.
+ *
+ * workspace_dev: MACKO_CHAIN_WORKSPACE_BYTES of device memory, 256-byte aligned,
+ * caller owned, zero before the first call; every call leaves it zero again
+ * (except the error word, see macko_chain_status).  Calls that share a workspace
+ * must not overlap in time.  While a chain runs on a device, kernels on other
+ * streams that occupy compute units for long delay it: its workgroups wait for
+ * each other at most "chain_wait_us" microseconds (macko_set_tuning; default one
+ * second), then the remaining phases are skipped, the kernel ends normally, and
+ * macko_chain_status reports it.  Two chains must never run at the same time on one
+ * device: each could hold the compute units the other is waiting for.
+ * Only enqueues on `stream`; allocates nothing. */
+#define MACKO_MAX_CHAIN_PHASES 8
+#define MACKO_MAX_CHAIN_PRODUCTS 16
+#define MACKO_CHAIN_WORKSPACE_BYTES 8192
+MACKO_API int macko_spmv_chain(int n_phases, const int* phase_sizes, const macko_handle_t* handles,
+                               const void* const* x_dev, void* const* y_dev, void* workspace_dev,
+                               int64_t workspace_bytes, void* stream);
+
+/* Whether any chain that used workspace_dev since the last call of this function gave
+ * up waiting: MACKO_OK, or MACKO_E_WAIT_EXPIRED with the phase (0-based) whose inputs
+ * were not ready in *failed_phase (may be NULL); the results of that chain are
+ * incomplete.  Synchronises `stream` and clears the record. */
+MACKO_API int macko_chain_status(void* workspace_dev, void* stream, int* failed_phase);
 MACKO_API int macko_dense_gemv_group(int n, const void* const* W_dev, const int64_t* rows,
                                      const int64_t* cols, const int64_t* ld, const void* const* x_dev,
                                      void* const* y_dev, void* stream);
@@ -315,6 +358,10 @@ MACKO_API int macko_last_hip_error(void);
  *   "spmv_steps_per_wave"  larger launches: steps of work per wavefront, 0 default
  *   "spmv_step_align"   stored entries that the first step of every row is aligned to in the
  *                       wave-per-row kernel (power of two, 8..512), 0 auto (by row length)
+ *   "chain_wait_us"     longest wait of a chain's workgroups for each other, in microseconds
+ *                       (at most 40,000,000), 0 default (one second)
+ *   "chain_no_wait"     1: such a wait gives up at once when the phase before is unfinished (for
+ *                       tests of the give-up path; the chain then reports MACKO_E_WAIT_EXPIRED)
  *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8), "gemv_resident",
  *   "gemv_wgs_per_cu"   the same for the dense GEMV
  * Settings are process wide and not thread safe. */

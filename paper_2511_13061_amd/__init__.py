@@ -5,12 +5,17 @@ arithmetic step runs inside the library's HIP kernels; this package only
 marshals arguments.  PyTorch supplies device memory and streams.
 """
 from .binding import (  # noqa: F401
+    CHAIN_WORKSPACE_BYTES,
+    MACKO_E_WAIT_EXPIRED,
     GemvGroup,
     MackoError,
     MackoMatrix,
     Report,
+    SpmvChain,
     SpmvGroup,
     SpmvMany,
+    chain_status,
+    chain_workspace,
     dense_gemv,
     dense_gemv_group,
     encode,

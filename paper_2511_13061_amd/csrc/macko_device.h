@@ -188,6 +188,10 @@ struct XStage {
 // not 16-byte aligned and the descriptor is made empty) get zeros back without
 // touching memory.  The loads are therefore unconditional, which keeps the
 // compiler's count of outstanding loads exact.
+// AUX: cache policy bits of the loads (0: ordinary; kCoherentLoad: coherent over the whole device,
+// for an x that workgroups on other parts of the chip have just written, see spmv_chain_kernel).
+constexpr int kCoherentLoad = 16;     // sc1: the load does not hit lines that another L2 may have made stale
+template <int AUX = 0>
 __device__ __forceinline__ void stage_x_begin(XStage& st, const uint16_t* __restrict__ x, int cols) {
   const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15) == 0;
   const int bytes = aligned ? (cols >> 3) * 16 : 0;   // whole 16-byte chunks of x
@@ -196,15 +200,30 @@ __device__ __forceinline__ void stage_x_begin(XStage& st, const uint16_t* __rest
 #pragma unroll
   for (int k = 0; k < kXStageRegs; ++k) {
     const int i = (int)threadIdx.x + k * (int)blockDim.x;
-    const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, i * 16, 0, 0);
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, i * 16, 0, AUX);
     st.r[k] = make_uint4(v[0], v[1], v[2], v[3]);
   }
+}
+
+// one element / one aligned 16-byte chunk of x, device-coherent when AUX asks for it
+template <int AUX>
+__device__ __forceinline__ uint16_t load_x_elem(const uint16_t* x) {
+  if (AUX == 0) return *x;
+  return __hip_atomic_load(x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <int AUX>
+__device__ __forceinline__ uint4 load_x_chunk(const uint4* x) {
+  if (AUX == 0) return *x;
+  const unsigned long long* q = reinterpret_cast<const unsigned long long*>(x);
+  const unsigned long long lo = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long hi = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
 }
 
 // SIMPLE promises: x is 16-byte aligned, cols is a multiple of 8 and x fits the
 // staging registers (cols <= 8 * kXStageRegs * blockDim.x).  The general version
 // also copies what did not fit, the ragged tail, or all of an unaligned x.
-template <bool SIMPLE>
+template <bool SIMPLE, int AUX = 0>
 __device__ __forceinline__ void stage_x_finish(unsigned char* lds, const XStage& st,
                                                const uint16_t* __restrict__ x, int cols,
                                                int front_pad = kFrontPad, int back_pad = kBackPad) {
@@ -228,11 +247,12 @@ __device__ __forceinline__ void stage_x_finish(unsigned char* lds, const XStage&
     }
     if (!SIMPLE) {
       const uint4* xg = reinterpret_cast<const uint4*>(x);
-      for (int i = tid + kXStageRegs * nt; i < chunks; i += nt) xd[i] = xg[i];
-      for (int i = chunks * 8 + tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
+      for (int i = tid + kXStageRegs * nt; i < chunks; i += nt) xd[i] = load_x_chunk<AUX>(xg + i);
+      for (int i = chunks * 8 + tid; i < tail_chunks * 8; i += nt)
+        xs[i] = i < cols ? load_x_elem<AUX>(x + i) : (uint16_t)0;
     }
   } else {
-    for (int i = tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? x[i] : (uint16_t)0;
+    for (int i = tid; i < tail_chunks * 8; i += nt) xs[i] = i < cols ? load_x_elem<AUX>(x + i) : (uint16_t)0;
   }
   __syncthreads();
 }

@@ -650,6 +650,70 @@ int macko_spmv_many(int64_t n, const macko_handle_t* handles, const void* const*
   return result;
 }
 
+namespace {
+
+// argument checks and problem list shared by the two chain entry points
+int chain_problems(int n_phases, const int* phase_sizes, const macko_handle_t* handles, const void* const* x_dev,
+                   void* const* y_dev, macko::SpmvProblem* p, int* total_out) {
+  if (n_phases < 1 || !phase_sizes || !handles || !x_dev || !y_dev) return MACKO_E_INVALID_ARG;
+  if (n_phases > MACKO_MAX_CHAIN_PHASES) return MACKO_E_UNSUPPORTED;
+  int total = 0;
+  for (int ph = 0; ph < n_phases; ++ph) {
+    if (phase_sizes[ph] < 1 || phase_sizes[ph] > MACKO_MAX_GROUP) return MACKO_E_INVALID_ARG;
+    total += phase_sizes[ph];
+    if (total > MACKO_MAX_CHAIN_PRODUCTS) return MACKO_E_UNSUPPORTED;
+  }
+  for (int i = 0; i < total; ++i) {
+    macko_handle_t h = handles[i];
+    if (!h) return MACKO_E_INVALID_ARG;
+    if (!h->bound) return MACKO_E_NOT_BOUND;
+    int st = check_vec_ptrs(x_dev[i], y_dev[i], h->cols);
+    if (st != MACKO_OK) return st;
+    p[i] = macko::SpmvProblem{h->d_values, h->d_deltas, h->d_row_ptr, h->rows, h->cols, h->pad_nnz,
+                              x_dev[i], y_dev[i], h->b_delta, h->b_val};
+  }
+  *total_out = total;
+  return MACKO_OK;
+}
+
+uint32_t chain_wait_ticks() {
+  const macko::Tuning& t = macko::tuning();
+  if (t.chain_no_wait) return 0u;
+  const int64_t us = t.chain_wait_us ? t.chain_wait_us : 1000000;      // default: one second
+  return (uint32_t)(us * 100);                                          // the wall clock ticks at 100 MHz
+}
+
+int chain_status_of(uint32_t* scratch, hipStream_t s, int* failed_phase) {
+  if (failed_phase) *failed_phase = -1;
+  uint32_t* word = scratch + macko::chain_error_word();
+  uint32_t err = 0;
+  MACKO_HIP_TRY(hipStreamSynchronize(s));
+  MACKO_HIP_TRY(hipMemcpy(&err, word, sizeof(err), hipMemcpyDeviceToHost));
+  if (err == 0) return MACKO_OK;
+  MACKO_HIP_TRY(hipMemset(word, 0, sizeof(err)));
+  if (failed_phase) *failed_phase = (int)err - 1;
+  return MACKO_E_WAIT_EXPIRED;
+}
+
+}  // namespace
+
+int macko_spmv_chain(int n_phases, const int* phase_sizes, const macko_handle_t* handles, const void* const* x_dev,
+                     void* const* y_dev, void* workspace_dev, int64_t workspace_bytes, void* stream) {
+  macko::SpmvProblem p[MACKO_MAX_CHAIN_PRODUCTS];
+  int total = 0;
+  int st = chain_problems(n_phases, phase_sizes, handles, x_dev, y_dev, p, &total);
+  if (st != MACKO_OK) return st;
+  if (!workspace_dev || (reinterpret_cast<uintptr_t>(workspace_dev) & 255) || workspace_bytes < MACKO_CHAIN_WORKSPACE_BYTES)
+    return MACKO_E_INVALID_ARG;
+  return macko::launch_spmv_chain(n_phases, phase_sizes, p, static_cast<uint32_t*>(workspace_dev), chain_wait_ticks(),
+                                  static_cast<hipStream_t>(stream));
+}
+
+int macko_chain_status(void* workspace_dev, void* stream, int* failed_phase) {
+  if (!workspace_dev) return MACKO_E_INVALID_ARG;
+  return chain_status_of(static_cast<uint32_t*>(workspace_dev), static_cast<hipStream_t>(stream), failed_phase);
+}
+
 int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void* Y_dev, int64_t ldy,
                void* stream) {
   if (!h || batch < 0 || batch > MACKO_MAX_BATCH) return MACKO_E_INVALID_ARG;
@@ -703,6 +767,7 @@ const char* macko_status_string(int status) {
     case MACKO_E_NOT_BOUND: return "handle has no device buffers";
     case MACKO_E_HIP: return "HIP error";
     case MACKO_E_CORRUPT: return "the device arrays are not a valid encoding";
+    case MACKO_E_WAIT_EXPIRED: return "a chain's workgroups gave up waiting for each other; its results are incomplete";
     default: return "unknown status";
   }
 }
@@ -723,6 +788,8 @@ static int64_t* tuning_slot(const char* name) {
   if (n == "spmv_steps_per_wave") return &t.spmv_steps_per_wave;
   if (n == "spmv_resident_steps") return &t.spmv_resident_steps;
   if (n == "spmv_step_align") return &t.spmv_step_align;
+  if (n == "chain_wait_us") return &t.chain_wait_us;
+  if (n == "chain_no_wait") return &t.chain_no_wait;
   if (n == "gemv_resident") return &t.gemv_resident;
   if (n == "gemv_wgs_per_cu") return &t.gemv_wgs_per_cu;
   if (n == "gemv_block") return &t.gemv_block;
@@ -744,6 +811,8 @@ int macko_set_tuning(const char* name, int64_t value) {
   if (n == "spmv_resident_steps" && value > (int64_t{1} << 30)) return MACKO_E_INVALID_ARG;
   if (n == "spmv_step_align" && value != 0 && (value < 8 || value > 512 || (value & (value - 1)) != 0))
     return MACKO_E_INVALID_ARG;
+  if (n == "chain_wait_us" && value > 40000000) return MACKO_E_INVALID_ARG;   // the tick count is 32 bits wide
+  if (n == "chain_no_wait" && value > 1) return MACKO_E_INVALID_ARG;
   if (n == "spmv_lanes" && value != 0 && value != 16 && value != 32 && value != 64) return MACKO_E_INVALID_ARG;
   if ((n == "spmv_block" || n == "gemv_block") && value != 0 && (value % 64 != 0 || value > 1024))
     return MACKO_E_INVALID_ARG;

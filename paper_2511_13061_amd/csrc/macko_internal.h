@@ -25,6 +25,8 @@ struct Tuning {
   int64_t spmv_steps_per_wave = 0; // many-workgroup regime: steps of work per wavefront (0 = default)
   int64_t spmv_step_align = 0;     // entries a row's first step is aligned to (8 ... 512, power of two; 0 = by row length)
   int64_t spmv_resident_steps = 0; // largest work (steps per compute unit) launched as one resident round (0 = default)
+  int64_t chain_wait_us = 0;       // longest wait of a chain's workgroups for each other (0 = default, -1 = none)
+  int64_t chain_no_wait = 0;       // 1: such a wait gives up at once when the phase before is unfinished
   int64_t gemv_block = 0;
   int64_t gemv_rows_per_wg = 0;
   int64_t gemv_ring = 0;
@@ -65,6 +67,12 @@ struct GemvProblem {
 // n independent products, as few kernel launches as the shapes allow (1 <= n <= kMaxGroup)
 int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream);
 int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream);
+// phases of products in one launch, phase p + 1 after phase p: sizes[p] products in phase p, listed in
+// phase order; `scratch` is chain_scratch_bytes() of zeroed device memory that the launch leaves zeroed
+int launch_spmv_chain(int n_phases, const int* sizes, const SpmvProblem* problems, uint32_t* scratch,
+                      uint32_t wait_ticks, hipStream_t stream);
+constexpr int64_t chain_scratch_bytes() { return 8192; }
+constexpr int chain_error_word() { return 25 * 64; }
 // batch products with one matrix: Y[b] = W X[b], vectors ldx / ldy elements apart (p.x, p.y unused)
 int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64_t ldy, int batch,
                 hipStream_t stream);

@@ -135,4 +135,110 @@ inline bool plan_resident(Plan& plan, int n, const PlanInput* in, int cus, int f
   return true;
 }
 
+// ---------------------------------------------------------------------------
+// A chain: phases of independent products executed in order by ONE launch of
+// workgroups that all have to be on the chip at the same time, because a phase
+// may only read its inputs once every workgroup has finished the phase before
+// (the workgroups wait for each other inside the kernel).  The launch is one
+// resident round of k workgroups per compute unit, k the same for every phase;
+// a phase uses the first `nwaves` wavefronts of every workgroup, the others idle
+// through it.  A plan whose workgroups cannot all be resident is refused: the
+// waiting workgroups would hold the compute units that the missing ones need.
+// ---------------------------------------------------------------------------
+constexpr int kMaxChainPhases = 8;      // MACKO_MAX_CHAIN_PHASES
+constexpr int kMaxChainMats = 16;       // MACKO_MAX_CHAIN_PRODUCTS
+
+// Workgroups of `waves` wavefronts that one compute unit certainly holds at the same time, from the
+// kernel's vector registers per lane and the LDS one workgroup needs.  Deliberately pessimistic: the
+// wavefronts of a workgroup are dealt to the four SIMDs in turn starting anywhere, so each SIMD must
+// have room for ceil(waves / 4) of them per workgroup (the runtime's occupancy query packs ideally
+// and promised two workgroups of 13 wavefronts at 72 registers, of which only one was resident).
+// A SIMD has 512 registers per lane, handed out in blocks of 8, and at most 8 wavefronts.
+inline int resident_wgs_per_cu(int vgprs, int waves, int64_t lds_bytes) {
+  if (vgprs < 1 || waves < 1 || waves > 16) return 0;
+  const int per_wave = (vgprs + 7) / 8 * 8;
+  const int waves_per_simd = std::min(8, 512 / per_wave);
+  const int by_waves = waves_per_simd / ((waves + 3) / 4);
+  const int64_t by_lds = lds_bytes > 0 ? kPlanLdsPerCu / ((lds_bytes + 1023) / 1024 * 1024) : 64;
+  return (int)std::min<int64_t>(by_waves, by_lds);
+}
+
+struct ChainPlan {
+  int wgs_per_cu = 0;       // k
+  int64_t total_wgs = 0;    // k x compute units: the whole launch
+  int block = 0;            // threads per workgroup: the widest phase
+  int nwaves[kMaxChainPhases] = {};        // wavefronts a phase works with
+  PlanMat m[kMaxChainMats] = {};           // per product, in phase order
+};
+
+// sizes[p] products in phase p; in[] holds them in phase order.  max_wgs_per_cu(block) is
+// what the device can hold of the kernel at that workgroup size (the occupancy
+// the runtime reports, LDS included).  Returns false when no admissible plan exists.
+template <class Occupancy>
+inline bool plan_chain(ChainPlan& cp, int n_phases, const int* sizes, const PlanInput* in, int cus,
+                       Occupancy max_wgs_per_cu) {
+  if (n_phases < 1 || n_phases > kMaxChainPhases || cus < 1) return false;
+  int total = 0;
+  int64_t max_lds = 0;
+  for (int p = 0; p < n_phases; ++p) {
+    if (sizes[p] < 1 || sizes[p] > kMaxGroup) return false;
+    total += sizes[p];
+  }
+  if (total > kMaxChainMats) return false;
+  for (int i = 0; i < total; ++i) {
+    if (in[i].rows < 1) return false;
+    max_lds = std::max(max_lds, in[i].lds_bytes);
+  }
+  for (int k = 2; k >= 1; --k) {
+    if (k * max_lds > kPlanLdsPerCu) continue;
+    ChainPlan c;
+    c.wgs_per_cu = k;
+    c.total_wgs = (int64_t)cus * k;
+    bool ok = true;
+    int at = 0;
+    for (int p = 0; p < n_phases && ok; ++p) {
+      Plan ph;
+      const int n = sizes[p];
+      if (!plan_resident(ph, n, in + at, cus, 0, k)) {
+        // too few rows for a full round: one wavefront-sized share per workgroup, the matrices
+        // side by side, the remaining workgroups idle through this phase
+        int64_t given = 0;
+        ph.block = 4 * 64;
+        for (int i = 0; i < n; ++i) {
+          const int64_t want = (in[at + i].rows + 3) / 4;
+          const int64_t g = std::max<int64_t>(1, std::min<int64_t>(want, c.total_wgs / n));
+          plan_split(ph.m[i], in[at + i].rows, std::min<int64_t>(g, in[at + i].rows));
+          given += ph.m[i].nwg;
+        }
+        if (given > c.total_wgs) ok = false;
+        // and few enough rows per wavefront: widen the workgroup if need be
+        for (int nw = 4; nw <= 16 && ok; ++nw) {
+          bool fits = true;
+          for (int i = 0; i < n; ++i) {
+            const int64_t rows_wg = ph.m[i].q + (ph.m[i].r ? 1 : 0);
+            if ((rows_wg + nw - 1) / nw > kPlanMaxRowsPerWave) fits = false;
+          }
+          ph.block = nw * 64;
+          if (fits) break;
+          if (nw == 16) ok = false;
+        }
+      }
+      if (!ok) break;
+      c.nwaves[p] = ph.block / 64;
+      c.block = std::max(c.block, ph.block);
+      for (int i = 0; i < n; ++i) {
+        c.m[at + i] = ph.m[i];
+        const int64_t rows_wg = ph.m[i].q + (ph.m[i].r ? 1 : 0);
+        if ((rows_wg + c.nwaves[p] - 1) / c.nwaves[p] > kPlanMaxRowsPerWave || rows_wg > 1024) ok = false;
+      }
+      at += n;
+    }
+    if (!ok) continue;
+    if (max_wgs_per_cu(c.block) < k) continue;          // not all resident at once: refused
+    cp = c;
+    return true;
+  }
+  return false;
+}
+
 }  // namespace macko

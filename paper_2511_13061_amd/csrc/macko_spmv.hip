@@ -13,6 +13,8 @@
 #include "macko_plan.h"
 
 #include <climits>
+#include <mutex>
+#include <vector>
 
 namespace macko {
 namespace {
@@ -185,26 +187,38 @@ __host__ __device__ inline int64_t spmv_lds_bytes(int64_t cols, int b_delta) {
 
 // The work of one workgroup: workgroup number `wg` of the matrix given by the
 // pointers, whose rows are dealt out q (+1 for the first r workgroups) at a time.
-template <int RING, bool SIMPLE, int BD, int VB = 16>
-__device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ values,
+// Gate: what has to happen before x may be read.  The plain kernels have none; a chain's later
+// phases wait there for the workgroups that produce x (see spmv_chain_kernel).
+struct NoGate {
+  static constexpr bool kActive = false;
+  __device__ __forceinline__ bool needed() const { return false; }
+  __device__ __forceinline__ bool wait() const { return true; }
+};
+
+// `nwaves` wavefronts of the workgroup share its rows (all of them in the plain kernels; a chain
+// may leave the last ones of a workgroup without rows in some phase: they only help to stage x).
+// Returns false when the gate gave up; nothing has been written to y then.
+template <int RING, bool SIMPLE, int BD, int VB = 16, class Gate = NoGate>
+__device__ __forceinline__ bool spmv_wave_row_body(const void* __restrict__ values,
                                                    const uint32_t* __restrict__ deltas,
                                                    const uint32_t* __restrict__ row_ptr,
                                                    const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
                                                    const int rows, const int cols, const int q, const int r,
-                                                   const int wg, const int inv_nwaves, const uint32_t amask) {
+                                                   const int wg, const int nwaves, const int inv_nwaves,
+                                                   const uint32_t amask, const Gate gate = Gate()) {
   extern __shared__ __align__(16) unsigned char lds[];
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
   const int row_begin = wg * q + min(wg, r);
   const int wg_rows = q + (wg < r ? 1 : 0);
-  const int nwaves = blockDim.x >> 6;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const unsigned char* xbase = lds + spmv_front_pad(BD);   // LDS address of x[0]
   const uint32_t lane8 = 8u * lane;
   const int per_wave = (wg_rows * inv_nwaves) >> 16;   // wg_rows / nwaves (exact for wg_rows <= 1024)
   const int extra = wg_rows - per_wave * nwaves;         // wg_rows % nwaves
+  const bool has_rows = wave < nwaves;
   const int wrow_begin = row_begin + wave * per_wave + min(wave, extra);
-  const int wrow_end = wrow_begin + per_wave + (wave < extra ? 1 : 0);
+  const int wrow_end = has_rows ? wrow_begin + per_wave + (wave < extra ? 1 : 0) : wrow_begin;
 
   uint32_t chunk = 0;      // 8-entry chunk index this lane loads next (chunk 0 exists: pad_nnz > 0)
   const int blk = wrow_begin;
@@ -244,11 +258,20 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
   // Start-up order: the row pointers and x are requested together; once they
   // are in registers the first streaming loads go out, and only then is x
   // written to LDS, so the stream is already in flight behind the barrier.
+  // Behind a gate the matrix streams do not wait (they do not depend on what the gate waits for):
+  // pointers and ring first, then the gate, then x.
+  // Behind it x is read with device-coherent loads, and y is written through to memory (see Gate).
+  constexpr int kXAux = Gate::kActive ? kCoherentLoad : 0;
   XStage xst;
   fetch_row_ptrs();
-  stage_x_begin(xst, x, cols);
+  const bool gated = Gate::kActive && gate.needed();
+  if (!gated) stage_x_begin<0>(xst, x, cols);
   prime_ring();
-  stage_x_finish<SIMPLE>(lds, xst, x, cols, spmv_front_pad(BD), back_pad_for(BD));  // ends with a barrier
+  if (gated) {
+    if (!gate.wait()) return false;
+      stage_x_begin<kXAux>(xst, x, cols);
+  }
+  stage_x_finish<SIMPLE, kXAux>(lds, xst, x, cols, spmv_front_pad(BD), back_pad_for(BD));  // ends with a barrier
 
   {
     float yv = 0.0f;                                   // lane i: result of row blk + i
@@ -305,8 +328,14 @@ __device__ __forceinline__ void spmv_wave_row_body(const void* __restrict__ valu
         }
       }
     }
-    if (lane < nb) y[blk + lane] = f32_to_f16_bits(yv);
+      if (lane < nb) {
+      if (Gate::kActive)     // written through to memory: workgroups under other L2 caches read it next
+        __hip_atomic_store(y + blk + lane, f32_to_f16_bits(yv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else
+        y[blk + lane] = f32_to_f16_bits(yv);
+    }
   }
+  return true;
 }
 
 // Grouped launch (matrices of one code width): the workgroup first finds its matrix.
@@ -325,7 +354,7 @@ spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4,
   }
   spmv_wave_row_body<RING, SIMPLE, BD, VB>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
                                        g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
-                                       inv_nwaves, (uint32_t)g.m[mi].amask);
+                                       (int)(blockDim.x >> 6), inv_nwaves, (uint32_t)g.m[mi].amask);
 }
 
 // One matrix: everything the workgroup needs is a scalar argument (16 registers),
@@ -337,7 +366,7 @@ spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
                      uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
                      const int inv_nwaves, const int amask) {
   spmv_wave_row_body<RING, SIMPLE, BD>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
-                                       inv_nwaves, (uint32_t)amask);
+                                       (int)(blockDim.x >> 6), inv_nwaves, (uint32_t)amask);
 }
 
 // One matrix with 8-bit values (4-bit codes): 8 bytes of values and 4 bytes of codes per lane and step.
@@ -348,7 +377,154 @@ spmv_wave_row_fp8_kernel(const uint2* __restrict__ values, const uint32_t* __res
                          uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
                          const int inv_nwaves, const int amask) {
   spmv_wave_row_body<2, SIMPLE, 4, 8>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
-                                      inv_nwaves, (uint32_t)amask);
+                                      (int)(blockDim.x >> 6), inv_nwaves, (uint32_t)amask);
+}
+
+// ---------------------------------------------------------------------------
+// Chain: phases of independent products in ONE launch.  Phase p + 1 may read, as its x,
+// what phase p wrote as its y (the products of a decoder layer in the order of Appendix B:
+// {q,k,v} -> {o} -> {gate,up} -> {down}); a kernel boundary between dependent products costs
+// about 3 us on this hardware, as much as streaming a 4096 x 4096 matrix at 50 % sparsity.
+//
+// The launch is exactly one resident round (the host has checked that all workgroups fit the
+// chip at once).  A workgroup walks the phases in order.  In each it takes its share of the
+// phase's rows, fetches their row pointers and starts its load ring -- the matrix arrays do
+// not depend on the phase before -- and only then waits until every workgroup has reported the
+// previous phase done; then it stages x and runs the ordinary loop.
+//
+// Scratch memory (32-bit words, all zero before the launch and zero again after it):
+//   arrive[g]  g < 8, 64 words apart: workgroups with (number % 8 == g) add 1 after each phase
+//              but the last, once their y has reached memory; the gate of phase p waits for
+//              the sum to reach p x workgroups
+//   abort      set by a workgroup whose wait ran out; every waiting workgroup then gives up too
+//   exit1[g], exit2   count the workgroups that are leaving; the last one clears all of the above
+//   error      phase (1-based) whose gate gave up; kept until the host reads and clears it
+// Visibility without cache maintenance: the compute units sit under eight L2 caches that do not
+// snoop each other, and the release / acquire fences that would make ordinary stores and loads
+// visible across them write back and invalidate a whole L2 each time (measured: 33 us per phase
+// with 512 workgroups doing so).  Instead y is stored write-through (device-scope stores, waited
+// for before the workgroup reports) and x is loaded with device-coherent loads, so that no
+// stale or dirty line is ever involved; the counters are device-scope atomics.
+// The wait is bounded by `wait_ticks` ticks of the 100 MHz wall clock; a workgroup that gives up
+// skips the remaining phases and leaves normally, so the launch always ends.
+// ---------------------------------------------------------------------------
+constexpr int kChainSlot = 64;                         // words between two counters (256 bytes)
+constexpr int kChainArrive = 0;                        // 8 slots
+constexpr int kChainAbort = 8 * kChainSlot;
+constexpr int kChainExit1 = 16 * kChainSlot;           // 8 slots
+constexpr int kChainExit2 = 24 * kChainSlot;
+constexpr int kChainError = 25 * kChainSlot;
+constexpr int kChainScratchWords = 26 * kChainSlot;    // 6656 bytes
+static_assert(kChainScratchWords * 4 <= chain_scratch_bytes() && kChainError == chain_error_word(), "scratch layout");
+
+struct ChainArgs {
+  SpmvMat m[kMaxChainMats];
+  int wg_begin[kMaxChainMats];     // first workgroup of the product within its phase
+  int nwg[kMaxChainMats];          // workgroups that work on it
+  int first[kMaxChainPhases + 1];  // products first[p] .. first[p + 1] - 1 make up phase p
+  int nwaves[kMaxChainPhases];     // wavefronts of a workgroup that take rows in phase p
+  int inv_nwaves[kMaxChainPhases];
+  int n_phases;
+};
+
+struct ChainGate {
+  static constexpr bool kActive = true;
+  uint32_t* scratch;
+  uint32_t target;        // arrivals that complete the previous phase; 0: nothing to wait for
+  uint32_t wait_ticks;
+  int phase;
+  __device__ __forceinline__ bool needed() const { return target != 0u; }   // uniform over the launch
+  __device__ __forceinline__ bool wait() const {
+    __shared__ int gave_up;
+    if (target == 0u) return true;
+    if (threadIdx.x < 64) {
+      const int lane = threadIdx.x;
+      const uint64_t t0 = wall_clock64();
+      int fail = 0;
+      for (;;) {
+        uint32_t v = 0u;                               // lanes 0..7: the arrival counters, lane 8: the abort word
+        if (lane < 9) v = __hip_atomic_load(scratch + lane * kChainSlot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t sum = 0u;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) sum += (uint32_t)__builtin_amdgcn_readlane((int)v, g);
+        if (sum >= target) break;
+        const uint32_t aborted = (uint32_t)__builtin_amdgcn_readlane((int)v, 8);
+        if (aborted != 0u || (uint64_t)(wall_clock64() - t0) >= (uint64_t)wait_ticks) {
+          fail = 1;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+      }
+      if (fail && lane == 0) {
+        __hip_atomic_store(scratch + kChainAbort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_max(scratch + kChainError, (uint32_t)phase + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (lane == 0) gave_up = fail;
+    }
+    __syncthreads();
+    return gave_up == 0;
+  }
+};
+
+template <bool SIMPLE, int BD>
+// Register caps: the whole round must be resident, two workgroups of up to 16 wavefronts per compute
+// unit, i.e. 8 wavefronts on a SIMD.  That needs at most 64 vector registers and at most 80 scalar
+// registers per wavefront (a SIMD has 800; the driver's trap handler takes 16 more per wavefront, so
+// a kernel with 82 left room for 7 and only half of the round was resident).
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_num_sgpr(72), amdgpu_num_vgpr(64)))
+spmv_chain_kernel(const ChainArgs a, uint32_t* __restrict__ scratch, const uint32_t wait_ticks) {
+  const int wg = (int)blockIdx.x;
+  const uint32_t total_wgs = gridDim.x;
+  bool ok = true;
+#pragma unroll 1
+  for (int p = 0; p < a.n_phases; ++p) {
+    // this workgroup's product in phase p (none: it idles through the phase)
+    int mi = -1;
+    for (int i = a.first[p]; i < a.first[p + 1]; ++i)
+      if (wg >= a.wg_begin[i] && wg < a.wg_begin[i] + a.nwg[i]) mi = i;
+    // A workgroup reports phase p only after it has seen phase p - 1 complete, also when it has no
+    // rows in phase p: the arrival counters run on from phase to phase, and a workgroup that ran
+    // ahead by two phases would be counted twice towards a phase that others are still working on.
+    const ChainGate gate{scratch, (uint32_t)p * total_wgs, wait_ticks, p};
+    if (mi >= 0) {
+      const SpmvMat& m = a.m[mi];
+      ok = spmv_wave_row_body<2, SIMPLE, BD, 16, ChainGate>(m.values, m.deltas, m.row_ptr, m.x, m.y, m.rows, m.cols,
+                                                           m.q, m.r, wg - a.wg_begin[mi], a.nwaves[p],
+                                                           a.inv_nwaves[p], (uint32_t)m.amask, gate);
+    } else {
+      ok = gate.wait();
+    }
+    if (!ok) break;
+    // Every wavefront's y has reached memory (the stores are write-through and have been
+    // acknowledged) and nobody reads this phase's x in LDS any more; then the workgroup reports.
+    __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      if (p + 1 < a.n_phases && threadIdx.x == 0)
+      __hip_atomic_fetch_add(scratch + kChainArrive + (wg & 7) * kChainSlot, 1u, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // Leaving: the last workgroup of all clears the counters for the next launch.  A workgroup's own
+  // arrivals have been performed (acknowledged) before it is counted as gone.
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __builtin_amdgcn_s_waitcnt(0);
+    const uint32_t g = (uint32_t)wg & 7u;
+    const uint32_t in_group = (total_wgs + 7u - g) >> 3;           // workgroups with number % 8 == g
+    const uint32_t before = __hip_atomic_fetch_add(scratch + kChainExit1 + g * kChainSlot, 1u, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+    if (before + 1u == in_group) {
+      const uint32_t groups = total_wgs < 8u ? total_wgs : 8u;
+      const uint32_t gone = __hip_atomic_fetch_add(scratch + kChainExit2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (gone + 1u == groups) {
+        for (int i = 0; i < 8; ++i) {
+          __hip_atomic_store(scratch + kChainArrive + i * kChainSlot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(scratch + kChainExit1 + i * kChainSlot, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __hip_atomic_store(scratch + kChainAbort, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(scratch + kChainExit2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
 }
 
 // y = 0 for a matrix without stored entries
@@ -614,6 +790,128 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, in
 }
 
 }  // namespace
+
+namespace {
+
+// Workgroups of `kernel` that one compute unit holds at a time, as the runtime reports it
+// (registers, LDS and wavefront slots); asked once per (kernel, shape) and remembered.
+struct OccupancyKey {
+  const void* kernel;
+  int block;
+  int64_t lds;
+  int dev;
+  int result;
+};
+std::mutex g_occ_mutex;
+std::vector<OccupancyKey> g_occ;
+
+int occupancy_of(const void* kernel, int block, int64_t lds) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  std::lock_guard<std::mutex> lock(g_occ_mutex);
+  for (const OccupancyKey& k : g_occ)
+    if (k.kernel == kernel && k.block == block && k.lds == lds && k.dev == dev) return k.result;
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, block, (size_t)lds) != hipSuccess) {
+    (void)hipGetLastError();
+    n = 0;
+  }
+  // and never more than the pessimistic count from the kernel's own resource use
+  hipFuncAttributes attr{};
+  if (hipFuncGetAttributes(&attr, kernel) != hipSuccess) {
+    (void)hipGetLastError();
+    n = 0;
+  } else {
+    n = std::min(n, resident_wgs_per_cu(attr.numRegs, block / 64, lds + (int64_t)attr.sharedSizeBytes));
+  }
+  g_occ.push_back(OccupancyKey{kernel, block, lds, dev, n});
+  return n;
+}
+
+}  // namespace
+
+int launch_spmv_chain(int n_phases, const int* sizes, const SpmvProblem* problems, uint32_t* scratch,
+                      uint32_t wait_ticks, hipStream_t stream) {
+  if (n_phases < 1 || n_phases > kMaxChainPhases || !sizes || !problems || !scratch) return MACKO_E_INVALID_ARG;
+  const Tuning& t = tuning();
+  const int cus = device_cu_count();
+  int total = 0;
+  for (int p = 0; p < n_phases; ++p) {
+    if (sizes[p] < 1 || sizes[p] > kMaxGroup) return MACKO_E_INVALID_ARG;
+    total += sizes[p];
+  }
+  if (total > kMaxChainMats) return MACKO_E_UNSUPPORTED;
+  // one kernel for the whole chain: every product must be one the wave-per-row kernel serves,
+  // with the same code width and 16-bit values
+  const int bd = problems[0].b_delta;
+  if (bd != 4 && bd != 2) return MACKO_E_UNSUPPORTED;
+  PlanInput in[kMaxChainMats];
+  int64_t max_lds = 0;
+  bool simple_x = true;
+  for (int i = 0; i < total; ++i) {
+    const SpmvProblem& q = problems[i];
+    if (q.rows < 1 || q.pad_nnz < 1 || q.b_delta != bd || q.b_val != 16) return MACKO_E_UNSUPPORTED;
+    if (q.pad_nnz > (int64_t{1} << 32) - 4096) return MACKO_E_UNSUPPORTED;
+    in[i].rows = q.rows;
+    in[i].steps_per_row = std::max<int64_t>(1, (q.pad_nnz / q.rows + 511) / 512);
+    in[i].lds_bytes = spmv_lds_bytes(q.cols, bd);
+    if (in[i].lds_bytes > kMaxLdsBytes) return MACKO_E_UNSUPPORTED;
+    max_lds = std::max(max_lds, in[i].lds_bytes);
+  }
+  using KC = void (*)(ChainArgs, uint32_t*, uint32_t);
+  auto kernel_for = [&](bool simple) -> KC {
+    if (bd == 2) return simple ? (KC)spmv_chain_kernel<true, 2> : (KC)spmv_chain_kernel<false, 2>;
+    return simple ? (KC)spmv_chain_kernel<true, 4> : (KC)spmv_chain_kernel<false, 4>;
+  };
+  // the general x staging needs no more resources than the lean one: plan with it, choose afterwards
+  {
+    int st = set_lds_limit(kernel_for(false), max_lds);
+    if (st != MACKO_OK) return st;
+    st = set_lds_limit(kernel_for(true), max_lds);
+    if (st != MACKO_OK) return st;
+  }
+  ChainPlan plan;
+  const bool planned = plan_chain(plan, n_phases, sizes, in, cus, [&](int block) {
+    return std::min(occupancy_of(reinterpret_cast<const void*>(kernel_for(false)), block, max_lds),
+                    occupancy_of(reinterpret_cast<const void*>(kernel_for(true)), block, max_lds));
+  });
+  if (!planned) return MACKO_E_UNSUPPORTED;             // some workgroup would not be resident
+
+  ChainArgs args{};
+  args.n_phases = n_phases;
+  int at = 0;
+  for (int p = 0; p < n_phases; ++p) {
+    args.first[p] = at;
+    args.nwaves[p] = plan.nwaves[p];
+    args.inv_nwaves[p] = 65536 / plan.nwaves[p] + 1;
+    int wg_begin = 0;
+    for (int i = 0; i < sizes[p]; ++i, ++at) {
+      const SpmvProblem& q = problems[at];
+      SpmvMat& m = args.m[at];
+      m.values = q.values;
+      m.deltas = reinterpret_cast<const uint32_t*>(q.deltas);
+      m.row_ptr = q.row_ptr;
+      m.x = static_cast<const uint16_t*>(q.x);
+      m.y = static_cast<uint16_t*>(q.y);
+      m.rows = (int)q.rows;
+      m.cols = (int)q.cols;
+      m.q = plan.m[at].q;
+      m.r = plan.m[at].r;
+      const int64_t align_knob = t.spmv_step_align;
+      const int align = align_knob ? (int)align_knob : (q.pad_nnz / q.rows >= kAlignMinEntries ? kStepAlign : 8);
+      m.amask = std::min(std::max(align, 8), kMaxStepAlign) - 1;
+      args.wg_begin[at] = wg_begin;
+      args.nwg[at] = plan.m[at].nwg;
+      wg_begin += plan.m[at].nwg;
+      simple_x = simple_x && stage_x_is_simple(m.x, m.cols, plan.block);
+    }
+  }
+  args.first[n_phases] = at;
+  hipLaunchKernelGGL(kernel_for(simple_x), dim3((unsigned)plan.total_wgs), dim3(plan.block), (size_t)max_lds, stream,
+                     args, scratch, wait_ticks);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MACKO_OK : hip_fail(e);
+}
 
 int launch_spmv_group(int n, const SpmvProblem* problems, hipStream_t stream) {
   if (n < 1 || n > kMaxGroup) return MACKO_E_INVALID_ARG;

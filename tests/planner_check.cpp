@@ -3,7 +3,9 @@
 // that every row is taken exactly once, that no wavefront gets more than 64 rows,
 // that the reciprocal multiply the kernels use equals the division, and that a
 // resident round has exactly (workgroups per compute unit) x (compute units)
-// workgroups.  Built and run by tests/test_library_host.py; prints "ok" on success.
+// workgroups.  Chains (several phases in one launch whose workgroups wait for each other): every
+// phase deals its rows out exactly once within the one round, and a chain whose round would not
+// be resident as a whole is refused.  Built and run by tests/test_library_host.py; prints "ok" on success.
 #include "macko_plan.h"
 
 #include <cstdio>
@@ -105,6 +107,85 @@ int main() {
     for (int64_t v = 0; v <= 65535; ++v)
       if (((v * inv) >> 20) != v / nw) { EXPECT(false, "20-bit reciprocal: %lld / %d", (long long)v, nw); break; }
   }
+  // ---- chains ----------------------------------------------------------------------------
+  // residency rule: pessimistic packing of a workgroup's wavefronts over the four SIMDs
+  EXPECT(resident_wgs_per_cu(52, 13, 24576 + 16) == 2, "13 wavefronts at 52 registers: 4 + 4 per SIMD fit");
+  EXPECT(resident_wgs_per_cu(72, 13, 24576 + 16) == 1, "13 wavefronts at 72 registers: 7 per SIMD hold one workgroup's 4");
+  EXPECT(resident_wgs_per_cu(64, 16, 24576) == 2, "16 wavefronts at 64 registers");
+  EXPECT(resident_wgs_per_cu(65, 16, 24576) == 1, "16 wavefronts at 65 registers");
+  EXPECT(resident_wgs_per_cu(40, 8, 100 * 1024) == 1, "LDS for one workgroup only");
+  EXPECT(resident_wgs_per_cu(40, 8, 161 * 1024) == 0, "LDS for none");
+  EXPECT(resident_wgs_per_cu(300, 4, 1024) == 1 && resident_wgs_per_cu(600, 4, 1024) == 0, "register limits");
+  {
+    // the decoder-layer chain: {q,k,v} -> {o} -> {gate,up} -> {down}
+    const int sizes[4] = {3, 1, 2, 1};
+    PlanInput in[7];
+    const int64_t rows[7] = {4096, 4096, 4096, 4096, 11008, 11008, 4096};
+    const int64_t cols[7] = {4096, 4096, 4096, 4096, 4096, 4096, 11008};
+    for (int i = 0; i < 7; ++i) in[i] = PlanInput{rows[i], (cols[i] / 2 + 511) / 512, 2 * cols[i] + 2560};
+    ChainPlan cp;
+    int asked = 0;
+    const bool ok = plan_chain(cp, 4, sizes, in, 256, [&](int block) { ++asked; return resident_wgs_per_cu(52, block / 64, 24576); });
+    EXPECT(ok && asked >= 1 && cp.wgs_per_cu == 2 && cp.total_wgs == 512, "layer chain: ok %d k %d wgs %lld", ok, cp.wgs_per_cu, (long long)cp.total_wgs);
+    // the same chain on a device that holds one such workgroup per compute unit: one per compute unit
+    const bool ok1 = plan_chain(cp, 4, sizes, in, 256, [&](int) { return 1; });
+    EXPECT(ok1 && cp.wgs_per_cu == 1 && cp.total_wgs == 256, "k = 1 plan: ok %d k %d", ok1, cp.wgs_per_cu);
+    // and on one that holds none: refused, never launched
+    EXPECT(!plan_chain(cp, 4, sizes, in, 256, [&](int) { return 0; }), "a round that is not resident must be refused");
+    // too many phases / products, empty phases, matrices without rows
+    const int nine[9] = {1, 1, 1, 1, 1, 1, 1, 1, 1};
+    EXPECT(!plan_chain(cp, 9, nine, in, 256, [&](int) { return 2; }), "9 phases");
+    const int zero[2] = {1, 0};
+    EXPECT(!plan_chain(cp, 2, zero, in, 256, [&](int) { return 2; }), "empty phase");
+    PlanInput none = in[0];
+    none.rows = 0;
+    const int one[1] = {1};
+    EXPECT(!plan_chain(cp, 1, one, &none, 256, [&](int) { return 2; }), "matrix without rows");
+    // x too large for two workgroups' LDS: one per compute unit
+    PlanInput wide = PlanInput{8192, 40, 100 * 1024};
+    const bool okw = plan_chain(cp, 1, one, &wide, 256, [&](int) { return 4; });
+    EXPECT(okw && cp.wgs_per_cu == 1, "wide x: ok %d k %d", okw, cp.wgs_per_cu);
+  }
+  for (int t = 0; t < 1500; ++t) {
+    const int n_phases = 1 + (int)(rng() % kMaxChainPhases);
+    int sizes[kMaxChainPhases];
+    PlanInput in[kMaxChainMats];
+    int total = 0;
+    for (int p = 0; p < n_phases; ++p) {
+      sizes[p] = 1 + (int)(rng() % 3);
+      if (total + sizes[p] > kMaxChainMats) sizes[p] = 1;
+      total += sizes[p];
+    }
+    if (total > kMaxChainMats) continue;
+    for (int i = 0; i < total; ++i) {
+      const int64_t rows = (rng() % 4 == 0) ? 1 + (int64_t)(rng() % 900) : 1 + (int64_t)(rng() % 60000);
+      in[i] = PlanInput{rows, 1 + (int64_t)(rng() % 40), 2048 + (int64_t)(rng() % 60000)};
+    }
+    const int cus = (rng() % 3 == 0) ? 256 : 1 + (int)(rng() % 300);
+    const int cap = (int)(rng() % 4);                       // workgroups the device holds per compute unit
+    ChainPlan cp;
+    const bool ok = plan_chain(cp, n_phases, sizes, in, cus, [&](int) { return cap; });
+    if (!ok) continue;
+    EXPECT(cp.wgs_per_cu >= 1 && cp.wgs_per_cu <= cap && cp.wgs_per_cu <= 2, "chain k %d with room for %d", cp.wgs_per_cu, cap);
+    EXPECT(cp.total_wgs == (int64_t)cus * cp.wgs_per_cu, "chain round %lld on %d compute units", (long long)cp.total_wgs, cus);
+    EXPECT(cp.block % 64 == 0 && cp.block >= 64 && cp.block <= 1024, "chain block %d", cp.block);
+    int at = 0;
+    for (int p = 0; p < n_phases; ++p) {
+      EXPECT(cp.nwaves[p] >= 1 && cp.nwaves[p] * 64 <= cp.block, "phase %d works with %d wavefronts of %d threads", p, cp.nwaves[p], cp.block);
+      // replay the phase as a plan of its own at its own wavefront count
+      Plan ph;
+      ph.block = cp.nwaves[p] * 64;
+      ph.total_wgs = 0;
+      for (int i = 0; i < sizes[p]; ++i) {
+        ph.m[i] = cp.m[at + i];
+        ph.total_wgs += ph.m[i].nwg;
+      }
+      EXPECT(ph.total_wgs <= cp.total_wgs, "phase %d uses %lld of %lld workgroups", p, (long long)ph.total_wgs, (long long)cp.total_wgs);
+      replay(ph, sizes[p], in + at, "chain phase");
+      at += sizes[p];
+    }
+  }
+
   if (failures) { std::printf("%d failures\n", failures); return 1; }
   std::printf("ok %d resident plans\n", resident_plans);
   return 0;

@@ -1141,3 +1141,147 @@ def test_spmv_many_independent_products_eager_ordered_and_under_graph_capture():
     unbound = M.encode(Ws[0])
     bad = M.SpmvMany(mats[:9] + [unbound], xs[:9] + [xs[0]], ys[:9] + [ys[0]])
     assert bad.launch_raw(0) < 0
+
+
+# ------------------------------------------------------------------ a chain of dependent products in one launch
+
+def _chain_handles(shapes, seed, b_delta=4):
+    return [M.encode(wl.half_row_matrix(r, c, 3000 + 10 * seed + i), b_delta).to_device()
+            for i, (r, c) in enumerate(shapes)]
+
+
+CHAINS = {
+    # x of every product is the y of the one before: any stale or early read shows
+    "tiny_4_phases": [(512, 512), (512, 512), (1024, 512), (512, 1024)],
+    "ragged_3_phases": [(300, 777), (777, 300), (301, 777)],
+    "layer_shapes": [(4096, 4096), (4096, 4096), (11008, 4096), (4096, 11008)],
+    "eight_phases": [(640, 640)] * 8,
+}
+
+
+@pytest.mark.parametrize("b_delta", [4, 2])
+@pytest.mark.parametrize("name", list(CHAINS))
+def test_chain_of_dependent_products_equals_separate_launches(name, b_delta):
+    """macko_spmv_chain: phase p + 1 reads what phase p wrote.  Per row the arithmetic is that of the
+    wave-per-row kernel, so the results must equal those of separate launches in stream order bit
+    for bit, and the first and last product are also checked against the oracle."""
+    shapes = CHAINS[name]
+    seed = sorted(CHAINS).index(name) + (10 if b_delta == 2 else 0)
+    hs = _chain_handles(shapes, seed, b_delta)
+    x0h = wl.x_vector(shapes[0][1], 7, seed)
+    x0 = to_dev(x0h)
+    M.set_tuning("spmv_kernel", 2)
+    try:
+        ref, x = [], x0
+        for h in hs:
+            x = h.spmv(x)
+            ref.append(x)
+        torch.cuda.synchronize()
+    finally:
+        M.set_tuning("spmv_kernel", 0)
+    check_y(ref[0], wl.half_row_matrix(*shapes[0], 3000 + 10 * seed), x0h, name)
+    ws = M.chain_workspace()
+    ys = [torch.empty(h.rows, dtype=torch.float16, device="cuda") for h in hs]
+    chain = M.SpmvChain([[(hs[i], x0 if i == 0 else ys[i - 1], ys[i])] for i in range(len(hs))], ws)
+    for rep in range(10):
+        for y in ys:
+            y.fill_(float("nan"))
+        chain.launch()
+        torch.cuda.synchronize()
+        assert chain.status() == (0, -1)
+        for i, (y, r) in enumerate(zip(ys, ref)):
+            assert torch.equal(y, r), f"{name} repetition {rep} phase {i}: {(y != r).sum().item()} rows differ"
+    assert int(ws.to(torch.int32).abs().sum().item()) == 0          # the workspace is left zeroed
+    last = len(hs) - 1
+    check_y(ys[last], wl.half_row_matrix(*shapes[last], 3000 + 10 * seed + last),
+            ref[last - 1].cpu().numpy().view(np.uint16), name + " last phase")
+
+
+def test_chain_layer_step_as_the_bench_issues_it():
+    """{q,k,v} -> {o} -> {gate,up} -> {down} of a Llama2-7B-shaped layer, several products per phase,
+    against the four grouped launches of the same products, and against the oracle."""
+    cases = list(wl.config2())
+    h = {c.name.split("_")[1]: M.encode(c.W).to_device() for c in cases}
+    x = {c.name.split("_")[1]: to_dev(c.x) for c in cases}
+    hq, hg, hd = h["qkvo"], h["gate"], h["down"]
+    xq, xg, xd = x["qkvo"], x["gate"], x["down"]
+
+    def outs(m, n):
+        return [torch.full((m.rows,), float("nan"), dtype=torch.float16, device="cuda") for _ in range(n)]
+    yq, yo, yg, yd = outs(hq, 3), outs(hq, 1), outs(hg, 2), outs(hd, 1)
+    phases = [[(hq, xq, y) for y in yq], [(hq, xq, yo[0])], [(hg, xg, y) for y in yg], [(hd, xd, yd[0])]]
+    ws = M.chain_workspace()
+    M.SpmvChain(phases, ws).launch()
+    torch.cuda.synchronize()
+    assert M.chain_status(ws) == (0, -1)
+    for ph in phases:
+        got = [y for _, _, y in ph]
+        want = M.spmv_group([m for m, _, _ in ph], [xx for _, xx, _ in ph])
+        torch.cuda.synchronize()
+        for g, w in zip(got, want):
+            assert torch.equal(g, w)
+    for c, y in zip(cases, (yq[0], yg[1], yd[0])):
+        check_y(y, c.W, c.x, "chain " + c.name)
+    check_y(yo[0], cases[0].W, cases[0].x, "chain o")
+
+
+def test_chain_gives_up_when_told_not_to_wait_and_recovers():
+    """The bounded wait, forced from the host: with "chain_no_wait" a workgroup that finds the phase
+    before unfinished gives up at once.  The launch still ends normally, the status call reports the
+    phase, and the next chain on the same workspace runs as if nothing had happened."""
+    hs = _chain_handles([(4096, 4096), (4096, 4096), (4096, 4096)], 5)
+    x0 = to_dev(wl.x_vector(4096, 7, 5))
+    ys = [torch.empty(4096, dtype=torch.float16, device="cuda") for _ in hs]
+    ws = M.chain_workspace()
+    chain = M.SpmvChain([[(hs[i], x0 if i == 0 else ys[i - 1], ys[i])] for i in range(3)], ws)
+    chain.launch()
+    torch.cuda.synchronize()
+    assert chain.status() == (0, -1)
+    good = [y.clone() for y in ys]
+    M.set_tuning("chain_no_wait", 1)
+    try:
+        chain.launch()
+        torch.cuda.synchronize()                      # returns: every workgroup has left
+        st, phase = chain.status()
+    finally:
+        M.set_tuning("chain_no_wait", 0)
+    assert st == M.MACKO_E_WAIT_EXPIRED and phase in (1, 2)
+    assert torch.equal(ys[0], good[0])                # phase 0 waits for nothing and is complete
+    assert chain.status() == (0, -1)                  # the record was cleared by the call that read it
+    for y in ys:
+        y.fill_(float("nan"))
+    chain.launch()
+    torch.cuda.synchronize()
+    assert chain.status() == (0, -1)
+    for y, g in zip(ys, good):
+        assert torch.equal(y, g)
+    assert int(ws.to(torch.int32).abs().sum().item()) == 0
+
+
+def test_chain_argument_checks():
+    lib = M.load_library()
+    hs = _chain_handles([(512, 512)], 6)
+    x = to_dev(wl.x_vector(512, 7, 6))
+    y = torch.empty(512, dtype=torch.float16, device="cuda")
+    ws = M.chain_workspace()
+    # one phase of one product is an ordinary product
+    M.SpmvChain([[(hs[0], x, y)]], ws).launch()
+    torch.cuda.synchronize()
+    assert torch.equal(y, spmv_case(wl.half_row_matrix(512, 512, 3060), wl.x_vector(512, 7, 6), spmv_kernel=2))
+    # nine phases, seventeen products
+    assert M.SpmvChain([[(hs[0], x, y)]] * 9, ws).launch_raw(0) == -3
+    assert M.SpmvChain([[(hs[0], x, y)] * 3] * 6, ws).launch_raw(0) == -3
+    assert M.SpmvChain([[(hs[0], x, y)] * 9], ws).launch_raw(0) == -1            # more than MACKO_MAX_GROUP in a phase
+    # workspace: too small, misaligned, missing
+    small = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    assert M.SpmvChain([[(hs[0], x, y)]], small).launch_raw(0) == -1
+    big = torch.zeros(M.CHAIN_WORKSPACE_BYTES + 256, dtype=torch.uint8, device="cuda")
+    assert M.SpmvChain([[(hs[0], x, y)]], big[8:]).launch_raw(0) == -1
+    # 8-bit values and unbound handles are refused
+    h8 = M.encode_fp8(wl.fp8_case(512, 512).W).to_device()
+    assert M.SpmvChain([[(h8, x, y)]], ws).launch_raw(0) == -3
+    assert M.SpmvChain([[(M.encode(wl.half_row_matrix(64, 64, 1)), x, y)]], ws).launch_raw(0) == -5
+    empty = M.encode(np.zeros((64, 512), dtype=np.uint16)).to_device()
+    assert M.SpmvChain([[(empty, x, torch.empty(64, dtype=torch.float16, device="cuda"))]], ws).launch_raw(0) == -3
+    torch.cuda.synchronize()
+    assert lib.macko_chain_status(None, None, None) == -1
