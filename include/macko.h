@@ -325,9 +325,26 @@ MACKO_API int macko_spmv_chain(int n_phases, const int* phase_sizes, const macko
                                const void* const* x_dev, void* const* y_dev, void* workspace_dev,
                                int64_t workspace_bytes, void* stream);
 
-/* Whether any chain that used workspace_dev since the last call of this function gave
- * up waiting: MACKO_OK, or MACKO_E_WAIT_EXPIRED with the phase (0-based) whose inputs
- * were not ready in *failed_phase (may be NULL); the results of that chain are
+/* macko_spmv_chain for callers that can neither allocate nor hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and limits without workspace_dev: the 8 KB of scratch
+ * memory (MACKO_CHAIN_WORKSPACE_BYTES) are a static array in the library's device
+ * code, one copy per GPU, held until the process ends, zero when the library is
+ * loaded and left zero by every call.  The call allocates nothing on the host or the
+ * device (the first call on a device looks the array's address up).  More than
+ * MACKO_MAX_CHAIN_PHASES phases or MACKO_MAX_CHAIN_PRODUCTS products do not fit the
+ * scratch layout and the kernel's argument block: MACKO_E_UNSUPPORTED.  Every call on
+ * a GPU shares that GPU's array: calls that overlap in time on one GPU race (the
+ * bounded wait of the chain then ends them with MACKO_E_WAIT_EXPIRED at best, wrong
+ * results at worst); calls in stream order on one stream, or otherwise ordered, are
+ * fine.  macko_chain_status(NULL, ...) reports on this scratch. */
+MACKO_API int macko_spmv_chain_static(int n_phases, const int* phase_sizes, const macko_handle_t* handles,
+                                      const void* const* x_dev, void* const* y_dev, void* stream);
+
+/* Whether any chain that used workspace_dev (NULL: the library's own scratch of
+ * macko_spmv_chain_static on the current device) since the last call of this function
+ * gave up waiting: MACKO_OK, or MACKO_E_WAIT_EXPIRED with the phase (0-based) whose
+ * inputs were not ready in *failed_phase (may be NULL); the results of that chain are
  * incomplete.  Synchronises `stream` and clears the record. */
 MACKO_API int macko_chain_status(void* workspace_dev, void* stream, int* failed_phase);
 MACKO_API int macko_dense_gemv_group(int n, const void* const* W_dev, const int64_t* rows,

@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "macko_encode", "macko_encode_device", "macko_wrap_device", "macko_encode_ex", "macko_encode_device_ex",
     "macko_wrap_device_ex", "macko_storage_by_code_width", "macko_get_report",
     "macko_device_bytes", "macko_bind_device", "macko_host_buffers", "macko_fetch_device",
-    "macko_decode", "macko_encode_fp8", "macko_encode_device_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_spmv_many", "macko_spmv_chain", "macko_chain_status", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
+    "macko_decode", "macko_encode_fp8", "macko_encode_device_fp8", "macko_wrap_device_fp8", "macko_host_values_fp8", "macko_decode_fp8", "macko_check_device", "macko_columns_device", "macko_decode_device", "macko_spmv", "macko_dense_gemv", "macko_spmv_group", "macko_spmv_many", "macko_spmv_chain", "macko_spmv_chain_static", "macko_chain_status", "macko_dense_gemv_group", "macko_spmm", "macko_destroy", "macko_status_string",
     "macko_last_hip_error", "macko_set_tuning", "macko_get_tuning",
 ]
 
@@ -126,6 +126,7 @@ def load_library():
     lib.macko_spmv_group.argtypes = [ci, vpp, vpp, vpp, vp]
     lib.macko_spmv_many.argtypes = [i64, vpp, vpp, vpp, vp]
     lib.macko_spmv_chain.argtypes = [ci, ctypes.POINTER(ci), vpp, vpp, vpp, vp, i64, vp]
+    lib.macko_spmv_chain_static.argtypes = [ci, ctypes.POINTER(ci), vpp, vpp, vpp, vp]
     lib.macko_chain_status.argtypes = [vp, vp, ctypes.POINTER(ci)]
     lib.macko_dense_gemv_group.argtypes = [ci, vpp, i64p, i64p, i64p, vpp, vpp, vp]
     lib.macko_spmm.argtypes = [vp, ci, vp, i64, vp, i64, vp]
@@ -501,7 +502,8 @@ class SpmvChain:
     (matrix, x, y); phase p + 1 runs after phase p inside one launch.  `workspace` is a zeroed uint8
     device tensor of CHAIN_WORKSPACE_BYTES, 256-byte aligned (chain_workspace() makes one)."""
 
-    def __init__(self, phases, workspace):
+    def __init__(self, phases, workspace=None):
+        """workspace None: macko_spmv_chain_static (the library's own scratch, nothing to provide)."""
         flat = [item for ph in phases for item in ph]
         n = len(flat)
         self.n_phases = len(phases)
@@ -511,10 +513,13 @@ class SpmvChain:
         self._h = VP(*[m._h.value for m, _, _ in flat])
         self._x = VP(*[_dev_ptr(x) for _, x, _ in flat])
         self._y = VP(*[_dev_ptr(y) for _, _, y in flat])
-        self._ws = _dev_ptr(workspace)
-        self._ws_bytes = int(workspace.numel() * workspace.element_size())
+        self._ws = _dev_ptr(workspace) if workspace is not None else None
+        self._ws_bytes = int(workspace.numel() * workspace.element_size()) if workspace is not None else 0
 
     def launch_raw(self, stream_ptr: int) -> int:
+        if self._ws is None:
+            return load_library().macko_spmv_chain_static(self.n_phases, self._sizes, self._h, self._x, self._y,
+                                                          stream_ptr)
         return load_library().macko_spmv_chain(self.n_phases, self._sizes, self._h, self._x, self._y, self._ws,
                                                self._ws_bytes, stream_ptr)
 
@@ -535,7 +540,8 @@ def chain_workspace(device="cuda"):
 def chain_status(workspace, stream=None):
     """macko_chain_status: (0, -1) or (MACKO_E_WAIT_EXPIRED, phase whose inputs were not ready)."""
     phase = ctypes.c_int(-1)
-    st = load_library().macko_chain_status(_dev_ptr(workspace), _stream_ptr(stream), ctypes.byref(phase))
+    ws = _dev_ptr(workspace) if workspace is not None else None
+    st = load_library().macko_chain_status(ws, _stream_ptr(stream), ctypes.byref(phase))
     if st not in (0, MACKO_E_WAIT_EXPIRED):
         _check(st, "macko_chain_status")
     return st, phase.value

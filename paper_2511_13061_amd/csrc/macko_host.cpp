@@ -709,9 +709,25 @@ int macko_spmv_chain(int n_phases, const int* phase_sizes, const macko_handle_t*
                                   static_cast<hipStream_t>(stream));
 }
 
+int macko_spmv_chain_static(int n_phases, const int* phase_sizes, const macko_handle_t* handles,
+                            const void* const* x_dev, void* const* y_dev, void* stream) {
+  macko::SpmvProblem p[MACKO_MAX_CHAIN_PRODUCTS];
+  int total = 0;
+  int st = chain_problems(n_phases, phase_sizes, handles, x_dev, y_dev, p, &total);
+  if (st != MACKO_OK) return st;
+  uint32_t* scratch = nullptr;
+  st = macko::chain_static_scratch(&scratch);
+  if (st != MACKO_OK) return st;
+  return macko::launch_spmv_chain(n_phases, phase_sizes, p, scratch, chain_wait_ticks(), static_cast<hipStream_t>(stream));
+}
+
 int macko_chain_status(void* workspace_dev, void* stream, int* failed_phase) {
-  if (!workspace_dev) return MACKO_E_INVALID_ARG;
-  return chain_status_of(static_cast<uint32_t*>(workspace_dev), static_cast<hipStream_t>(stream), failed_phase);
+  uint32_t* scratch = static_cast<uint32_t*>(workspace_dev);
+  if (!scratch) {                                      // the library's own scratch
+    int st = macko::chain_static_scratch(&scratch);
+    if (st != MACKO_OK) return st;
+  }
+  return chain_status_of(scratch, static_cast<hipStream_t>(stream), failed_phase);
 }
 
 int macko_spmm(macko_handle_t h, int batch, const void* X_dev, int64_t ldx, void* Y_dev, int64_t ldy,

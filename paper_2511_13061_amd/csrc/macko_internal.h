@@ -72,6 +72,8 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream);
 int launch_spmv_chain(int n_phases, const int* sizes, const SpmvProblem* problems, uint32_t* scratch,
                       uint32_t wait_ticks, hipStream_t stream);
 constexpr int64_t chain_scratch_bytes() { return 8192; }
+// device address, on the current device, of the library's own chain scratch (a static device array)
+int chain_static_scratch(uint32_t** out);
 constexpr int chain_error_word() { return 25 * 64; }
 // batch products with one matrix: Y[b] = W X[b], vectors ldx / ldy elements apart (p.x, p.y unused)
 int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64_t ldy, int batch,

@@ -14,7 +14,6 @@
 
 #include <climits>
 #include <mutex>
-#include <vector>
 
 namespace macko {
 namespace {
@@ -795,6 +794,11 @@ namespace {
 
 // Workgroups of `kernel` that one compute unit holds at a time, as the runtime reports it
 // (registers, LDS and wavefront slots); asked once per (kernel, shape) and remembered.
+// Scratch memory of macko_spmv_chain_static: one copy per device, part of the loaded code object, zero when
+// the library is loaded and left zero by every chain.  Host code never uses this name as an address (on the
+// host it is a stand-in for the symbol): chain_static_scratch() asks the runtime for the device address once per device.
+static __device__ __align__(256) unsigned char g_chain_scratch[chain_scratch_bytes()];
+
 struct OccupancyKey {
   const void* kernel;
   int block;
@@ -803,14 +807,18 @@ struct OccupancyKey {
   int result;
 };
 std::mutex g_occ_mutex;
-std::vector<OccupancyKey> g_occ;
+constexpr int kOccSlots = 64;           // a fixed table: nothing on the launch path allocates
+OccupancyKey g_occ[kOccSlots];
+int g_occ_n = 0;
 
 int occupancy_of(const void* kernel, int block, int64_t lds) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   std::lock_guard<std::mutex> lock(g_occ_mutex);
-  for (const OccupancyKey& k : g_occ)
+  for (int i = 0; i < g_occ_n; ++i) {
+    const OccupancyKey& k = g_occ[i];
     if (k.kernel == kernel && k.block == block && k.lds == lds && k.dev == dev) return k.result;
+  }
   int n = 0;
   if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, block, (size_t)lds) != hipSuccess) {
     (void)hipGetLastError();
@@ -824,11 +832,28 @@ int occupancy_of(const void* kernel, int block, int64_t lds) {
   } else {
     n = std::min(n, resident_wgs_per_cu(attr.numRegs, block / 64, lds + (int64_t)attr.sharedSizeBytes));
   }
-  g_occ.push_back(OccupancyKey{kernel, block, lds, dev, n});
+  if (g_occ_n < kOccSlots) g_occ[g_occ_n++] = OccupancyKey{kernel, block, lds, dev, n};
   return n;
 }
 
 }  // namespace
+
+int chain_static_scratch(uint32_t** out) {
+  static std::mutex mutex;
+  static uint32_t* address[64] = {};
+  int dev = 0;
+  MACKO_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return MACKO_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mutex);
+  if (!address[dev]) {
+    void* p = nullptr;
+    MACKO_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_chain_scratch)));
+    if (!p) return MACKO_E_HIP;
+    address[dev] = static_cast<uint32_t*>(p);
+  }
+  *out = address[dev];
+  return MACKO_OK;
+}
 
 int launch_spmv_chain(int n_phases, const int* sizes, const SpmvProblem* problems, uint32_t* scratch,
                       uint32_t wait_ticks, hipStream_t stream) {
