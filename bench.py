@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the MACKO sparse matrix-vector product on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--sweep] [--stack]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-sweep] [--no-stack] [--no-spmm]
 
 Workload (default): the Llama2-7B-shaped linear layers at 50 % per-row
 unstructured sparsity (4 x 4096x4096, 2 x 11008x4096, 1 x 4096x11008), fp16
@@ -12,6 +12,13 @@ launches (macko_spmv_group); the seven-separate-launches timing is reported too.
 Steps rotate over several copies of the layer at distinct addresses so that no
 step finds its matrices in the 256 MB last-level cache (the paper invalidates
 the cache before every run, Section 5.1).
+
+Every timed region is repeated in rounds of K steps until at least 30 ms have been
+timed, and the median round is reported (a region of a millisecond right after set-up work
+reads up to 8 % slow: the clocks have not settled).  Outside the headline's timed region the
+default run also times the 36864 x 12288 sparsity sweep at its nine levels, the 32-layer
+Llama2-13B-shaped stack and the small-batch product, and compares y of every timed
+configuration with the CPU oracle's dense product once before timing it.
 
 Prints ONE JSON line.  `value` is algorithmic bytes (format arrays + x + y, the
 compute-intensity accounting of Section 3.1) moved per second over the timed
@@ -85,20 +92,50 @@ class DenseOp:
                         self.y.data_ptr(), stream_ptr)
 
 
+LAST_ROUNDS = 0
+
+
 def time_region(torch, fn, n_warm, n_timed):
-    """fn(i) enqueues iteration i on torch's current stream.  Returns seconds for
-    the n_timed iterations, measured with HIP events on that stream."""
-    for i in range(n_warm):
-        fn(i)
+    """fn(i) enqueues iteration i on torch's current stream.  Returns seconds for n_timed
+    iterations: the median of the rounds time_rounds() runs (HIP events on that stream)."""
+    global LAST_ROUNDS
+    t, LAST_ROUNDS = time_rounds(torch, fn, n_warm, n_timed)
+    return t
+
+
+MIN_TIMED_SECONDS = 0.030
+
+
+def time_rounds(torch, fn, n_warm, n_timed, min_seconds=MIN_TIMED_SECONDS, max_rounds=200):
+    """Rounds of exactly n_timed iterations each, after n_warm untimed ones.  A pilot round sizes the
+    measurement; then enough rounds for min_seconds in total (at least 3) are enqueued back to back
+    with an event between two rounds and no host synchronisation before the last one, so that no
+    round starts on an idle device.  Returns (median seconds per round, rounds)."""
+    it = 0
+
+    def run(k):
+        nonlocal it
+        for _ in range(k):
+            fn(it)
+            it += 1
+
+    run(n_warm)
     torch.cuda.synchronize()
-    start = torch.cuda.Event(enable_timing=True)
-    stop = torch.cuda.Event(enable_timing=True)
-    start.record()
-    for i in range(n_timed):
-        fn(n_warm + i)
-    stop.record()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    run(n_timed)
+    b.record()
     torch.cuda.synchronize()
-    return start.elapsed_time(stop) * 1e-3
+    pilot = max(a.elapsed_time(b) * 1e-3, 1e-7)
+    n = int(min(max_rounds, max(3, -(-min_seconds // pilot))))
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    marks[0].record()
+    for r in range(n):
+        run(n_timed)
+        marks[r + 1].record()
+    torch.cuda.synchronize()
+    rounds = sorted(marks[r].elapsed_time(marks[r + 1]) * 1e-3 for r in range(n))
+    return rounds[n // 2], n
 
 
 def time_multi_stream(torch, launch, n_warm, n_timed, n_streams=3):
@@ -194,13 +231,18 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--sweep", action="store_true", help="also time the 36864x12288 sparsity sweep")
-    ap.add_argument("--stack", action="store_true", help="also time the Llama2-13B-shaped 32-layer stack")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the 36864x12288 sparsity sweep (configs[2])")
+    ap.add_argument("--no-stack", action="store_true", help="skip the Llama2-13B-shaped 32-layer stack (configs[4])")
+    ap.add_argument("--no-spmm", action="store_true", help="skip the small-batch product macko_spmm")
+    ap.add_argument("--no-verify", action="store_true",
+                    help="do not compare y of every timed configuration with the CPU oracle before timing it")
+    ap.add_argument("--sweep", action="store_true", help=argparse.SUPPRESS)     # on by default now
+    ap.add_argument("--stack", action="store_true", help=argparse.SUPPRESS)
+    ap.add_argument("--spmm", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--shapes", action="store_true",
                     help="also time every shape of the paper's Appendix D (see --shapes-sparsity)")
     ap.add_argument("--shapes-sparsity", default="50", metavar="LIST",
                     help="sparsity levels in per cent for --shapes, comma separated (default 50)")
-    ap.add_argument("--spmm", action="store_true", help="also time the small-batch product macko_spmm")
     ap.add_argument("--adversarial", action="store_true",
                     help="also time the two 8192x8192 padding stress matrices (configs[3])")
     ap.add_argument("--widths", action="store_true",
@@ -215,6 +257,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
+    args.sweep, args.stack, args.spmm = not args.no_sweep, not args.no_stack, not args.no_spmm
 
     import torch
     import oracle
@@ -224,6 +267,20 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     M.load_library()
+    verified = []
+
+    def verify(y_dev, case, what):
+        """y of a configuration that is about to be timed, against the oracle's dense product (fp64, by
+        definition), with the acceptance bound |y - y64| <= 1e-2 * sum_j |w_ij x_j| + 1e-3."""
+        if args.no_verify:
+            return
+        torch.cuda.synchronize()
+        y64, s64 = oracle.dense_matvec(case.W, case.x)
+        y = y_dev.float().cpu().numpy().astype(np.float64)
+        bad = ~(np.abs(y - y64) <= 1e-2 * s64 + 1e-3)
+        if bad.any():
+            raise SystemExit(f"bench.py: {what}: {int(bad.sum())} rows of y are outside the tolerance; not timing it")
+        verified.append(what)
     torch.cuda.set_device(0)
     stream_ptr = int(torch.cuda.current_stream().cuda_stream)
     props = torch.cuda.get_device_properties(0)
@@ -255,6 +312,12 @@ def main():
         dense_ops[tag] = DenseOp(M, torch, case, copies=mult * n_layers)
         layer_macko_bytes += mult * sparse_ops[tag].bytes
     layer_dense_bytes = sum(mult * dense_ops[tag].bytes for tag, mult in layer_plan)
+    for case, (tag, mult) in zip(cases, layer_plan):       # first (host-encoded) and last (GPU-encoded) copy, and the baseline
+        for copy in (0, mult * n_layers - 1):
+            sparse_ops[tag].launch(copy, stream_ptr)
+            verify(sparse_ops[tag].y, case, f"{case.name} copy {copy}")
+        dense_ops[tag].launch(0, stream_ptr)
+        verify(dense_ops[tag].y, case, f"{case.name} dense gemv")
     log(f"setup {time.perf_counter() - t0:.1f}s: layer = {layer_macko_bytes / 1e6:.1f} MB MACKO, "
         f"{layer_dense_bytes / 1e6:.1f} MB dense, {n_layers} copies")
 
@@ -320,6 +383,41 @@ def main():
     dense_gbps = layer_dense_bytes / (t_dense / args.steps) / 1e9
     log(f"layer, 4 grouped launches: MACKO {ms_per_step * 1e3:.1f} us/step ({gbps:.0f} GB/s), dense "
         f"{t_dense / args.steps * 1e6:.1f} us/step ({dense_gbps:.0f} GB/s), speedup {t_dense / t_sparse:.3f}")
+    headline_rounds = LAST_ROUNDS
+    # every grouped launch of layer 0 must give what the single launches gave (same arithmetic per row)
+    if not args.no_verify:
+        for g in gs[0]:
+            g.launch_raw(stream_ptr)
+        torch.cuda.synchronize()
+        for g in gs[0]:
+            for m, yv in zip(g._keep[0], g._keep[2]):
+                tag = next(t for t in sparse_ops if m in sparse_ops[t].handles)
+                sparse_ops[tag].launch(0, stream_ptr)
+                torch.cuda.synchronize()
+                if not torch.equal(yv, sparse_ops[tag].y):
+                    raise SystemExit("bench.py: a grouped launch disagrees with the single launch of the same product")
+        verified.append("grouped launches of layer 0 == single launches, bit for bit")
+
+    # the same step as ONE launch that honours the dependences (macko_spmv_chain_static: the four phases
+    # wait for each other inside the kernel); reported beside `value`, which stays on the four launches
+    chain_steps = []
+    for layer in range(n_layers):
+        phases = [[(m, xv, yv) for m, xv, yv in zip(*g._keep)] for g in gs[layer]]
+        chain_steps.append(M.SpmvChain(phases))
+
+    def chain_step(i):
+        st = chain_steps[i % n_layers].launch_raw(stream_ptr)
+        if st != 0:
+            raise RuntimeError(f"chain launch failed with status {st}")
+    t_chain = time_region(torch, chain_step, args.warmup, args.steps)
+    if M.chain_status(None)[0] != 0:
+        raise SystemExit("bench.py: a chain gave up waiting during the timed region")
+    chain = {"launches_per_step": 1, "macko_ms_per_step": round(t_chain / args.steps * 1e3, 5),
+             "macko_GBps": round(layer_macko_bytes / (t_chain / args.steps) / 1e9, 1),
+             "macko_frac_of_hbm_peak": round(layer_macko_bytes / (t_chain / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
+             "speedup_vs_dense_gemv": round(t_dense / t_chain, 3)}
+    log(f"layer, one launch with the dependences honoured inside (macko_spmv_chain_static): {chain}")
+    del chain_steps
     del gs, gd
 
     # the same seven products as seven separate launches (macko_spmv / macko_dense_gemv)
@@ -442,8 +540,11 @@ def main():
     # dominant kernel of the step: the wave-per-row SpMV kernel (all four grouped launches)
     avg_launch_s = t_sparse / (args.steps * launches_per_step)
     avg_launch_bytes = layer_macko_bytes / launches_per_step
+    # HBM traffic per launch is not measured by this run: it comes from two rocprofv3 --pmc runs of this
+    # same command (FETCH_SIZE, WRITE_SIZE), whose summary is kept in the file named beside it
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "spmv_wave_row_kernel_llama2_7b_layer_hbm_traffic.txt")
+    traffic_file = "profiles/spmv_wave_row_kernel_llama2_7b_layer_hbm_traffic.txt"
+    tpath = os.path.join(ROOT, traffic_file)
     if os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -454,6 +555,7 @@ def main():
         "frac": round(avg_launch_bytes / avg_launch_s / 1e9 / HBM_PEAK_GBPS, 4),
         "avg_launch_us": round(avg_launch_s * 1e6, 3), "bytes_per_launch": int(avg_launch_bytes),
         "traffic": traffic,
+        "traffic_from_profile": traffic_file if traffic is not None else None,
     }
 
     extra = {}
@@ -509,9 +611,13 @@ def main():
             # rotate over >= 1 GiB of copies: two copies of the 90 % matrix (278 MB) would half fit the 256 MB cache
             nc = copies_for(int(2.5 * case.rows * case.cols * (1 - s / 100.0)), 1 << 30)
             so = SparseOp(M, torch, case, copies=nc)
+            for copy in (0, nc - 1):
+                so.launch(copy, stream_ptr)
+                verify(so.y, case, f"{case.name} copy {copy}")
             ts = time_single_op(torch, so, stream_ptr, max(SIDE_WARM, nc), SIDE_TIMED)
-            row = {"macko_us": round(ts * 1e6, 1), "macko_GBps": round(so.bytes / ts / 1e9, 1),
-                   "frac_of_peak": round(so.bytes / ts / 1e9 / HBM_PEAK_GBPS, 4),
+            row = {"bytes": int(so.bytes), "us": round(ts * 1e6, 1), "GBps": round(so.bytes / ts / 1e9, 1),
+                   "frac_of_hbm_peak": round(so.bytes / ts / 1e9 / HBM_PEAK_GBPS, 4),
+                   "copies_rotated": nc,
                    "memory_reduction": round(so.report.dense_bytes / so.report.total_bytes, 3),
                    "effd": round(so.report.effd, 4), "padding_entries": so.report.padding_entries}
             # the same launches dealt to three streams in turn (independent products overlap at the seams)
@@ -521,9 +627,11 @@ def main():
                     raise RuntimeError(f"launch failed with status {st}")
             t3 = time_multi_stream(torch, launch3, max(SIDE_WARM, nc), SIDE_TIMED)
             row["three_streams_us"] = round(t3 * 1e6, 1)
-            row["three_streams_frac_of_peak"] = round(so.bytes / t3 / 1e9 / HBM_PEAK_GBPS, 4)
+            row["three_streams_frac_of_hbm_peak"] = round(so.bytes / t3 / 1e9 / HBM_PEAK_GBPS, 4)
             if s == 0:
                 do = DenseOp(M, torch, case, copies=2)
+                do.launch(0, stream_ptr)
+                verify(do.y, case, f"{case.name} dense gemv")
                 dense_t = time_single_op(torch, do, stream_ptr, SIDE_WARM, SIDE_TIMED)
                 row["dense_us"] = round(dense_t * 1e6, 1)
                 row["dense_GBps"] = round(do.bytes / dense_t / 1e9, 1)
@@ -648,9 +756,15 @@ def main():
         plan13 = [("qkvo", 4), ("gate_up", 2), ("down", 1)]
         ops13 = {}
         dops13 = {}
-        for case, (tag, mult) in zip(wl.config5_layer(), plan13):
+        cases13 = list(wl.config5_layer())
+        for case, (tag, mult) in zip(cases13, plan13):
             ops13[tag] = SparseOp(M, torch, case, copies=mult * 32)
             dops13[tag] = DenseOp(M, torch, case, copies=mult * 32)
+            for copy in (0, mult * 32 - 1):
+                ops13[tag].launch(copy, stream_ptr)
+                verify(ops13[tag].y, case, f"{case.name} copy {copy}")
+            dops13[tag].launch(0, stream_ptr)
+            verify(dops13[tag].y, case, f"{case.name} dense gemv")
         def stack_pass(ops):
             def run(_i):
                 for layer in range(32):
@@ -737,6 +851,11 @@ def main():
             st = many.launch_raw(stream_ptr)
             if st != 0:
                 raise RuntimeError(f"macko_spmv_many failed with status {st}")
+        many_pass(0)
+        for case, (tag, mult) in zip(cases13, plan13):
+            idx = [i for i, (t, _) in enumerate(seq) if t == tag]
+            for i in (idx[0], idx[-1]):
+                verify(many._keep[2][i], case, f"macko_spmv_many product {i} ({case.name})")
         tsm = time_region(torch, many_pass, STACK_WARM, STACK_TIMED) / STACK_TIMED
         del many
         ts224 = time_multi_stream(torch, separate_over_streams(ops13), STACK_WARM * 224, STACK_TIMED * 224) * 224
@@ -756,12 +875,17 @@ def main():
                                   "macko_frac_of_hbm_peak": round(sb / ts3 / 1e9 / HBM_PEAK_GBPS, 4),
                                   "speedup_vs_dense": round(td3 / ts3, 3)},
             "one_call_spmv_many_224": {"macko_us": round(tsm * 1e6, 1), "launches": 28,
-                                       "macko_GBps": round(sb / tsm / 1e9, 1),
-                                       "macko_frac_of_hbm_peak": round(sb / tsm / 1e9 / HBM_PEAK_GBPS, 4)},
+                                       "bytes": int(sb), "us": round(tsm * 1e6, 1),
+                                       "GBps": round(sb / tsm / 1e9, 1),
+                                       "frac_of_hbm_peak": round(sb / tsm / 1e9 / HBM_PEAK_GBPS, 4),
+                                       "speedup_vs_dense": round(td3 / tsm, 3),
+                                       "dense_is": "the 128 grouped dense launches over three streams"},
             "three_streams_224_separate": {"macko_us": round(ts224 * 1e6, 1), "dense_us": round(td224 * 1e6, 1),
                                            "macko_frac_of_hbm_peak": round(sb / ts224 / 1e9 / HBM_PEAK_GBPS, 4),
                                            "speedup_vs_dense": round(td224 / ts224, 3)},
             "macko_GB": round(sb / 1e9, 3), "dense_GB": round(db / 1e9, 3),
+            "bytes": int(sb), "us": round(ts * 1e6, 1), "GBps": round(sb / ts / 1e9, 1),
+            "frac_of_hbm_peak": round(sb / ts / 1e9 / HBM_PEAK_GBPS, 4),
             "macko_GBps": round(sb / ts / 1e9, 1), "dense_GBps": round(db / td / 1e9, 1),
             "speedup_vs_dense": round(td / ts, 3),
             "note": "one layer's three distinct matrices, device buffers replicated to 32 layers at distinct addresses",
@@ -796,7 +920,9 @@ def main():
         "speedup_vs_dense_gemv": round(t_dense / t_sparse, 3),
         "memory_reduction_vs_dense": round(layer_dense_bytes / layer_macko_bytes, 3),
         "per_shape": per_shape,
+        "rounds_of_steps_timed": headline_rounds,
         "separate_launches": single,
+        "one_launch_chain_dependences_honoured": chain,
         "one_launch_independent_products": one_launch,
         "two_bit_codes": two_bit,
         **({"eight_bit_values": fp8} if fp8 else {}),
@@ -804,6 +930,7 @@ def main():
         "cpu_baseline": cpu,
     }
     out.update(extra)
+    out["verified_against_oracle_before_timing"] = len(verified)
     print(json.dumps(out), flush=True)
 
 
