@@ -96,8 +96,9 @@ MACKO_API int macko_encode(const uint16_t* dense_host, int64_t rows, int64_t col
  * is bound on return and keeps no host copy.  Synchronises `stream` (the sizes
  * of the outputs are only known after a counting pass).  The result is
  * bit-identical to macko_encode on the same input.  The encoder keeps one scratch
- * buffer per device (about a quarter of the largest dense matrix seen so far, in
- * bytes) until the process ends, and runs one call at a time per process. */
+ * buffer per device between calls as long as it is at most 64 MiB (matrices of up
+ * to about 100 M cells then encode without any allocation but the output's); a
+ * larger one is released before the call returns.  One call at a time per process. */
 MACKO_API int macko_encode_device(const void* dense_dev, int64_t rows, int64_t cols, int64_t ld,
                                   void* stream, macko_handle_t* out, macko_report_t* report);
 
@@ -143,10 +144,12 @@ MACKO_API int macko_device_bytes(macko_handle_t h, int64_t* values_bytes, int64_
                                  int64_t* rowptr_bytes);
 
 /* Attach caller-owned device buffers (each at least as large as reported by
- * macko_device_bytes; values_dev and deltas_dev 16-byte aligned) and enqueue
- * the host-to-device copies of the encoding on `stream`.  The host arrays of
- * the handle must stay alive until those copies complete (they do: the handle
- * owns them).  The buffers must outlive the handle's use. */
+ * macko_device_bytes; values_dev and deltas_dev 16-byte aligned) and copy the
+ * encoding into them: the three host-to-device copies are enqueued on `stream`
+ * and the call then SYNCHRONISES `stream` (the host arrays are ordinary pageable
+ * memory, so the copies are staged by the runtime; on return the device arrays
+ * are complete and the handle is bound).  A one-time set-up call, not part of
+ * the product path.  The buffers must outlive the handle's use. */
 MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas_dev,
                                 void* rowptr_dev, void* stream);
 
@@ -381,7 +384,13 @@ MACKO_API int macko_last_hip_error(void);
  *                       tests of the give-up path; the chain then reports MACKO_E_WAIT_EXPIRED)
  *   "gemv_block", "gemv_rows_per_wg", "gemv_ring" (2, 4 or 8), "gemv_resident",
  *   "gemv_wgs_per_cu"   the same for the dense GEMV
- * Settings are process wide and not thread safe. */
+ * Settings are process wide and not thread safe: macko_set_tuning must not run
+ * at the same time as any call that launches a kernel (macko_spmv, macko_spmv_group,
+ * macko_spmv_many, macko_spmv_chain*, macko_spmm, macko_dense_gemv*) on another host
+ * thread; those calls read the settings without locking.  With all knobs at 0, which
+ * is the state of a process that never calls macko_set_tuning, the launching calls
+ * may run concurrently on any number of host threads (macko_spmv_many and
+ * macko_encode_device serialise themselves). */
 MACKO_API int macko_set_tuning(const char* name, int64_t value);
 MACKO_API int macko_get_tuning(const char* name, int64_t* value);
 

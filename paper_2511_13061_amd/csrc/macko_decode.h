@@ -159,6 +159,12 @@ struct LaneValues<16> {
     v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
     v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
   }
+  __device__ __forceinline__ void clear_first(uint32_t n) {       // clear the values of entries 0 .. n-1 (n <= 7)
+    v.x &= n >= 2 ? 0u : (n == 1 ? 0xFFFF0000u : 0xFFFFFFFFu);
+    v.y &= n >= 4 ? 0u : (n == 3 ? 0xFFFF0000u : 0xFFFFFFFFu);
+    v.z &= n >= 6 ? 0u : (n == 5 ? 0xFFFF0000u : 0xFFFFFFFFu);
+    v.w &= n == 7 ? 0xFFFF0000u : 0xFFFFFFFFu;
+  }
   template <int K>
   __device__ __forceinline__ uint32_t bits() const {              // the stored bit pattern of entry K
     const uint32_t w = (K >> 1) == 0 ? v.x : ((K >> 1) == 1 ? v.y : ((K >> 1) == 2 ? v.z : v.w));
@@ -179,6 +185,11 @@ struct LaneValues<8> {
     const uint32_t lo = nv >= 4 ? 4u : nv, hi = nv >= 8 ? 4u : (nv > 4 ? nv - 4u : 0u);
     v.x &= lo == 4 ? 0xFFFFFFFFu : ((1u << (8u * lo)) - 1u);
     v.y &= hi == 4 ? 0xFFFFFFFFu : ((1u << (8u * hi)) - 1u);
+  }
+  __device__ __forceinline__ void clear_first(uint32_t n) {       // n <= 7
+    const uint32_t lo = n >= 4 ? 4u : n, hi = n > 4 ? n - 4u : 0u;
+    v.x &= lo == 4 ? 0u : ~((1u << (8u * lo)) - 1u);
+    v.y &= ~((1u << (8u * hi)) - 1u);
   }
   template <int K>
   __device__ __forceinline__ uint32_t bits() const {

@@ -96,30 +96,30 @@ __device__ __forceinline__ float wave_sum_to_last_lane(float v) {
   return v;
 }
 
-// The same for N registers at once (N = 2, 4 or 8).  The N independent instructions of one
-// level follow each other, so from N = 4 on the two wait states a DPP read needs after a VALU
-// write of its register are covered by the level's other instructions and only the first
-// level needs an s_nop.
+// The same for N registers at once (N = 2, 4 or 8).  A DPP read needs two wait states after a VALU
+// write of its register, and the hazard is not seen inside inline assembly, so the s_nop has to sit in
+// the same asm statement as the instruction it protects (a separate statement could be scheduled away
+// from it).  First level: every instruction carries its own s_nop (the producer of a[b] is ordinary
+// code).  Later levels, N >= 4: the producer is the previous level's instruction for the same register,
+// and the level's other N - 1 instructions, which volatile asm keeps in order, cover the wait states.
 #define MACKO_DPP_ADD_NOWAIT(op, v, ctrl, rmask) \
   asm volatile(op " %0, %0, %0 " ctrl " row_mask:" rmask " bank_mask:0xf bound_ctrl:0" : "+v"(v))
 template <int N>
 __device__ __forceinline__ void wave_sum_to_last_lane_n(float (&a)[N]) {
   static_assert(N == 2 || N == 4 || N == 8, "batch piece sizes");
-#define MACKO_LEVEL(ctrl, rmask)                                             \
+#define MACKO_LEVEL(ctrl, rmask, first)                                      \
   {                                                                          \
-    if (N < 4) asm volatile("s_nop 1");                                      \
     _Pragma("unroll") for (int b = 0; b < N; ++b) {                          \
-      if (N < 4 && b > 0) asm volatile("s_nop 1");                           \
-      MACKO_DPP_ADD_NOWAIT("v_add_f32_dpp", a[b], ctrl, rmask);              \
+      if (first || N < 4) MACKO_DPP_ADD("v_add_f32_dpp", a[b], ctrl, rmask); \
+      else MACKO_DPP_ADD_NOWAIT("v_add_f32_dpp", a[b], ctrl, rmask);         \
     }                                                                        \
   }
-  asm volatile("s_nop 1");
-  MACKO_LEVEL("row_shr:1", "0xf")
-  MACKO_LEVEL("row_shr:2", "0xf")
-  MACKO_LEVEL("row_shr:4", "0xf")
-  MACKO_LEVEL("row_shr:8", "0xf")
-  MACKO_LEVEL("row_bcast:15", "0xa")
-  MACKO_LEVEL("row_bcast:31", "0xc")
+  MACKO_LEVEL("row_shr:1", "0xf", true)
+  MACKO_LEVEL("row_shr:2", "0xf", false)
+  MACKO_LEVEL("row_shr:4", "0xf", false)
+  MACKO_LEVEL("row_shr:8", "0xf", false)
+  MACKO_LEVEL("row_bcast:15", "0xa", false)
+  MACKO_LEVEL("row_bcast:31", "0xc", false)
 #undef MACKO_LEVEL
 }
 

@@ -457,6 +457,7 @@ struct Workspace {
 };
 std::mutex g_ws_mutex;
 Workspace g_ws[64];
+constexpr size_t kKeepScratchBytes = size_t{64} << 20;
 
 hipError_t workspace_reserve(Workspace& ws, size_t bytes) {
   if (bytes <= ws.cap) return hipSuccess;
@@ -598,6 +599,12 @@ int encode_on_device(const void* dense, int64_t rows, int64_t cols, int64_t ld, 
   }
   MACKO_HIP_TRY(hipGetLastError());
   MACKO_HIP_TRY(hipStreamSynchronize(stream));
+  // a large scratch buffer is not kept: after a 36864 x 12288 matrix it would hold 280 MB until the process ends
+  if (ws.cap > kKeepScratchBytes) {
+    (void)hipFree(ws.p);
+    ws.p = nullptr;
+    ws.cap = 0;
+  }
   *block = out.release();
   *values = vals;
   *deltas = reinterpret_cast<uint8_t*>(dels);

@@ -208,7 +208,16 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
       if (live && cp.step == 0) {
         base2 = 0;
         const int before = (int)(cp.start - cp.a0);
-        if (before > 0) base2 = -(int)w.through(before - 1);
+        if (before > 0) {
+          base2 = -(int)w.through(before - 1);
+          // lane 0 also holds the previous row's last entries: they read the zero guard, and their values
+          // are cleared so that an infinity or a NaN among them cannot become a NaN of this row
+          const uint32_t n = lane == 0 ? (uint32_t)before : 0u;
+          v.x &= n >= 2 ? 0u : (n == 1 ? 0xFFFF0000u : 0xFFFFFFFFu);
+          v.y &= n >= 4 ? 0u : (n == 3 ? 0xFFFF0000u : 0xFFFFFFFFu);
+          v.z &= n >= 6 ? 0u : (n == 5 ? 0xFFFF0000u : 0xFFFFFFFFu);
+          v.w &= n == 7 ? 0xFFFF0000u : 0xFFFFFFFFu;
+        }
       }
       const int lanebase = base2 + (int)(incl - tot);
       const int off[8] = {w.template offset<0>(), w.template offset<1>(), w.template offset<2>(),

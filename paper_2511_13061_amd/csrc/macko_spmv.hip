@@ -129,8 +129,8 @@ spmv_subwave_kernel(const uint4* __restrict__ values, const uint32_t* __restrict
 //    codes and values cleared; they advance 16 bytes each below x[0];
 //  - entries of the previous row in the lane that holds the row start: the base is set
 //    so that the row's first entry lands on its own column; the earlier entries then
-//    decode to positions <= 0, which read the zero guard in front of x and contribute
-//    nothing;
+//    decode to positions <= 0, which read the zero guard in front of x, and their values
+//    are cleared as well (y_i depends on row i alone, also when a neighbour holds inf or NaN);
 //  - after the row end (last step only): codes and values cleared.
 // No load ever leaves [0, alloc_nnz).
 // ---------------------------------------------------------------------------
@@ -302,7 +302,12 @@ __device__ __forceinline__ bool spmv_wave_row_body(const void* __restrict__ valu
           // the row's first entry must land on its own column: the cleared lanes in front of it advance
           // 16 bytes each, and the lane that holds the start counts its entries of the previous row
           base2 = -2 * (before & ~7);
-          if (before & 7) base2 -= (int)w.through((before & 7) - 1, before >> 3);
+          if (before & 7) {
+            base2 -= (int)w.through((before & 7) - 1, before >> 3);
+            // the previous row's entries in that lane read the zero guard; their values are cleared all
+            // the same, so that an infinity or a NaN among them cannot turn 0 * value into a NaN of this row
+            v.clear_first(lane == (before >> 3) ? (uint32_t)(before & 7) : 0u);
+          }
         }
         const int lanebase = base2 + (int)(incl - tot);   // byte offset in x of the lane's chunk start
 #define MACKO_X(k) gather_x(xbase, lanebase + w.template offset<k>())

@@ -1284,3 +1284,79 @@ def test_chain_argument_checks():
     empty = M.encode(np.zeros((64, 512), dtype=np.uint16)).to_device()
     assert M.SpmvChain([[(empty, x, torch.empty(64, dtype=torch.float16, device="cuda"))]], ws).launch_raw(0) == -3
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ a row depends on its own entries only
+
+def _rows_ending_in_nonfinite(rows, cols, density, seed, fp8=False):
+    """Every even row's last non-zero is an infinity or a NaN (a NaN only, for 8-bit values); odd rows are
+    ordinary.  Most even rows end inside an 8-entry chunk that also holds the start of the next row."""
+    W = wl.bernoulli(rows, cols, density, 0.02, 77, seed)
+    if fp8:
+        W = wl.fp8_values_of(W)
+    for r in range(0, rows, 2):
+        nz = np.flatnonzero(W[r])
+        if nz.size:
+            W[r, nz[-1]] = (0x7F if fp8 else (0x7C00, 0xFC00, 0x7E00)[(r // 2) % 3])
+    return W
+
+
+def _check_rows_independent(y_dev, W, x, what, dense=oracle.dense_matvec):
+    y64, s64 = dense(W, x)
+    y = y_dev.float().cpu().numpy().astype(np.float64)
+    odd = np.arange(1, W.shape[0], 2)
+    assert np.isfinite(y64[odd]).all()
+    assert np.isfinite(y[odd]).all(), f"{what}: rows {odd[~np.isfinite(y[odd])][:8]} picked up a neighbour's inf/NaN"
+    assert (np.abs(y[odd] - y64[odd]) <= REL_TOL * s64[odd] + ABS_TOL).all(), what
+    even = np.arange(0, W.shape[0], 2)
+    assert not np.isfinite(y[even]).any(), what
+    assert np.array_equal(np.isnan(y[even]), np.isnan(y64[even])), what
+    inf = even[np.isinf(y64[even])]
+    assert np.array_equal(np.sign(y[inf]), np.sign(y64[inf])), what
+
+
+@pytest.mark.parametrize("b_delta", [1, 2, 4, 8])
+def test_inf_or_nan_at_the_end_of_a_row_stays_in_that_row(b_delta):
+    """Section 4.4 makes y_i a function of row i alone.  The wave-per-row kernels load whole 8-entry chunks,
+    so the lane that holds a row's start also holds the previous row's last entries; those must not reach
+    this row's sum, not even as 0 * inf."""
+    rows, cols = 130, 2048
+    density = {1: 0.9, 2: 0.6, 4: 0.5, 8: 0.2}[b_delta]
+    W = _rows_ending_in_nonfinite(rows, cols, density, b_delta)
+    x = wl.x_vector(cols, 77, b_delta)
+    x[x == 0] = 0x3C00
+    for knobs in ({"spmv_kernel": 2}, {"spmv_kernel": 2, "spmv_step_align": 256},
+                  {"spmv_kernel": 2, "spmv_step_align": 64, "spmv_block": 128, "spmv_rows_per_wg": 7},
+                  {"spmv_kernel": 1, "spmv_lanes": 16}):
+        y = spmv_case(W, x, b_delta=b_delta, **knobs)
+        _check_rows_independent(y, W, x, f"b_delta {b_delta} {knobs}")
+    # the small-batch kernel shares the pattern
+    m = M.encode(W, b_delta).to_device()
+    X = torch.stack([to_dev(x), to_dev(x)])
+    Y = m.spmm(X)
+    torch.cuda.synchronize()
+    for b in range(2):
+        _check_rows_independent(Y[b], W, x, f"spmm b_delta {b_delta} vector {b}")
+    # and the chain (2- and 4-bit codes)
+    if b_delta in (2, 4):
+        y = torch.empty(rows, dtype=torch.float16, device="cuda")
+        M.SpmvChain([[(m, to_dev(x), y)]]).launch()
+        torch.cuda.synchronize()
+        _check_rows_independent(y, W, x, f"chain b_delta {b_delta}")
+
+
+def test_nan_at_the_end_of_a_row_stays_in_that_row_with_8_bit_values():
+    rows, cols = 130, 2048
+    W8 = _rows_ending_in_nonfinite(rows, cols, 0.5, 9, fp8=True)
+    x = wl.x_vector(cols, 77, 9)
+    x[x == 0] = 0x3C00
+    for knobs in ({}, {"spmv_step_align": 256}):
+        for k, v in knobs.items():
+            M.set_tuning(k, v)
+        try:
+            y = M.encode_fp8(W8).to_device().spmv(to_dev(x))
+            torch.cuda.synchronize()
+        finally:
+            for k in knobs:
+                M.set_tuning(k, 0)
+        _check_rows_independent(y, W8, x, f"8-bit values {knobs}", dense=oracle.dense_matvec8)

@@ -220,6 +220,30 @@ def test_launch_planner_covers_every_row_exactly_once(tmp_path):
     assert out.returncode == 0 and out.stdout.startswith("ok"), out.stdout + out.stderr
 
 
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The library's host translation unit (encoders for every code and value width, decoders, storage
+    report, argument checks) linked with stand-ins for the GPU launchers and run under ASan + UBSan on
+    random, ragged, strided, empty and overflowing inputs (tests/host_sanitizer_check.cpp)."""
+    import shutil
+    import subprocess
+    from paper_2511_13061_amd import build as B
+    if not shutil.which("g++") or not os.path.exists("/opt/rocm/lib/libamdhip64.so"):
+        pytest.skip("needs g++ and the HIP runtime library to link against")
+    exe = tmp_path / "host_sanitizer_check"
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+                           "-I", os.path.join(ROOT, "include"), "-I", B.CSRC,
+                           os.path.join(ROOT, "tests", "host_sanitizer_check.cpp"),
+                           os.path.join(ROOT, "tests", "host_sanitizer_stubs.cpp"),
+                           os.path.join(B.CSRC, "macko_host.cpp"), "-o", str(exe),
+                           "-L/opt/rocm/lib", "-lamdhip64", "-lpthread", "-Wl,-rpath,/opt/rocm/lib"],
+                          stderr=subprocess.DEVNULL)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0:verify_asan_link_order=0",
+               UBSAN_OPTIONS="print_stacktrace=1")
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=600, env=env)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stdout[-2000:] + out.stderr[-4000:]
+
+
 # ------------------------------------------------------------------ 8-bit values (host side)
 
 @pytest.mark.parametrize("shape,density", [((64, 512), 0.5), ((33, 1031), 0.07), ((5, 40), 1.0), ((300, 2000), 0.3)])

@@ -309,3 +309,68 @@ def test_check_rejects_planted_mistakes():
         assert oracle.check(mutated(values=v)) == 7
     d2 = good.deltas.copy(); d2[0] |= 0xFF; d2[1] |= 0xFF; d2[2:40] |= 0xFF
     assert oracle.check(mutated(deltas=d2)) in (4, 5)
+
+
+def test_check_names_every_kind_of_planted_mistake():
+    """Each return code of the checker provoked on its own: the mistake is planted in a copy of a good
+    encoding, every other invariant left intact, so exactly that code must come back."""
+    import copy
+    W = wl.bernoulli(8, 200, 0.05, 1.0, 3, 5000)
+    W[5, :] = 0
+    W[5, 3] = 0x3C00
+    W[5, 60] = 0x4000                       # row 5: entries at columns 3, then padding up to 60
+    good = oracle.encode(W)
+    assert oracle.check(good) == 0 and good.alloc_nnz > good.pad_nnz
+
+    def with_(**kw):
+        m = copy.deepcopy(good)
+        for k, v in kw.items():
+            setattr(m, k, v)
+        return m
+
+    # 1: the first row pointer is not 0
+    rp = good.row_ptr.copy(); rp[0] = 1
+    assert oracle.check(with_(row_ptr=rp)) == 1
+    # 2: a row pointer decreases
+    rp = good.row_ptr.copy(); rp[4] = rp[3] - 1 if rp[3] > 0 else rp[3]; rp[3] = max(rp[3], 1); rp[4] = rp[3] - 1
+    assert oracle.check(with_(row_ptr=rp)) == 2
+    # 3: more entries than the arrays hold
+    rp = good.row_ptr.copy(); rp[-1] = good.alloc_nnz + 1
+    assert oracle.check(with_(row_ptr=rp)) == 3
+    # 8: the arrays are longer than pad_nnz rounded up to 32 entries
+    longer = with_(alloc_nnz=good.alloc_nnz + 32,
+                   values=np.concatenate([good.values, np.zeros(32, np.uint16)]),
+                   deltas=np.concatenate([good.deltas, np.zeros(16, np.uint8)]))
+    assert oracle.check(longer) == 8
+    # 4: an entry decodes to a column beyond the last (the last entry of a row pushed out by a larger code)
+    k_last = int(good.row_ptr[1]) - 1
+    d = good.deltas.copy()
+    d[k_last >> 1] |= 0xF0 if (k_last & 1) else 0x0F
+    last_col = oracle.unpack(good)[1][k_last]
+    if last_col + 15 >= good.cols:
+        assert oracle.check(with_(deltas=d)) == 4
+    # 5: a zero value whose code is not 15, and a -0 stored as a padding value
+    k_pad = int(np.flatnonzero(good.values[: good.pad_nnz] == 0)[0])
+    d = good.deltas.copy()
+    d[k_pad >> 1] &= 0xF0 if (k_pad & 1) == 0 else 0x0F
+    assert oracle.check(with_(deltas=d)) in (4, 5)
+    v = good.values.copy(); v[k_pad] = 0x8000
+    assert oracle.check(with_(values=v)) == 5
+    # 6: a row that ends in a padding entry (row 5 cut off after its first padding entry)
+    a5 = int(good.row_ptr[5])
+    assert good.values[a5] != 0 and good.values[a5 + 1] == 0
+    rows6 = oracle.encode(W[:6])
+    cut = copy.deepcopy(rows6)
+    cut.row_ptr = rows6.row_ptr.copy(); cut.row_ptr[6] = a5 + 2          # entries: column 3, one padding entry
+    cut.pad_nnz = a5 + 2
+    cut.alloc_nnz = (cut.pad_nnz + 31) // 32 * 32
+    cut.values = rows6.values[: cut.alloc_nnz].copy(); cut.values[cut.pad_nnz:] = 0
+    cut.deltas = rows6.deltas[: cut.alloc_nnz // 2].copy()
+    for k in range(cut.pad_nnz, cut.alloc_nnz):
+        cut.deltas[k >> 1] &= 0x0F if (k & 1) else 0xF0
+    assert oracle.check(cut) == 6
+    # 7: something in the tail
+    v = good.values.copy(); v[-1] = 1
+    assert oracle.check(with_(values=v)) == 7
+    d = good.deltas.copy(); d[-1] |= 0x10
+    assert oracle.check(with_(deltas=d)) == 7
