@@ -723,6 +723,22 @@ def main():
                 td = time_region(torch, g, SIDE_WARM, SIDE_TIMED) / SIDE_TIMED
                 row[f"batch{B}"] = {"macko_us": round(ts * 1e6, 2), "dense_library_gemm_us": round(td * 1e6, 2),
                                     "format_GBps": round(so.bytes / ts / 1e9)}
+            # the same with 8-bit (E4M3) values: 1.5 bytes per stored entry, the same batch kernel
+            W8 = wl.fp8_values_of(case.W)
+            W8d = torch.from_numpy(W8).cuda()
+            h8 = [M.encode_fp8(W8).to_device()] + [M.encode_device_fp8(W8d) for _ in range(7)]
+            del W8d
+            for B in (1, 8):
+                X = torch.randn(B, case.cols, device="cuda", dtype=torch.float16)
+                Y = torch.empty(B, case.rows, device="cuda", dtype=torch.float16)
+
+                def f8(i):
+                    st = lib.macko_spmm(h8[i % 8]._h, B, X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), stream_ptr)
+                    if st != 0:
+                        raise RuntimeError(f"macko_spmm failed with status {st}")
+                t8 = time_region(torch, f8, SIDE_WARM, SIDE_TIMED) / SIDE_TIMED
+                row[f"batch{B}"]["macko_8_bit_values_us"] = round(t8 * 1e6, 2)
+            del h8
             table[f"{case.rows}x{case.cols}"] = row
             log(f"  spmm {case.rows}x{case.cols}: {row}")
             del Wd

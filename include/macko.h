@@ -173,8 +173,8 @@ MACKO_API int macko_bind_device(macko_handle_t h, void* values_dev, void* deltas
  * accumulation; the wave-per-row kernel serves every row length; x must fit
  * LDS, about 78 K columns, otherwise MACKO_E_UNSUPPORTED), macko_columns_device,
  * macko_check_device, macko_decode_device (the dense matrix as bytes),
- * macko_spmm (the vectors of the batch run as independent matrix-vector
- * products, up to 8 per launch: the matrix is read once per vector).
+ * macko_spmm (the same batch kernel as for 16-bit values: the matrix is read and
+ * decoded once per piece of up to 8 vectors).
  * macko_decode and macko_host_buffers' `values` are MACKO_E_UNSUPPORTED for
  * such a handle (macko_decode_fp8, macko_host_values_fp8 instead). */
 MACKO_API int macko_encode_fp8(const uint8_t* dense_host, int64_t rows, int64_t cols, int64_t ld,
@@ -256,7 +256,13 @@ MACKO_API int macko_spmv(macko_handle_t h, const void* x_dev, void* y_dev, void*
 MACKO_API int macko_dense_gemv(const void* W_dev, int64_t rows, int64_t cols, int64_t ld,
                                const void* x_dev, void* y_dev, void* stream);
 
-/* Small-batch product with one matrix (decode shared by the batch):
+/* Small-batch product with one matrix (the matrix is streamed and decoded once per piece of
+ * up to 8 vectors, for every code width and both value widths; rows shorter than 384
+ * stored entries on average, and batches whose interleaved vectors do not fit LDS, run
+ * as independent matrix-vector products instead).  From batch 8 on the kernel is bound
+ * by vector arithmetic, not by memory: on the Llama2-7B shapes at 50 % sparsity the
+ * vendor library's dense fp16 GEMM on the decoded matrix (macko_decode_device) is as
+ * fast at batch 8 and faster beyond; this call is meant for batch 2 to 8.
  * Y[b][r] = sum_k values[k] * X[b][column(k)] for b < batch, 0 <= batch <= MACKO_MAX_BATCH.
  * X_dev: fp16, batch vectors of `cols` elements, vector b at X_dev + b*ldx
  * (ldx >= cols); Y_dev: fp16, vector b at Y_dev + b*ldy (ldy >= rows).  fp32

@@ -1,7 +1,7 @@
 // Small-batch product Y = W X^T for the MACKO format on gfx950: the same
 // wavefront-per-row streaming kernel as the matrix-vector product (Section 4.4
 // of the paper), with the decode done once per stored entry and reused for
-// BT = 2, 4 or 8 activation vectors.  The paper leaves matrix-matrix products
+// BT = 2, 4 or 8 activation vectors, for every code width and for 16- and 8-bit values.  The paper leaves matrix-matrix products
 // with small batch dimensions as future work (Section 7); this is the natural
 // extension: the streamed bytes per entry stay 2.5, the arithmetic per byte
 // grows with the batch.
@@ -125,9 +125,10 @@ struct XStageBatch {
   }
 };
 
-template <int BT, int BD>
+// VB: bits per stored value (16: fp16; 8: E4M3, 4-bit codes only).
+template <int BT, int BD, int VB>
 __global__ void __launch_bounds__(1024)
-spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
+spmm_wave_row_kernel(const void* __restrict__ values, const uint32_t* __restrict__ deltas,
                      const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ X, int64_t ldx,
                      uint16_t* __restrict__ Y, int64_t ldy, int batch, int rows, int cols, int q, int r_extra,
                      int inv_nwaves) {
@@ -151,7 +152,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
   uint32_t chunk = 0;
   RowCursor ld, cp;
   LaneCodes<BD> wq[RING];
-  uint4 vq[RING];
+  LaneValues<VB> vq[RING];
   const int r = min(blk + lane, rows - 1);             // unconditional loads, clamped to the last row
   const uint32_t rp_lo = row_ptr[r];
   const uint32_t rp_hi = row_ptr[r + 1];
@@ -172,7 +173,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
       chunk = 0;
     }
     wq[j].load(deltas, chunk);
-    vq[j] = load_stream(values + chunk);
+    vq[j].load(values, chunk);
   };
   ld.i = 0;
   seek_nonempty(ld, nb, rp_lo, rp_hi);
@@ -189,7 +190,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
 #pragma unroll
     for (int j = 0; j < RING; ++j) {
       LaneCodes<BD> w = wq[j];
-      uint4 v = vq[j];
+      LaneValues<VB> v = vq[j];
       const bool live = cp.i < nb;
       if (!live) base2 = 0;
       const uint32_t end_eff = live ? cp.end : 0u;
@@ -197,10 +198,7 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
       if (!live || cp.step == cp.nsteps - 1) {
         const uint32_t nv = e0 < end_eff ? end_eff - e0 : 0u;
         w.keep_if(nv != 0);
-        v.x &= nv >= 2 ? 0xFFFFFFFFu : (nv == 1 ? 0xFFFFu : 0u);
-        v.y &= nv >= 4 ? 0xFFFFFFFFu : (nv == 3 ? 0xFFFFu : 0u);
-        v.z &= nv >= 6 ? 0xFFFFFFFFu : (nv == 5 ? 0xFFFFu : 0u);
-        v.w &= nv >= 8 ? 0xFFFFFFFFu : (nv == 7 ? 0xFFFFu : 0u);
+        v.keep_first(nv);
       }
       w.decode();
       const uint32_t tot = w.total();
@@ -212,28 +210,23 @@ spmm_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restric
           base2 = -(int)w.through(before - 1);
           // lane 0 also holds the previous row's last entries: they read the zero guard, and their values
           // are cleared so that an infinity or a NaN among them cannot become a NaN of this row
-          const uint32_t n = lane == 0 ? (uint32_t)before : 0u;
-          v.x &= n >= 2 ? 0u : (n == 1 ? 0xFFFF0000u : 0xFFFFFFFFu);
-          v.y &= n >= 4 ? 0u : (n == 3 ? 0xFFFF0000u : 0xFFFFFFFFu);
-          v.z &= n >= 6 ? 0u : (n == 5 ? 0xFFFF0000u : 0xFFFFFFFFu);
-          v.w &= n == 7 ? 0xFFFF0000u : 0xFFFFFFFFu;
+          v.clear_first(lane == 0 ? (uint32_t)before : 0u);
         }
       }
       const int lanebase = base2 + (int)(incl - tot);
-      const int off[8] = {w.template offset<0>(), w.template offset<1>(), w.template offset<2>(),
-                          w.template offset<3>(), w.template offset<4>(), w.template offset<5>(),
-                          w.template offset<6>(), w.template offset<7>()};
-      const uint32_t vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const int q = lanebase + off[k];                                    // byte offset for one vector
-        const XV xraw = *reinterpret_cast<const XV*>(xbase + q * BT);
-        float xf[BT];
-        unpack_x<BT>(xraw, xf);
-        const float wk = f16_bits_to_f32((uint16_t)(vv[k >> 1] >> (16 * (k & 1))));
-#pragma unroll
-        for (int b = 0; b < BT; ++b) acc[b] = fmaf(wk, xf[b], acc[b]);
+      // entry K: one gather address fetches the BT activations of its column
+#define MACKO_ENTRY(K)                                                                       \
+      {                                                                                      \
+        const int q = lanebase + w.template offset<K>();     /* byte offset for one vector */ \
+        const XV xraw = *reinterpret_cast<const XV*>(xbase + q * BT);                          \
+        float xf[BT];                                                                        \
+        unpack_x<BT>(xraw, xf);                                                              \
+        const float wk = v.template get<K>();                                                \
+        _Pragma("unroll") for (int b = 0; b < BT; ++b) acc[b] = fmaf(wk, xf[b], acc[b]);     \
       }
+      MACKO_ENTRY(0) MACKO_ENTRY(1) MACKO_ENTRY(2) MACKO_ENTRY(3)
+      MACKO_ENTRY(4) MACKO_ENTRY(5) MACKO_ENTRY(6) MACKO_ENTRY(7)
+#undef MACKO_ENTRY
       issue(j);
       base2 += (int)__builtin_amdgcn_readlane((int)incl, 63);
       if (live && ++cp.step == cp.nsteps) {
@@ -262,7 +255,7 @@ __global__ void __launch_bounds__(256) zero_Y_kernel(uint16_t* __restrict__ Y, i
     for (int b = 0; b < batch; ++b) Y[(int64_t)b * ldy + i] = 0;
 }
 
-template <int BT, int BD>
+template <int BT, int BD, int VB = 16>
 int launch_bt_bd(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y, int64_t ldy, int batch,
                  hipStream_t stream) {
   const int cus = device_cu_count();
@@ -286,14 +279,14 @@ int launch_bt_bd(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t*
   const int block = plan.block;
   const int64_t grid = plan.total_wgs;
   if (grid >= (int64_t{1} << 31)) return MACKO_E_UNSUPPORTED;
-  auto kfn = spmm_wave_row_kernel<BT, BD>;
+  auto kfn = spmm_wave_row_kernel<BT, BD, VB>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e);
   }
   hipLaunchKernelGGL(kfn, dim3((unsigned)grid), dim3(block), (size_t)lds, stream,
-                     reinterpret_cast<const uint4*>(p.values), reinterpret_cast<const uint32_t*>(p.deltas),
+                     static_cast<const void*>(p.values), reinterpret_cast<const uint32_t*>(p.deltas),
                      p.row_ptr, X, ldx, Y, ldy, batch, (int)p.rows, (int)p.cols, plan.m[0].q, plan.m[0].r,
                      65536 / (block / 64) + 1);
   hipError_t e = hipGetLastError();
@@ -303,7 +296,9 @@ int launch_bt_bd(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t*
 template <int BT>
 int launch_bt(const SpmvProblem& p, const uint16_t* X, int64_t ldx, uint16_t* Y, int64_t ldy, int batch,
               hipStream_t stream) {
+  if (p.b_val == 8) return p.b_delta == 4 ? launch_bt_bd<BT, 4, 8>(p, X, ldx, Y, ldy, batch, stream) : MACKO_E_UNSUPPORTED;
   switch (p.b_delta) {
+    case 1: return launch_bt_bd<BT, 1>(p, X, ldx, Y, ldy, batch, stream);
     case 2: return launch_bt_bd<BT, 2>(p, X, ldx, Y, ldy, batch, stream);
     case 4: return launch_bt_bd<BT, 4>(p, X, ldx, Y, ldy, batch, stream);
     case 8: return launch_bt_bd<BT, 8>(p, X, ldx, Y, ldy, batch, stream);
@@ -330,9 +325,7 @@ int launch_spmm(const SpmvProblem& p, const void* X, int64_t ldx, void* Y, int64
   }
   const int64_t one = lds_bytes_for(p.cols, p.b_delta);
   const int64_t limit = 160 * 1024 - 64;
-  // 1-bit codes and 8-bit values have no batch kernel: their vectors go through the matrix-vector
-  // path, up to 8 of them per launch as independent products
-  const bool long_rows = p.pad_nnz / p.rows >= 384 && p.b_delta != 1 && p.b_val == 16;
+  const bool long_rows = p.pad_nnz / p.rows >= 384;
   int done = 0;
   while (done < batch) {
     const int left = batch - done;

@@ -495,6 +495,39 @@ def test_spmm_shapes_strides_and_fallbacks():
         assert (Ybuf[:, :3] == 7).all() and (Ybuf[:, 3 + W.shape[0]:] == 7).all()
 
 
+@pytest.mark.parametrize("batch", [2, 4, 8, 13])
+@pytest.mark.parametrize("kind", ["b1", "b2", "b4", "b8", "fp8"])
+def test_spmm_batch_kernel_every_code_width_and_8_bit_values(kind, batch):
+    """The batch kernel proper (rows long enough for it): one decode per stored entry, `batch` products.
+    Row lengths straddle steps, rows start inside chunks, some rows are empty."""
+    b_delta = {"b1": 1, "b2": 2, "b4": 4, "b8": 8, "fp8": 4}[kind]
+    density = {"b1": 0.9, "b2": 0.6, "b4": 0.5, "b8": 0.25, "fp8": 0.5}[kind]
+    rows, cols = 150, 4100
+    W = wl.bernoulli(rows, cols, density, 0.02, 54, b_delta)
+    W[7] = 0
+    W[40:43] = 0
+    X = np.stack([wl.x_vector(cols, 54, 10 * batch + b) for b in range(batch)])
+    if kind == "fp8":
+        W8 = wl.fp8_values_of(W)
+        m = M.encode_fp8(W8).to_device()
+        assert m.report.pad_nnz // rows >= 384
+        Y = m.spmm(to_dev(X))
+        torch.cuda.synchronize()
+        for b in range(batch):
+            check_y8(Y[b], W8, X[b], f"fp8 batch {batch} vector {b}")
+        y0 = m.spmv(to_dev(X[0]))
+    else:
+        m = M.encode(W, b_delta).to_device()
+        assert m.report.pad_nnz // rows >= 384
+        Y = m.spmm(to_dev(X))
+        torch.cuda.synchronize()
+        check_Y(Y, W, X, f"{kind} batch {batch}")
+        y0 = m.spmv(to_dev(X[0]))
+    torch.cuda.synchronize()
+    assert (Y[:, 7] == 0).all() and (Y[:, 40:43] == 0).all()
+    assert torch.allclose(Y[0].float(), y0.float(), atol=2e-3, rtol=2e-2)
+
+
 def test_spmm_llama_shape_full_size():
     case = next(iter(wl.config2()))
     X = np.stack([wl.x_vector(case.cols, 53, b) for b in range(8)])
@@ -986,7 +1019,7 @@ def test_fp8_groups_unsupported_calls_and_full_size():
     yw = w.spmv(to_dev(a.x))
     torch.cuda.synchronize()
     assert torch.equal(yw, ys[0])
-    # a batch of vectors: no batch kernel for 8-bit values, the vectors run as independent products
+    # a batch of vectors: the batch kernel, a piece of 8 and a piece of 4 (3 used)
     xs = [wl.x_vector(2048, 88, i) for i in range(11)]
     X = torch.stack([to_dev(v) for v in xs])
     Y = ma.spmm(X)
