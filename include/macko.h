@@ -340,7 +340,9 @@ MACKO_API int macko_spmv_chain(int n_phases, const int* phase_sizes, const macko
  * memory (MACKO_CHAIN_WORKSPACE_BYTES) are a static array in the library's device
  * code, one copy per GPU, held until the process ends, zero when the library is
  * loaded and left zero by every call.  The call allocates nothing on the host or the
- * device (the first call on a device looks the array's address up).  More than
+ * device (the first call on a device looks the array's address up and asks the
+ * runtime for the kernel's resource use: make that call outside a graph capture;
+ * later calls can be captured, the launch records one kernel node and no memset).  More than
  * MACKO_MAX_CHAIN_PHASES phases or MACKO_MAX_CHAIN_PRODUCTS products do not fit the
  * scratch layout and the kernel's argument block: MACKO_E_UNSUPPORTED.  Every call on
  * a GPU shares that GPU's array: calls that overlap in time on one GPU race (the

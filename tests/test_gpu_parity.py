@@ -1393,3 +1393,42 @@ def test_nan_at_the_end_of_a_row_stays_in_that_row_with_8_bit_values():
             for k in knobs:
                 M.set_tuning(k, 0)
         _check_rows_independent(y, W8, x, f"8-bit values {knobs}", dense=oracle.dense_matvec8)
+
+
+def test_chain_under_graph_capture_replays_like_eager():
+    """macko_spmv_chain_static allocates nothing and records no memset, so it can be captured; every replay,
+    with eager work and synchronisations between the replays, must reproduce the eager results, also when the
+    chain's inputs changed in between (the graph holds pointers, not values)."""
+    shapes = [(2048, 1536), (1536, 2048), (1024, 1536), (512, 1024)]
+    hs = _chain_handles(shapes, 8)
+    xa, xb = to_dev(wl.x_vector(1536, 7, 80)), to_dev(wl.x_vector(1536, 7, 81))
+    x0 = torch.empty_like(xa)
+    ys = [torch.empty(h.rows, dtype=torch.float16, device="cuda") for h in hs]
+    chain = M.SpmvChain([[(hs[i], x0 if i == 0 else ys[i - 1], ys[i])] for i in range(4)])     # static scratch
+
+    def eager(x):
+        x0.copy_(x)
+        chain.launch(stream=torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert M.chain_status(None) == (0, -1)
+        return [y.clone() for y in ys]
+
+    main = torch.cuda.Stream()
+    with torch.cuda.stream(main):
+        want_a, want_b = eager(xa), eager(xb)        # also the first calls on this device: look-ups happen here
+        assert not torch.equal(want_a[3], want_b[3])
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=main):
+            chain.launch(stream=torch.cuda.current_stream())
+        for rep, (x, want) in enumerate([(xa, want_a), (xb, want_b), (xb, want_b), (xa, want_a)]):
+            x0.copy_(x)
+            for y in ys:
+                y.fill_(float("nan"))
+            main.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for i, (y, w) in enumerate(zip(ys, want)):
+                assert torch.equal(y, w), f"replay {rep} phase {i}"
+            # eager work between replays: an ordinary product and another eager chain
+            assert torch.equal(eager(x)[3], want[3])
+        assert M.chain_status(None) == (0, -1)
