@@ -232,10 +232,16 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
   Plan plan;
   bool planned = false;
   const bool small = total_steps <= (int64_t)cus * kResidentStepsPerCu;
-  if (t.gemv_rows_per_wg == 0 && (t.gemv_resident == 2 || (t.gemv_resident == 0 && small)))
+  // Rows that are a multiple of 4096 bytes apart (4096 or 8192 columns): as for the sparse product, many
+  // 256-thread workgroups instead of workgroups that all start at a row start together (measured on the
+  // 7B-shaped layer: {gate,up} 31.3 -> 29.6 us, {q,k,v} 18.7 -> 18.0, {o} 7.3 -> 7.1).  The baseline gets
+  // every launch-side improvement the sparse kernel gets.
+  bool in_step = t.gemv_resident == 0 && t.gemv_block == 0;
+  for (int i = 0; i < nwr; ++i) in_step = in_step && wr[i]->ld % 2048 == 0 && wr[i]->cols <= 8192;
+  if (!in_step && t.gemv_rows_per_wg == 0 && (t.gemv_resident == 2 || (t.gemv_resident == 0 && small)))
     planned = plan_resident(plan, nwr, in, cus, (int)t.gemv_block, (int)t.gemv_wgs_per_cu);
   if (!planned) {
-    const int block = t.gemv_block ? (int)t.gemv_block : 512;
+    const int block = t.gemv_block ? (int)t.gemv_block : (in_step ? 256 : 512);
     const int nwaves = block / 64;
     int64_t rpw[kMaxGroup];
     for (int i = 0; i < nwr; ++i) {
