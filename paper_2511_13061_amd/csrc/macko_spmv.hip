@@ -712,14 +712,15 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, in
   const int64_t resident_steps = t.spmv_resident_steps ? t.spmv_resident_steps : kResidentStepsPerCu;
   const bool small = total_steps <= (int64_t)cus * resident_steps;
   const bool wide = max_lds - kAlignFrontPad >= kWideLdsBytes;
-  // Rows whose length is a multiple of 2048 stored entries (4096 or 8192 columns at exactly 50 % per row,
+  // Rows of a multiple of 2048 stored entries on average (4096 or 8192 columns at 50 %,
   // 4096 columns dense): every row start is a multiple of 4096 bytes into the values array, and a
   // resident round, which starts all its wavefronts at row starts at the same moment, runs them through
   // the memory system in step.  Such matrices go to many 256-thread workgroups instead, which the
   // dispatcher hands out as compute units become free.  Measured against the resident round (interleaved
   // runs): {gate,up} of a 7B-shaped layer 23.1 -> 21.1 us, {q,k,v} 13.5 -> 13.1, 14336 x 4096 15.7 -> 14.7,
   // 32000 x 4096 30.0 -> 28.3 (dense: 59.6 -> 50.7 against the 512-thread workgroups it used to get),
-  // 8192 x 8192 17.8 -> 16.4, 28672 x 8192 49.2 -> 47.8.  Other row lengths on the same shapes (30, 70, 80,
+  // 8192 x 8192 17.8 -> 16.4, 28672 x 8192 49.2 -> 47.8; iid masks with that average gain as much as exact
+  // per-row counts (14336 x 4096: 15.7 -> 14.9 and 15.9 -> 14.8).  Other row lengths on the same shapes (30, 70, 80,
   // 90 % sparsity, 3584 columns) are 1-4 % faster in the resident round and stay there; x of more than
   // 8192 columns costs too much to stage once per small workgroup.
   bool in_step = t.spmv_resident == 0 && t.spmv_block == 0;
