@@ -217,8 +217,15 @@ def cpu_baseline(oracle, cases, min_cpu_seconds=10.0):
         passes += 1
         if (time.perf_counter() - t0) * threads >= min_cpu_seconds or passes >= 50:
             break
+    # the oracle's dense product by definition (fp64, O(rows x cols)): the parity reference, timed once per matrix
+    dense_us = {}
+    for c in cases:
+        td = time.perf_counter()
+        oracle.dense_matvec(c.W, c.x)
+        dense_us[f"{c.rows}x{c.cols}"] = round((time.perf_counter() - td) * 1e6, 1)
     return {
         "value": nbytes / best / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "dense_matvec_by_definition_us": dense_us,
         "sample": f"one pass over the {len(encs)} distinct layer matrices "
                   f"({nbytes / 1e6:.1f} MB of format+x+y), best of {passes} passes, OpenMP over rows",
         "us_per_pass": best * 1e6,
