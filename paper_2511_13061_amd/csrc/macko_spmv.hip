@@ -268,7 +268,7 @@ __device__ __forceinline__ bool spmv_wave_row_body(const void* __restrict__ valu
   prime_ring();
   if (gated) {
     if (!gate.wait()) return false;
-      stage_x_begin<kXAux>(xst, x, cols);
+    stage_x_begin<kXAux>(xst, x, cols);
   }
   stage_x_finish<SIMPLE, kXAux>(lds, xst, x, cols, spmv_front_pad(BD), back_pad_for(BD));  // ends with a barrier
 
@@ -332,7 +332,7 @@ __device__ __forceinline__ bool spmv_wave_row_body(const void* __restrict__ valu
         }
       }
     }
-      if (lane < nb) {
+    if (lane < nb) {
       if (Gate::kActive)     // written through to memory: workgroups under other L2 caches read it next
         __hip_atomic_store(y + blk + lane, f32_to_f16_bits(yv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       else
@@ -502,8 +502,8 @@ spmv_chain_kernel(const ChainArgs a, uint32_t* __restrict__ scratch, const uint3
     // Every wavefront's y has reached memory (the stores are write-through and have been
     // acknowledged) and nobody reads this phase's x in LDS any more; then the workgroup reports.
     __builtin_amdgcn_s_waitcnt(0);
-      __syncthreads();
-      if (p + 1 < a.n_phases && threadIdx.x == 0)
+    __syncthreads();
+    if (p + 1 < a.n_phases && threadIdx.x == 0)
       __hip_atomic_fetch_add(scratch + kChainArrive + (wg & 7) * kChainSlot, 1u, __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_AGENT);
   }
@@ -816,8 +816,6 @@ int launch_wave_row_group(int nwr, const SpmvProblem* const* wr, int b_delta, in
 
 namespace {
 
-// Workgroups of `kernel` that one compute unit holds at a time, as the runtime reports it
-// (registers, LDS and wavefront slots); asked once per (kernel, shape) and remembered.
 // Scratch memory of macko_spmv_chain_static: one copy per device, part of the loaded code object, zero when
 // the library is loaded and left zero by every chain.  Host code never uses this name as an address (on the
 // host it is a stand-in for the symbol): chain_static_scratch() asks the runtime for the device address once per device.
@@ -835,6 +833,9 @@ constexpr int kOccSlots = 64;           // a fixed table: nothing on the launch 
 OccupancyKey g_occ[kOccSlots];
 int g_occ_n = 0;
 
+// Workgroups of `kernel` that one compute unit holds at a time: the smaller of what the runtime
+// reports (registers, LDS and wavefront slots) and the pessimistic count from the kernel's own
+// register use; asked once per (kernel, shape, device) and remembered.
 int occupancy_of(const void* kernel, int block, int64_t lds) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
