@@ -6,6 +6,7 @@ and a closed-form padding count); it must agree with the oracle byte for byte.
 import ctypes
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -53,6 +54,17 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(M.library_path())
     for name in declared:
         assert hasattr(lib, name), name
+
+
+def test_header_is_plain_c_and_cpp(tmp_path):
+    """The boundary is a C ABI: include/macko.h must compile as C99 and as C++11, pedantic, without warnings."""
+    c = tmp_path / "use.c"
+    c.write_text('#include "macko.h"\nint main(void) { macko_report_t r; macko_handle_t h = 0; (void)r; (void)h; return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(c)])
+    cpp = tmp_path / "use.cpp"
+    cpp.write_text(c.read_text())
+    subprocess.check_call(["g++", "-std=c++11", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)])
 
 
 CASES = [
