@@ -191,15 +191,17 @@ struct XStage {
 // AUX: cache policy bits of the loads (0: ordinary; kCoherentLoad: coherent over the whole device,
 // for an x that workgroups on other parts of the chip have just written, see spmv_chain_kernel).
 constexpr int kCoherentLoad = 16;     // sc1: the load does not hit lines that another L2 may have made stale
+// nt: threads of the workgroup (a kernel that has it in an argument register passes that: reading
+// blockDim is a scalar load from the dispatch's argument block, one memory round trip at start-up)
 template <int AUX = 0>
-__device__ __forceinline__ void stage_x_begin(XStage& st, const uint16_t* __restrict__ x, int cols) {
+__device__ __forceinline__ void stage_x_begin(XStage& st, const uint16_t* __restrict__ x, int cols, int nt) {
   const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15) == 0;
   const int bytes = aligned ? (cols >> 3) * 16 : 0;   // whole 16-byte chunks of x
   const __amdgpu_buffer_rsrc_t rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x), 0, bytes, 0x00020000);
 #pragma unroll
   for (int k = 0; k < kXStageRegs; ++k) {
-    const int i = (int)threadIdx.x + k * (int)blockDim.x;
+    const int i = (int)threadIdx.x + k * nt;
     const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, i * 16, 0, AUX);
     st.r[k] = make_uint4(v[0], v[1], v[2], v[3]);
   }
@@ -226,9 +228,8 @@ __device__ __forceinline__ uint4 load_x_chunk(const uint4* x) {
 template <bool SIMPLE, int AUX = 0>
 __device__ __forceinline__ void stage_x_finish(unsigned char* lds, const XStage& st,
                                                const uint16_t* __restrict__ x, int cols,
-                                               int front_pad = kFrontPad, int back_pad = kBackPad) {
+                                               int front_pad, int back_pad, int nt) {
   const int tid = threadIdx.x;
-  const int nt = blockDim.x;
   const uint4 zero = make_uint4(0, 0, 0, 0);
   uint4* lds16 = reinterpret_cast<uint4*>(lds);
   const int chunks = cols >> 3;
@@ -264,8 +265,8 @@ __host__ __device__ inline bool stage_x_is_simple(const void* x, int64_t cols, i
 
 __device__ __forceinline__ void stage_x_to_lds(unsigned char* lds, const uint16_t* __restrict__ x, int cols) {
   XStage st;
-  stage_x_begin(st, x, cols);
-  stage_x_finish<false>(lds, st, x, cols);
+  stage_x_begin(st, x, cols, (int)blockDim.x);
+  stage_x_finish<false>(lds, st, x, cols, kFrontPad, kBackPad, (int)blockDim.x);
 }
 
 }  // namespace macko

@@ -49,12 +49,15 @@ template <int RING>
 __device__ __forceinline__ void gemv_wave_row_body(const uint4* __restrict__ W, const uint16_t* __restrict__ x,
                                                    uint16_t* __restrict__ y, const int64_t ld8, const int cols,
                                                    const int q, const int r, const int wg,
-                                                   const int inv_nwaves) {
+                                                   const uint32_t waves) {
   extern __shared__ __align__(16) unsigned char lds[];
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
   const int row_begin = wg * q + min(wg, r);
   const int wg_rows = q + (wg < r ? 1 : 0);
-  const int nwaves = blockDim.x >> 6;
+  // waves: floor(2^20 / wavefronts per workgroup) + 1 in bits 0..20, wavefronts per workgroup above (an
+  // argument that arrives in a register; blockDim would be a load from the dispatch's argument block)
+  const int inv_nwaves = (int)(waves & 0x1FFFFFu), nwaves = (int)(waves >> 21);
+  const int nthreads = 64 * nwaves;
   const uint4* xs = reinterpret_cast<const uint4*>(lds + kFrontPad);
 
   const int lane = threadIdx.x & 63;
@@ -97,9 +100,9 @@ __device__ __forceinline__ void gemv_wave_row_body(const uint4* __restrict__ W, 
   // x is requested first, then the first weight loads go out, and only then is
   // x written to LDS: the stream is already in flight behind the barrier
   XStage xst;
-  stage_x_begin(xst, x, cols);
+  stage_x_begin(xst, x, cols, nthreads);
   open_block();
-  stage_x_finish<false>(lds, xst, x, cols);                   // ends with a barrier
+  stage_x_finish<false>(lds, xst, x, cols, kFrontPad, kBackPad, nthreads);   // ends with a barrier
 
   while (true) {
     float yv = 0.0f;                                   // lane i: result of row blk + i
@@ -154,7 +157,7 @@ __device__ __forceinline__ void gemv_wave_row_body(const uint4* __restrict__ W, 
 template <int RING>
 __global__ void __launch_bounds__(1024)
 gemv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4, const int wb5, const int wb6,
-                     const int wb7, const int inv_nwaves, const GemvGroupArgs g) {
+                     const int wb7, const uint32_t waves, const GemvGroupArgs g) {
   static_assert(kMaxGroup == 8, "one scalar argument per group slot");
   int mi = 0, wg0 = 0;
   const int wbs[kMaxGroup] = {0, wb1, wb2, wb3, wb4, wb5, wb6, wb7};
@@ -165,15 +168,15 @@ gemv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4,
     wg0 = in ? wbs[i] : wg0;
   }
   gemv_wave_row_body<RING>(g.m[mi].W, g.m[mi].x, g.m[mi].y, g.m[mi].ld8, g.m[mi].cols, g.m[mi].q, g.m[mi].r,
-                           (int)blockIdx.x - wg0, inv_nwaves);
+                           (int)blockIdx.x - wg0, waves);
 }
 
 // One matrix: all scalar arguments, no argument load before the first weights are requested.
 template <int RING>
 __global__ void __launch_bounds__(1024)
 gemv_wave_row_kernel(const uint4* __restrict__ W, const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
-                     const int64_t ld8, const int cols, const int q, const int r, const int inv_nwaves) {
-  gemv_wave_row_body<RING>(W, x, y, ld8, cols, q, r, (int)blockIdx.x, inv_nwaves);
+                     const int64_t ld8, const int cols, const int q, const int r, const uint32_t waves) {
+  gemv_wave_row_body<RING>(W, x, y, ld8, cols, q, r, (int)blockIdx.x, waves);
 }
 
 // Any shape / alignment: one wavefront per row, 2-byte loads, x from global.
@@ -281,29 +284,29 @@ int launch_gemv_group(int n, const GemvProblem* problems, hipStream_t stream) {
     wg_begin += plan.m[i].nwg;
   }
   const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
+  const uint32_t waves = (uint32_t)head.inv_nwaves | ((uint32_t)(plan.block / 64) << 21);
   auto lds_limit = [&](const void* fn) -> int {
     if (max_lds <= 64 * 1024) return MACKO_OK;
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_lds);
     return e == hipSuccess ? MACKO_OK : hip_fail(e);
   };
   if (nwr == 1) {
-    using K1 = void (*)(const uint4*, const uint16_t*, uint16_t*, int64_t, int, int, int, int);
+    using K1 = void (*)(const uint4*, const uint16_t*, uint16_t*, int64_t, int, int, int, uint32_t);
     K1 kfn = t.gemv_ring == 2 ? (K1)gemv_wave_row_kernel<2>
              : t.gemv_ring == 8 ? (K1)gemv_wave_row_kernel<8> : (K1)gemv_wave_row_kernel<4>;
     int st = lds_limit(reinterpret_cast<const void*>(kfn));
     if (st != MACKO_OK) return st;
     const GemvMat& m = args.m[0];
-    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.W, m.x, m.y, m.ld8, m.cols, m.q, m.r,
-                       head.inv_nwaves);
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.W, m.x, m.y, m.ld8, m.cols, m.q, m.r, waves);
   } else {
-    using KG = void (*)(int, int, int, int, int, int, int, int, GemvGroupArgs);
+    using KG = void (*)(int, int, int, int, int, int, int, uint32_t, GemvGroupArgs);
     KG kfn = t.gemv_ring == 2 ? (KG)gemv_wave_row_kernel<2>
              : t.gemv_ring == 8 ? (KG)gemv_wave_row_kernel<8> : (KG)gemv_wave_row_kernel<4>;
     int st = lds_limit(reinterpret_cast<const void*>(kfn));
     if (st != MACKO_OK) return st;
     hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
                        head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
-                       head.inv_nwaves, args);
+                       waves, args);
   }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);

@@ -156,10 +156,10 @@ struct SpmvGroupArgs {
   SpmvMat m[kMaxGroup];
 };
 // Workgroups [wg_begin[i], wg_begin[i+1]) work on matrix i (wg_begin[0] = 0); unused
-// slots hold INT_MAX.  These and inv_nwaves are separate scalar kernel arguments in
-// front of the descriptors: scalar arguments at the start of the argument list can be
-// handed to a wavefront in registers when it starts, which saves one dependent load
-// on the way to the first row pointer.
+// slots hold INT_MAX.  These and inv_nwaves (packed with the wavefront count) are separate
+// scalar kernel arguments in front of the descriptors: scalar arguments at the start of the
+// argument list can be handed to a wavefront in registers when it starts, which saves one
+// dependent load on the way to the first row pointer.
 struct SpmvGroupHeader {
   int wg_begin[kMaxGroup];
   int inv_nwaves;          // floor(65536 / wavefronts per workgroup) + 1
@@ -204,7 +204,8 @@ __device__ __forceinline__ bool spmv_wave_row_body(const void* __restrict__ valu
                                                    const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
                                                    const int rows, const int cols, const int q, const int r,
                                                    const int wg, const int nwaves, const int inv_nwaves,
-                                                   const uint32_t amask, const Gate gate = Gate()) {
+                                                   const uint32_t amask, const int block_threads,
+                                                   const Gate gate = Gate()) {
   extern __shared__ __align__(16) unsigned char lds[];
   // this workgroup's rows, then this wavefront's share of them (both dealt out evenly)
   const int row_begin = wg * q + min(wg, r);
@@ -263,14 +264,17 @@ __device__ __forceinline__ bool spmv_wave_row_body(const void* __restrict__ valu
   constexpr int kXAux = Gate::kActive ? kCoherentLoad : 0;
   XStage xst;
   fetch_row_ptrs();
+  // the row pointers are requested before anything that may have to wait for a kernel argument
+  // which did not arrive in a register (the scheduler would otherwise put that wait first)
+  __builtin_amdgcn_sched_barrier(0);
   const bool gated = Gate::kActive && gate.needed();
-  if (!gated) stage_x_begin<0>(xst, x, cols);
+  if (!gated) stage_x_begin<0>(xst, x, cols, block_threads);
   prime_ring();
   if (gated) {
     if (!gate.wait()) return false;
-    stage_x_begin<kXAux>(xst, x, cols);
+    stage_x_begin<kXAux>(xst, x, cols, block_threads);
   }
-  stage_x_finish<SIMPLE, kXAux>(lds, xst, x, cols, spmv_front_pad(BD), back_pad_for(BD));  // ends with a barrier
+  stage_x_finish<SIMPLE, kXAux>(lds, xst, x, cols, spmv_front_pad(BD), back_pad_for(BD), block_threads);  // ends with a barrier
 
   {
     float yv = 0.0f;                                   // lane i: result of row blk + i
@@ -346,7 +350,10 @@ __device__ __forceinline__ bool spmv_wave_row_body(const void* __restrict__ valu
 template <int RING, bool SIMPLE, int BD, int VB = 16>
 __global__ void __launch_bounds__(1024)
 spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4, const int wb5, const int wb6,
-                     const int wb7, const int inv_nwaves, const SpmvGroupArgs g) {
+                     const int wb7, const uint32_t waves, const SpmvGroupArgs g) {
+  // waves: floor(65536 / wavefronts per workgroup) + 1 in bits 0..16, wavefronts per workgroup above
+  // (blockDim would have to be loaded from the dispatch's argument block)
+  const int inv_nwaves = (int)(waves & 0x1FFFFu), nwaves = (int)(waves >> 17);
   static_assert(kMaxGroup == 8, "one scalar argument per group slot");
   int mi = 0, wg0 = 0;
   const int wbs[kMaxGroup] = {0, wb1, wb2, wb3, wb4, wb5, wb6, wb7};
@@ -358,30 +365,37 @@ spmv_wave_row_kernel(const int wb1, const int wb2, const int wb3, const int wb4,
   }
   spmv_wave_row_body<RING, SIMPLE, BD, VB>(g.m[mi].values, g.m[mi].deltas, g.m[mi].row_ptr, g.m[mi].x, g.m[mi].y,
                                        g.m[mi].rows, g.m[mi].cols, g.m[mi].q, g.m[mi].r, (int)blockIdx.x - wg0,
-                                       (int)(blockDim.x >> 6), inv_nwaves, (uint32_t)g.m[mi].amask);
+                                       nwaves, inv_nwaves, (uint32_t)g.m[mi].amask, 64 * nwaves);
 }
 
-// One matrix: everything the workgroup needs is a scalar argument (16 registers),
-// so a starting wavefront goes straight to its row pointers without any argument load.
+// One matrix: the 14 leading arguments, which a starting wavefront finds in registers, hold
+// everything it needs to request its row pointers and x at once, without any argument load before:
+//   shape    floor(65536 / wavefronts per workgroup) + 1 in bits 0..16, wavefronts per workgroup in
+//            bits 17..21, alignment of a row's first step minus 1 in bits 22..30
+__host__ __device__ constexpr uint32_t pack_shape(int inv_nwaves, int nwaves, int amask) {
+  return (uint32_t)inv_nwaves | ((uint32_t)nwaves << 17) | ((uint32_t)amask << 22);
+}
 template <int RING, bool SIMPLE, int BD>
 __global__ void __launch_bounds__(1024)
-spmv_wave_row_kernel(const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
-                     const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
-                     uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
-                     const int inv_nwaves, const int amask) {
-  spmv_wave_row_body<RING, SIMPLE, BD>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
-                                       (int)(blockDim.x >> 6), inv_nwaves, (uint32_t)amask);
+spmv_wave_row_kernel(const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x, const int rows,
+                     const int q, const int r, const uint32_t shape, const int cols,
+                     const uint4* __restrict__ values, const uint32_t* __restrict__ deltas,
+                     uint16_t* __restrict__ y) {
+  const int nwaves = (int)((shape >> 17) & 31u);
+  spmv_wave_row_body<RING, SIMPLE, BD>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x, nwaves,
+                                       (int)(shape & 0x1FFFFu), shape >> 22, 64 * nwaves);
 }
 
 // One matrix with 8-bit values (4-bit codes): 8 bytes of values and 4 bytes of codes per lane and step.
 template <bool SIMPLE>
 __global__ void __launch_bounds__(1024)
-spmv_wave_row_fp8_kernel(const uint2* __restrict__ values, const uint32_t* __restrict__ deltas,
-                         const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x,
-                         uint16_t* __restrict__ y, const int rows, const int cols, const int q, const int r,
-                         const int inv_nwaves, const int amask) {
-  spmv_wave_row_body<2, SIMPLE, 4, 8>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x,
-                                      (int)(blockDim.x >> 6), inv_nwaves, (uint32_t)amask);
+spmv_wave_row_fp8_kernel(const uint32_t* __restrict__ row_ptr, const uint16_t* __restrict__ x, const int rows,
+                         const int q, const int r, const uint32_t shape, const int cols,
+                         const uint2* __restrict__ values, const uint32_t* __restrict__ deltas,
+                         uint16_t* __restrict__ y) {
+  const int nwaves = (int)((shape >> 17) & 31u);
+  spmv_wave_row_body<2, SIMPLE, 4, 8>(values, deltas, row_ptr, x, y, rows, cols, q, r, (int)blockIdx.x, nwaves,
+                                      (int)(shape & 0x1FFFFu), shape >> 22, 64 * nwaves);
 }
 
 // ---------------------------------------------------------------------------
@@ -494,7 +508,7 @@ spmv_chain_kernel(const ChainArgs a, uint32_t* __restrict__ scratch, const uint3
       const SpmvMat& m = a.m[mi];
       ok = spmv_wave_row_body<2, SIMPLE, BD, 16, ChainGate>(m.values, m.deltas, m.row_ptr, m.x, m.y, m.rows, m.cols,
                                                            m.q, m.r, wg - a.wg_begin[mi], a.nwaves[p],
-                                                           a.inv_nwaves[p], (uint32_t)m.amask, gate);
+                                                           a.inv_nwaves[p], (uint32_t)m.amask, (int)blockDim.x, gate);
     } else {
       ok = gate.wait();
     }
@@ -638,16 +652,17 @@ int launch_wave_row_fp8(const SpmvGroupArgs& args, const SpmvGroupHeader& head, 
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     const SpmvMat& m = args.m[0];
-    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, static_cast<const uint2*>(m.values), m.deltas,
-                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves, m.amask);
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.row_ptr, m.x, m.rows, m.q, m.r,
+                       pack_shape(head.inv_nwaves, plan.block / 64, m.amask), m.cols,
+                       static_cast<const uint2*>(m.values), m.deltas, m.y);
   } else {
-    using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
+    using KG = void (*)(int, int, int, int, int, int, int, uint32_t, SpmvGroupArgs);
     KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, 4, 8> : (KG)spmv_wave_row_kernel<2, false, 4, 8>;
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
                        head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
-                       head.inv_nwaves, args);
+                       (uint32_t)head.inv_nwaves | ((uint32_t)(plan.block / 64) << 17), args);
   }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
@@ -658,8 +673,8 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
                        int64_t max_lds, bool simple, int ring, hipStream_t stream) {
   const dim3 grid((unsigned)plan.total_wgs), blockdim(plan.block);
   if (nwr == 1) {
-    using K1 = void (*)(const uint4*, const uint32_t*, const uint32_t*, const uint16_t*, uint16_t*, int, int, int,
-                        int, int, int);
+    using K1 = void (*)(const uint32_t*, const uint16_t*, int, int, int, uint32_t, int, const uint4*, const uint32_t*,
+                        uint16_t*);
     K1 kfn = simple ? (K1)spmv_wave_row_kernel<2, true, BD> : (K1)spmv_wave_row_kernel<2, false, BD>;
     if (BD == 4 && ring == 4)
       kfn = simple ? (K1)spmv_wave_row_kernel<4, true, 4> : (K1)spmv_wave_row_kernel<4, false, 4>;
@@ -668,10 +683,11 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
     int st = set_lds_limit(kfn, max_lds);
     if (st != MACKO_OK) return st;
     const SpmvMat& m = args.m[0];
-    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, static_cast<const uint4*>(m.values), m.deltas,
-                       m.row_ptr, m.x, m.y, m.rows, m.cols, m.q, m.r, head.inv_nwaves, m.amask);
+    hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, m.row_ptr, m.x, m.rows, m.q, m.r,
+                       pack_shape(head.inv_nwaves, plan.block / 64, m.amask), m.cols,
+                       static_cast<const uint4*>(m.values), m.deltas, m.y);
   } else {
-    using KG = void (*)(int, int, int, int, int, int, int, int, SpmvGroupArgs);
+    using KG = void (*)(int, int, int, int, int, int, int, uint32_t, SpmvGroupArgs);
     KG kfn = simple ? (KG)spmv_wave_row_kernel<2, true, BD> : (KG)spmv_wave_row_kernel<2, false, BD>;
     if (BD == 4 && ring == 4)
       kfn = simple ? (KG)spmv_wave_row_kernel<4, true, 4> : (KG)spmv_wave_row_kernel<4, false, 4>;
@@ -681,7 +697,7 @@ int launch_wave_row_bd(const SpmvGroupArgs& args, const SpmvGroupHeader& head, i
     if (st != MACKO_OK) return st;
     hipLaunchKernelGGL(kfn, grid, blockdim, (size_t)max_lds, stream, head.wg_begin[1], head.wg_begin[2],
                        head.wg_begin[3], head.wg_begin[4], head.wg_begin[5], head.wg_begin[6], head.wg_begin[7],
-                       head.inv_nwaves, args);
+                       (uint32_t)head.inv_nwaves | ((uint32_t)(plan.block / 64) << 17), args);
   }
   hipError_t e = hipGetLastError();
   return e == hipSuccess ? MACKO_OK : hip_fail(e);
