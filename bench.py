@@ -13,9 +13,10 @@ Steps rotate over several copies of the layer at distinct addresses so that no
 step finds its matrices in the 256 MB last-level cache (the paper invalidates
 the cache before every run, Section 5.1).
 
-Every timed region is repeated in rounds of K steps until at least 30 ms have been
-timed, and the median round is reported (a region of a millisecond right after set-up work
-reads up to 8 % slow: the clocks have not settled).  Outside the headline's timed region the
+Every timed region is repeated in rounds of K steps (of the smallest multiple of K steps that
+lasts 5 ms, when K steps are shorter) until at least 30 ms have been timed, and the median
+round is reported per K steps (a region of a millisecond right after set-up work reads up to
+8 % slow: the clocks have not settled; the event between two rounds costs 1 % of a 1 ms round).  Outside the headline's timed region the
 default run also times the 36864 x 12288 sparsity sweep at its nine levels, the 32-layer
 Llama2-13B-shaped stack and the small-batch product, and compares y of every timed
 configuration with the CPU oracle's dense product once before timing it.
@@ -93,24 +94,29 @@ class DenseOp:
 
 
 LAST_ROUNDS = 0
+LAST_ROUND_STEPS = 0
 
 
 def time_region(torch, fn, n_warm, n_timed):
     """fn(i) enqueues iteration i on torch's current stream.  Returns seconds for n_timed
     iterations: the median of the rounds time_rounds() runs (HIP events on that stream)."""
-    global LAST_ROUNDS
-    t, LAST_ROUNDS = time_rounds(torch, fn, n_warm, n_timed)
+    global LAST_ROUNDS, LAST_ROUND_STEPS
+    t, LAST_ROUNDS, LAST_ROUND_STEPS = time_rounds(torch, fn, n_warm, n_timed)
     return t
 
 
 MIN_TIMED_SECONDS = 0.030
+MIN_ROUND_SECONDS = 0.005
 
 
 def time_rounds(torch, fn, n_warm, n_timed, min_seconds=MIN_TIMED_SECONDS, max_rounds=200):
-    """Rounds of exactly n_timed iterations each, after n_warm untimed ones.  A pilot round sizes the
-    measurement; then enough rounds for min_seconds in total (at least 3) are enqueued back to back
-    with an event between two rounds and no host synchronisation before the last one, so that no
-    round starts on an idle device.  Returns (median seconds per round, rounds)."""
+    """Rounds of a whole multiple of n_timed iterations each, after n_warm untimed ones.  A pilot round
+    of n_timed iterations sizes the measurement: a round is the smallest multiple of n_timed iterations
+    that lasts MIN_ROUND_SECONDS (the event between two rounds costs the launch stream a few
+    microseconds, 1 % of a round of 1 ms), and enough rounds for min_seconds in total (at least 3) are
+    enqueued back to back with an event between two rounds and no host synchronisation before the last
+    one, so that no round starts on an idle device.  Returns (median seconds per n_timed iterations,
+    rounds, iterations per round)."""
     it = 0
 
     def run(k):
@@ -127,15 +133,16 @@ def time_rounds(torch, fn, n_warm, n_timed, min_seconds=MIN_TIMED_SECONDS, max_r
     b.record()
     torch.cuda.synchronize()
     pilot = max(a.elapsed_time(b) * 1e-3, 1e-7)
-    n = int(min(max_rounds, max(3, -(-min_seconds // pilot))))
+    mult = int(max(1, -(-MIN_ROUND_SECONDS // pilot)))
+    n = int(min(max_rounds, max(3, -(-min_seconds // (pilot * mult)))))
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
     marks[0].record()
     for r in range(n):
-        run(n_timed)
+        run(n_timed * mult)
         marks[r + 1].record()
     torch.cuda.synchronize()
     rounds = sorted(marks[r].elapsed_time(marks[r + 1]) * 1e-3 for r in range(n))
-    return rounds[n // 2], n
+    return rounds[n // 2] / mult, n, n_timed * mult
 
 
 def time_multi_stream(torch, launch, n_warm, n_timed, n_streams=3):
@@ -390,7 +397,7 @@ def main():
     dense_gbps = layer_dense_bytes / (t_dense / args.steps) / 1e9
     log(f"layer, 4 grouped launches: MACKO {ms_per_step * 1e3:.1f} us/step ({gbps:.0f} GB/s), dense "
         f"{t_dense / args.steps * 1e6:.1f} us/step ({dense_gbps:.0f} GB/s), speedup {t_dense / t_sparse:.3f}")
-    headline_rounds = LAST_ROUNDS
+    headline_rounds, headline_round_steps = LAST_ROUNDS, LAST_ROUND_STEPS
     # every grouped launch of layer 0 must give what the single launches gave (same arithmetic per row)
     if not args.no_verify:
         for g in gs[0]:
@@ -944,6 +951,7 @@ def main():
         "memory_reduction_vs_dense": round(layer_dense_bytes / layer_macko_bytes, 3),
         "per_shape": per_shape,
         "rounds_of_steps_timed": headline_rounds,
+        "steps_per_timed_round": headline_round_steps,
         "separate_launches": single,
         "one_launch_chain_dependences_honoured": chain,
         "one_launch_independent_products": one_launch,
